@@ -1,0 +1,118 @@
+"""Seeded synthetic inputs shared by the GPU tests, the benchmark and the CPU checker.
+
+Holds no arithmetic of the method: only random draws, the named workload
+shapes and bf16 rounding of the drawn values.  Every tensor is drawn from its
+own numpy PCG64 stream keyed by (seed, tensor name), so the same bytes reach
+both sides regardless of the order tensors are requested in.
+
+Distributions: weight matrices and biases N(0, 0.02); norm gains 1 + N(0, 0.02)
+(a gain centred on zero would null the layer); norm biases N(0, 0.02);
+activations and upstream gradients N(0, 1).
+"""
+from __future__ import annotations
+
+import zlib
+from dataclasses import dataclass
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Workload:
+    """Shape of one TP rank's layer and the microbatch that flows through it."""
+    name: str
+    hidden: int
+    heads_local: int
+    head_dim: int
+    ffn_local: int
+    seq: int
+    tp: int
+    dtype: str = "bf16"      # "bf16" | "f32"
+    norm: str = "ln"         # "ln" | "rms"
+    act: str = "gelu"        # "gelu" | "swiglu"
+    causal: bool = True
+    rope: bool = False
+    has_bias: bool = True
+    eps: float = 1e-5
+    rope_base: float = 10000.0
+
+    @property
+    def attn_local(self) -> int:
+        return self.heads_local * self.head_dim
+
+
+WORKLOADS = {
+    # tiny GPT layer, unsharded, fp32
+    "tiny": Workload("tiny", 256, 4, 64, 1024, 128, 1, dtype="f32"),
+    # GPT-7B-style layer, TP=8 shard, seq 6144 (headline)
+    "gpt7b_tp8": Workload("gpt7b_tp8", 4096, 4, 128, 2048, 6144, 8),
+    # Llama-13B-style layer, TP=4 shard
+    "llama13b_tp4": Workload("llama13b_tp4", 5120, 10, 128, 3456, 4096, 4, norm="rms",
+                             act="swiglu", rope=True, has_bias=False),
+    # layer of the 4-layer pipeline stage
+    "gpt7b_tp8_s4096": Workload("gpt7b_tp8_s4096", 4096, 4, 128, 2048, 4096, 8),
+    # ViT encoder layer, unsharded, bidirectional
+    "vit": Workload("vit", 1024, 16, 64, 4096, 1024, 1, causal=False),
+}
+
+
+def _rng(seed: int, name: str) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64([seed, zlib.crc32(name.encode())]))
+
+
+def normal(seed: int, name: str, shape, std: float = 1.0, mean: float = 0.0) -> np.ndarray:
+    """fp32 N(mean, std) tensor from the stream keyed by (seed, name)."""
+    return (_rng(seed, name).standard_normal(shape, dtype=np.float32) * np.float32(std)
+            + np.float32(mean))
+
+
+def to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to bf16 (nearest even); returns the uint16 bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounded = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def quantize(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Value the device will hold for x in storage type `dtype`, as fp32."""
+    if dtype == "bf16":
+        return bf16_bits_to_f32(to_bf16_bits(x))
+    return np.ascontiguousarray(x, dtype=np.float32)
+
+
+WEIGHT_KEYS = ("norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+               "norm2_g", "norm2_b", "w_fc1", "b_fc1", "w_up", "w_fc2", "b_fc2")
+
+
+def weight_shapes(wl: Workload) -> dict:
+    h, a, f = wl.hidden, wl.attn_local, wl.ffn_local
+    shp = {"norm1_g": (h,), "norm2_g": (h,), "w_qkv": (h, 3 * a), "w_o": (a, h),
+           "w_fc1": (h, f), "w_fc2": (f, h)}
+    if wl.norm == "ln":
+        shp.update(norm1_b=(h,), norm2_b=(h,))
+    if wl.act == "swiglu":
+        shp["w_up"] = (h, f)
+    if wl.has_bias:
+        shp.update(b_qkv=(3 * a,), b_o=(h,), b_fc1=(f,), b_fc2=(h,))
+    return shp
+
+
+def make_weights(wl: Workload, seed: int, layer: int = 0) -> dict:
+    """fp32 arrays holding the values as stored on the device (bf16-rounded if bf16).
+
+    Layout: linear weights are [in_features, out_features], row-major; w_qkv
+    columns are ordered [Q heads | K heads | V heads], head-major."""
+    out = {}
+    for key, shape in weight_shapes(wl).items():
+        mean = 1.0 if key in ("norm1_g", "norm2_g") else 0.0
+        out[key] = quantize(normal(seed, f"L{layer}.{key}", shape, 0.02, mean), wl.dtype)
+    return out
+
+
+def make_activation(wl: Workload, seed: int, name: str) -> np.ndarray:
+    """[seq, hidden] N(0,1) tensor (layer input or upstream gradient), as stored."""
+    return quantize(normal(seed, name, (wl.seq, wl.hidden)), wl.dtype)
