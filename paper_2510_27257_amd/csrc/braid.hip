@@ -1,0 +1,246 @@
+// The braided execution block (Section 3, Fig. 3; Section 4.1 pattern (2); Appendix A):
+// the F units of microbatch i are issued on one HIP stream, the B units of an earlier
+// microbatch j on a second, the W units on a third, in the caller's interleaved order.
+// Only true data dependences are turned into events: a W waits for its B; a step waits
+// for the previous step on all three streams.  The four TP All-Reduce points per layer
+// are reported to the caller's boundary callback (no collective runs here).
+#include <stdlib.h>
+#include <string.h>
+#include "common.h"
+
+namespace {
+
+struct Cursor { int layer, unit; bool set; };
+
+inline bool is_first_of_chain(const stp_stage *st, int layer) {
+  return layer == 0 || (st->chain_break && st->chain_break[layer]);
+}
+inline bool is_last_of_chain(const stp_stage *st, int layer) {
+  return layer == st->n_layers - 1 || (st->chain_break && st->chain_break[layer + 1]);
+}
+
+// next unit in forward order after (layer, unit); false if the chain ends there
+inline bool fwd_successor(const stp_stage *st, int layer, int unit, int *nl, int *nu) {
+  if (unit < STP_MLP) { *nl = layer; *nu = unit + 1; return true; }
+  if (is_last_of_chain(st, layer)) return false;
+  *nl = layer + 1; *nu = STP_PRE_ATTN;
+  return true;
+}
+inline bool bwd_successor(const stp_stage *st, int layer, int unit, int *nl, int *nu) {
+  if (unit > STP_PRE_ATTN) { *nl = layer; *nu = unit - 1; return true; }
+  if (is_first_of_chain(st, layer)) return false;
+  *nl = layer - 1; *nu = STP_MLP;
+  return true;
+}
+
+int validate(const stp_stage *st, const stp_op *ops, size_t n, const uint8_t *b_done, size_t *bad) {
+  size_t dummy;
+  if (!bad) bad = &dummy;
+  *bad = 0;
+  if (!st || (!ops && n)) return STP_EINVAL;
+  if (st->n_layers < 1 || st->n_microbatches < 1 || !st->desc) return STP_EINVAL;
+  const int L = st->n_layers, MB = st->n_microbatches;
+  int f_mb = -1;
+  Cursor fcur = {0, 0, false};
+  Cursor *bcur = (Cursor *)calloc(MB, sizeof(Cursor));
+  uint8_t *b_here = (uint8_t *)calloc((size_t)L * MB * 2, 1);
+  if (!bcur || !b_here) { free(bcur); free(b_here); return STP_ENOSPACE; }
+  int rc = STP_OK;
+  // first pass: the forward microbatch
+  for (size_t i = 0; i < n; i++)
+    if (ops[i].kind == STP_OP_F) { f_mb = ops[i].microbatch; break; }
+  for (size_t i = 0; i < n && rc == STP_OK; i++) {
+    const stp_op &o = ops[i];
+    *bad = i;
+    if (o.kind < STP_OP_F || o.kind > STP_OP_BW || o.unit < STP_PRE_ATTN || o.unit > STP_MLP || o.layer < 0 ||
+        o.layer >= L || o.microbatch < 0 || o.microbatch >= MB) { rc = STP_EINVAL; break; }
+    if (o.kind == STP_OP_F) {
+      if (o.microbatch != f_mb) { rc = STP_ESEQ; break; }         // one forward microbatch per block
+      if (fcur.set) {
+        int nl, nu;
+        bool more = fwd_successor(st, fcur.layer, fcur.unit, &nl, &nu);
+        bool chain_start = o.unit == STP_PRE_ATTN && is_first_of_chain(st, o.layer) && !more;
+        if (!((more && nl == o.layer && nu == o.unit) || chain_start)) { rc = STP_ESEQ; break; }
+      }
+      fcur = {o.layer, o.unit, true};
+      continue;
+    }
+    // backward-side op: its microbatch must precede the forward one (Appendix A)
+    if (f_mb >= 0 && o.microbatch >= f_mb) { rc = STP_ESEQ; break; }
+    const bool has_w = o.unit == STP_ATTN || o.unit == STP_MLP;
+    const size_t slot = ((size_t)o.layer * MB + o.microbatch) * 2 + (o.unit == STP_MLP ? 1 : 0);
+    if (o.kind == STP_OP_W) {
+      if (!has_w) { rc = STP_ESEQ; break; }
+      if (!b_here[slot] && !(b_done && b_done[slot])) { rc = STP_ESEQ; break; }  // W needs its B first
+      continue;
+    }
+    Cursor &c = bcur[o.microbatch];
+    if (c.set) {
+      int nl, nu;
+      bool more = bwd_successor(st, c.layer, c.unit, &nl, &nu);
+      bool chain_start = o.unit == STP_MLP && is_last_of_chain(st, o.layer) && !more;
+      if (!((more && nl == o.layer && nu == o.unit) || chain_start)) { rc = STP_ESEQ; break; }
+    }
+    c = {o.layer, o.unit, true};
+    if (has_w) b_here[slot] = 1;
+  }
+  if (rc == STP_OK) *bad = n;
+  free(bcur);
+  free(b_here);
+  return rc;
+}
+
+int ensure_events(stp_ctx *ctx, int want) {
+  if (!ctx->have_step_events) {
+    for (int i = 0; i < 3; i++) STP_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_step[i], hipEventDisableTiming));
+    ctx->have_step_events = 1;
+  }
+  if (ctx->ev_pool_size < want) {
+    hipEvent_t *np = (hipEvent_t *)realloc(ctx->ev_pool, sizeof(hipEvent_t) * want);
+    if (!np) return stp_fail(ctx, STP_ENOSPACE, "out of host memory%s");
+    ctx->ev_pool = np;
+    for (int i = ctx->ev_pool_size; i < want; i++) {
+      STP_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_pool[i], hipEventDisableTiming));
+      ctx->ev_pool_size = i + 1;
+    }
+  }
+  return STP_OK;
+}
+
+}  // namespace
+
+extern "C" int stp_validate_ops(const stp_stage *stage, const stp_op *ops, size_t n_ops, size_t *bad_index) {
+  // without a context nothing is known about earlier steps: accept a W whose B is not in the list
+  if (!stage || stage->n_layers < 1 || stage->n_microbatches < 1) return STP_EINVAL;
+  size_t sz = (size_t)stage->n_layers * stage->n_microbatches * 2;
+  uint8_t *all = (uint8_t *)malloc(sz);
+  if (!all) return STP_ENOSPACE;
+  memset(all, 1, sz);
+  int rc = validate(stage, ops, n_ops, all, bad_index);
+  free(all);
+  return rc;
+}
+
+extern "C" int stp_braid_reset(stp_ctx *ctx) {
+  if (!ctx) return STP_EINVAL;
+  if (ctx->b_done) memset(ctx->b_done, 0, ctx->b_done_size);
+  return STP_OK;
+}
+
+extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *ops, size_t n_ops, void *s_fwd,
+                              void *s_bwd, void *s_wgrad, stp_boundary_fn cb, void *user) {
+  if (!ctx) return STP_EINVAL;
+  if (!st || !st->desc || !st->w || !st->g || !st->stash || !st->act || !st->grad)
+    return stp_fail(ctx, STP_EINVAL, "stp_braid_step: null stage table%s");
+  if (st->n_layers < 1 || st->n_microbatches < 1) return stp_fail(ctx, STP_EINVAL, "stp_braid_step: empty stage%s");
+  const int L = st->n_layers, MB = st->n_microbatches;
+  const size_t bsz = (size_t)L * MB * 2;
+  if (!ctx->b_done || ctx->b_layers != L || ctx->b_mbs != MB) {
+    free(ctx->b_done);
+    ctx->b_done = (uint8_t *)calloc(bsz, 1);
+    if (!ctx->b_done) return stp_fail(ctx, STP_ENOSPACE, "out of host memory%s");
+    ctx->b_done_size = bsz; ctx->b_layers = L; ctx->b_mbs = MB;
+  }
+  size_t bad = 0;
+  int rc = validate(st, ops, n_ops, ctx->b_done, &bad);
+  if (rc != STP_OK) return stp_fail(ctx, rc, "stp_braid_step: op list rejected%s at index %ld", "", (long)bad);
+  for (int l = 0; l < L; l++) {
+    rc = stp_check_desc(&st->desc[l]);
+    if (rc != STP_OK) return stp_fail(ctx, rc, "stp_braid_step: layer description rejected%s (layer %ld)", "", (long)l);
+  }
+  if (n_ops == 0) return STP_OK;
+
+  hipStream_t sF = (hipStream_t)s_fwd, sB = (hipStream_t)s_bwd, sW = (hipStream_t)s_wgrad;
+  const bool serial = (sF == sB) && (sB == sW);
+  hipStream_t streams[3] = {sF, sB, sW};
+  rc = ensure_events(ctx, (int)n_ops);
+  if (rc != STP_OK) return rc;
+  // join with the previous step: its stashes and gradients may be read by any stream now
+  if (!serial && ctx->ev_next) {
+    for (int i = 0; i < 3; i++)
+      for (int j = 0; j < 3; j++)
+        if (streams[i] != streams[j]) STP_HIP(ctx, hipStreamWaitEvent(streams[i], ctx->ev_step[j], 0));
+  }
+  int *ev_of = (int *)malloc(sizeof(int) * bsz);
+  if (!ev_of) return stp_fail(ctx, STP_ENOSPACE, "out of host memory%s");
+  for (size_t i = 0; i < bsz; i++) ev_of[i] = -1;
+  int ev_used = 0;
+  rc = STP_OK;
+
+  for (size_t i = 0; i < n_ops && rc == STP_OK; i++) {
+    const stp_op &o = ops[i];
+    const stp_layer_desc *d = &st->desc[o.layer];
+    const stp_weights *w = &st->w[o.layer];
+    stp_wgrads *g = &st->g[o.layer];
+    const stp_stash *stash = &st->stash[(size_t)o.layer * MB + o.microbatch];
+    if (!stash->base) { rc = stp_fail(ctx, STP_EINVAL, "stp_braid_step: null stash%s"); break; }
+    size_t off[STP_ST_NFIELDS], nbytes;
+    for (int f = 0; f < STP_ST_NFIELDS; f++) stp_stash_field(d, f, &off[f], &nbytes);
+    char *sb = (char *)stash->base;
+    void *x = st->act[(size_t)o.layer * MB + o.microbatch];
+    void *x_out = st->act[(size_t)(o.layer + 1) * MB + o.microbatch];
+    void *dx = st->grad[(size_t)o.layer * MB + o.microbatch];
+    void *dx_out = st->grad[(size_t)(o.layer + 1) * MB + o.microbatch];
+    void *x_attn = sb + off[STP_ST_X_ATTN], *dx_attn = sb + off[STP_ST_DX_ATTN];
+    void *dz = sb + off[STP_ST_DZ], *dx_ln = sb + off[STP_ST_DX_LN];
+    const size_t act_bytes = (size_t)d->seq * d->mbsz * d->hidden * stp_elem_size(d->dtype);
+    const size_t slot = ((size_t)o.layer * MB + o.microbatch) * 2 + (o.unit == STP_MLP ? 1 : 0);
+    const bool has_w = o.unit == STP_ATTN || o.unit == STP_MLP;
+
+    if (o.kind == STP_OP_F) {
+      switch (o.unit) {
+        case STP_PRE_ATTN: rc = stp_forward_unit(ctx, d, o.unit, w, x, nullptr, nullptr, stash, 0, sF); break;
+        case STP_ATTN:
+          rc = stp_forward_unit(ctx, d, o.unit, w, nullptr, x, x_attn, stash, 0, sF);
+          if (rc == STP_OK && cb) cb(user, STP_AR_F_ATTN, x_attn, act_bytes, o.layer, o.microbatch, sF);
+          break;
+        case STP_PRE_MLP: rc = stp_forward_unit(ctx, d, o.unit, w, x_attn, nullptr, nullptr, stash, 0, sF); break;
+        case STP_MLP:
+          rc = stp_forward_unit(ctx, d, o.unit, w, nullptr, x_attn, x_out, stash, 0, sF);
+          if (rc == STP_OK && cb) cb(user, STP_AR_F_MLP, x_out, act_bytes, o.layer, o.microbatch, sF);
+          break;
+      }
+      continue;
+    }
+    if (o.kind == STP_OP_B || o.kind == STP_OP_BW) {
+      switch (o.unit) {
+        case STP_MLP:
+          rc = stp_backward_input_unit(ctx, d, o.unit, w, stash, nullptr, dx_out, nullptr, dz, nullptr, 1, sB);
+          if (rc == STP_OK && cb) cb(user, STP_AR_B_MLP, dz, act_bytes, o.layer, o.microbatch, sB);
+          break;
+        case STP_PRE_MLP: rc = stp_backward_input_unit(ctx, d, o.unit, w, stash, x_attn, dz, dx_out, dx_attn, g, 1, sB); break;
+        case STP_ATTN:
+          rc = stp_backward_input_unit(ctx, d, o.unit, w, stash, nullptr, dx_attn, nullptr, dx_ln, nullptr, 1, sB);
+          if (rc == STP_OK && cb) cb(user, STP_AR_B_ATTN, dx_ln, act_bytes, o.layer, o.microbatch, sB);
+          break;
+        case STP_PRE_ATTN: rc = stp_backward_input_unit(ctx, d, o.unit, w, stash, x, dx_ln, dx_attn, dx, g, 1, sB); break;
+      }
+      if (rc != STP_OK) break;
+      if (has_w) {
+        ctx->b_done[slot] = 1;
+        if (!serial && sW != sB) {
+          hipError_t e = hipEventRecord(ctx->ev_pool[ev_used], sB);
+          if (e != hipSuccess) { rc = stp_fail(ctx, STP_EHIP, "hipEventRecord failed: %s", hipGetErrorString(e)); break; }
+          ev_of[slot] = ev_used++;
+        }
+      }
+    }
+    if ((o.kind == STP_OP_W || o.kind == STP_OP_BW) && has_w) {
+      if (!serial && sW != sB && ev_of[slot] >= 0) {
+        hipError_t e = hipStreamWaitEvent(sW, ctx->ev_pool[ev_of[slot]], 0);
+        if (e != hipSuccess) { rc = stp_fail(ctx, STP_EHIP, "hipStreamWaitEvent failed: %s", hipGetErrorString(e)); break; }
+      }
+      const void *dy = o.unit == STP_MLP ? dx_out : dx_attn;
+      rc = stp_backward_weight_unit(ctx, d, o.unit, stash, dy, g, 2, sW);
+    }
+  }
+  free(ev_of);
+  if (rc != STP_OK) return rc;
+  if (!serial) {
+    for (int i = 0; i < 3; i++) {
+      STP_HIP(ctx, hipEventRecord(ctx->ev_step[i], streams[i]));
+    }
+  }
+  ctx->ev_next = 1;
+  return STP_OK;
+}

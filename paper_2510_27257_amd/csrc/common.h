@@ -1,0 +1,123 @@
+// Internal helpers shared by the HIP translation units of libstp.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include "stp.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+
+#define STP_MAX_LAYER_EVENTS 4096
+
+struct stp_ctx {
+  int device;
+  char err[512];
+  char *ws;          // caller-supplied workspace (device)
+  size_t ws_bytes;
+  hipEvent_t ev_step[3];   // end-of-step events of the three braid streams
+  int have_step_events;
+  hipEvent_t *ev_pool;     // events recorded after B ops, waited on by their W ops
+  int ev_pool_size;
+  int ev_next;
+  // which B units have been issued since the last reset: bitmap over (layer, mb, unit)
+  uint8_t *b_done;
+  size_t b_done_size;
+  int b_layers, b_mbs;
+};
+
+static inline int stp_fail(stp_ctx *ctx, int status, const char *fmt, const char *a = "", long b = 0, long c = 0) {
+  if (ctx) snprintf(ctx->err, sizeof(ctx->err), fmt, a, b, c);
+  return status;
+}
+
+#define STP_HIP(ctx, call)                                                                 \
+  do {                                                                                     \
+    hipError_t e_ = (call);                                                                \
+    if (e_ != hipSuccess) {                                                                \
+      if (ctx) snprintf((ctx)->err, sizeof((ctx)->err), "%s failed: %s (%s:%d)", #call,    \
+                        hipGetErrorString(e_), __FILE__, __LINE__);                        \
+      return STP_EHIP;                                                                     \
+    }                                                                                      \
+  } while (0)
+
+#define STP_LAUNCH_CHECK(ctx) STP_HIP(ctx, hipGetLastError())
+
+static inline bool stp_aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
+static inline size_t stp_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline size_t stp_elem_size(int dtype) { return dtype == STP_BF16 ? 2 : 4; }
+
+// ---- device-side 8-element vector access, math in fp32 -----------------------------
+template <typename T> struct Vec8;
+template <> struct Vec8<float> {
+  static __device__ __forceinline__ void load(const float *p, float (&v)[8]) {
+    float4 a = *reinterpret_cast<const float4 *>(p);
+    float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float *p, const float (&v)[8]) {
+    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
+};
+template <> struct Vec8<bf16_t> {
+  static __device__ __forceinline__ void load(const bf16_t *p, float (&v)[8]) {
+    uint4 u = *reinterpret_cast<const uint4 *>(p);
+    uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      v[2 * i] = __uint_as_float(w[i] << 16);
+      v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ void store(bf16_t *p, const float (&v)[8]) {
+    bf16x8_t o;
+#pragma unroll
+    for (int i = 0; i < 8; i++) o[i] = (bf16_t)v[i];
+    *reinterpret_cast<bf16x8_t *>(p) = o;
+  }
+};
+
+template <typename T> __device__ __forceinline__ float to_f32(T x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f32(float x) { return (T)x; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// exact GELU x*Phi(x) and its derivative Phi(x) + x*phi(x)
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  float Phi = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
+  float phi = 0.3989422804014327f * __expf(-0.5f * x * x);
+  return Phi + x * phi;
+}
+__device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
+
+// ---- kernel launchers implemented in the .hip files ---------------------------------
+int stp_launch_gemm_bf16(stp_ctx *ctx, const stp_gemm_args *a, hipStream_t s);
+int stp_launch_gemm_f32(stp_ctx *ctx, const stp_gemm_args *a, hipStream_t s);
+int stp_launch_attn_fwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out, float *lse, hipStream_t s);
+int stp_launch_attn_bwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const void *out, const float *lse,
+                             const void *dout, float *delta, void *dqkv, hipStream_t s);
+int stp_launch_attn_fwd_generic(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out, float *lse, hipStream_t s);
+int stp_launch_attn_bwd_generic(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const void *out, const float *lse,
+                                const void *dout, float *delta, void *dqkv, hipStream_t s);
+// workspace lane: a third of the caller's workspace
+static inline char *stp_ws_lane(stp_ctx *ctx, int lane, size_t *bytes) {
+  size_t third = (ctx->ws_bytes / 3) & ~(size_t)255;
+  *bytes = third;
+  return ctx->ws ? ctx->ws + (size_t)lane * third : nullptr;
+}

@@ -1,0 +1,511 @@
+// HBM-bound kernels of the units: normalisation forward/backward (Pre-Attn and
+// Pre-MLP units, Eq. 1-2), GELU / SwiGLU, rotary embedding, bias-gradient
+// column sums and the attention-backward row dot.  All math in fp32; storage
+// type T is float or bf16.  Every global access is a 16-byte (bf16) or 32-byte
+// (fp32) vector per lane, lanes contiguous.
+#include "common.h"
+
+// ======================================================================
+// Norm forward: one 64-lane wave per token row, row kept in registers.
+// chunk c of a lane covers elements (c*64 + lane)*8 .. +7
+// ======================================================================
+template <typename T, int NORM, int NCH>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, const T *__restrict__ gamma,
+                                                       const T *__restrict__ beta, T *__restrict__ y,
+                                                       float *__restrict__ stats, int rows, int h, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T *xr = x + (size_t)row * h;
+  float v[NCH][8];
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    int col = (c * 64 + lane) * 8;
+    if (col < h) {
+      Vec8<T>::load(xr + col, v[c]);
+#pragma unroll
+      for (int i = 0; i < 8; i++) s += (NORM == STP_NORM_LN) ? v[c][i] : v[c][i] * v[c][i];
+    }
+  }
+  s = wave_sum(s);
+  float mean = 0.f, rstd;
+  if (NORM == STP_NORM_LN) {
+    mean = s / (float)h;
+    float q = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      int col = (c * 64 + lane) * 8;
+      if (col < h) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) { float d = v[c][i] - mean; q += d * d; }
+      }
+    }
+    q = wave_sum(q);
+    rstd = 1.0f / sqrtf(q / (float)h + eps);
+  } else {
+    rstd = 1.0f / sqrtf(s / (float)h + eps);
+  }
+  if (lane == 0) { stats[2 * (size_t)row] = mean; stats[2 * (size_t)row + 1] = rstd; }
+  T *yr = y + (size_t)row * h;
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    int col = (c * 64 + lane) * 8;
+    if (col < h) {
+      float g[8], b[8], o[8];
+      Vec8<T>::load(gamma + col, g);
+      if (NORM == STP_NORM_LN && beta) Vec8<T>::load(beta + col, b);
+      else {
+#pragma unroll
+        for (int i = 0; i < 8; i++) b[i] = 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; i++) o[i] = (v[c][i] - mean) * rstd * g[i] + b[i];
+      Vec8<T>::store(yr + col, o);
+    }
+  }
+}
+
+// ======================================================================
+// Norm backward (+ residual gradient, Eq. 2): one 256-thread group per row,
+// groups stride over rows and keep the gain/bias gradient partials of their
+// columns in registers; the partials go to the workspace and a second kernel
+// adds them up in a fixed order (deterministic, no float atomics).
+// chunk c of a thread covers elements (c*256 + tid)*8 .. +7
+// ======================================================================
+template <typename T, int NORM, int NCH>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, const T *__restrict__ gamma,
+                                                       const float *__restrict__ stats, const T *__restrict__ dy,
+                                                       const T *__restrict__ dres, T *__restrict__ dx,
+                                                       float *__restrict__ partial, int rows, int h) {
+  __shared__ float red[2][4][2];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  float gam[NCH][8], acc_g[NCH][8], acc_b[NCH][8];
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    int col = (c * 256 + tid) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; i++) { gam[c][i] = 0.f; acc_g[c][i] = 0.f; acc_b[c][i] = 0.f; }
+    if (col < h) Vec8<T>::load(gamma + col, gam[c]);
+  }
+  int it = 0;
+  for (int row = blockIdx.x; row < rows; row += gridDim.x, it++) {
+    const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
+    const size_t off = (size_t)row * h;
+    float xh[NCH][8], g[NCH][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      int col = (c * 256 + tid) * 8;
+      if (col < h) {
+        float xv[8], dv[8];
+        Vec8<T>::load(x + off + col, xv);
+        Vec8<T>::load(dy + off + col, dv);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+          xh[c][i] = (xv[i] - mean) * rstd;
+          acc_g[c][i] += dv[i] * xh[c][i];
+          acc_b[c][i] += dv[i];
+          g[c][i] = dv[i] * gam[c][i];
+          s1 += g[c][i];
+          s2 += g[c][i] * xh[c][i];
+        }
+      }
+    }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if (lane == 0) { red[it & 1][wv][0] = s1; red[it & 1][wv][1] = s2; }
+    __syncthreads();
+    float c1 = (red[it & 1][0][0] + red[it & 1][1][0]) + (red[it & 1][2][0] + red[it & 1][3][0]);
+    float c2 = (red[it & 1][0][1] + red[it & 1][1][1]) + (red[it & 1][2][1] + red[it & 1][3][1]);
+    c1 = (NORM == STP_NORM_LN) ? c1 / (float)h : 0.f;
+    c2 = c2 / (float)h;
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      int col = (c * 256 + tid) * 8;
+      if (col < h) {
+        float o[8], r[8];
+        if (dres) Vec8<T>::load(dres + off + col, r);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+          o[i] = rstd * (g[c][i] - c1 - xh[c][i] * c2);
+          if (dres) o[i] += r[i];
+        }
+        Vec8<T>::store(dx + off + col, o);
+      }
+    }
+  }
+  if (partial) {
+    float *pg = partial + (size_t)blockIdx.x * 2 * h;
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      int col = (c * 256 + tid) * 8;
+      if (col < h) {
+        Vec8<float>::store(pg + col, acc_g[c]);
+        Vec8<float>::store(pg + h + col, acc_b[c]);
+      }
+    }
+  }
+}
+
+// out[c] += scale * sum_{p < nparts} partial[p*stride + c]   (fixed order)
+__global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__restrict__ partial, int nparts,
+                                                            size_t stride, int n, float scale,
+                                                            float *__restrict__ out) {
+  int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= n) return;
+  float s = 0.f;
+  for (int p = 0; p < nparts; p++) s += partial[(size_t)p * stride + c];
+  out[c] += scale * s;
+}
+
+// ======================================================================
+// Column sums (bias gradients): stage 1 sums slabs of 64 rows, 8 columns per thread.
+// ======================================================================
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ x, int rows, int n,
+                                                     float *__restrict__ partial) {
+  int col = (blockIdx.x * 256 + threadIdx.x) * 8;
+  if (col >= n) return;
+  int r0 = blockIdx.y * 64, r1 = min(rows, r0 + 64);
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int r = r0; r < r1; r++) {
+    float v[8];
+    Vec8<T>::load(x + (size_t)r * n + col, v);
+#pragma unroll
+    for (int i = 0; i < 8; i++) acc[i] += v[i];
+  }
+  Vec8<float>::store(partial + (size_t)blockIdx.y * n + col, acc);
+}
+
+// ======================================================================
+// Activations
+// ======================================================================
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, size_t n8) {
+  for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+    float v[8];
+    Vec8<T>::load(x + i * 8, v);
+#pragma unroll
+    for (int k = 0; k < 8; k++) v[k] = gelu_f(v[k]);
+    Vec8<T>::store(y + i * 8, v);
+  }
+}
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy,
+                                                       T *__restrict__ dx, size_t n8) {
+  for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+    float v[8], d[8];
+    Vec8<T>::load(x + i * 8, v);
+    Vec8<T>::load(dy + i * 8, d);
+#pragma unroll
+    for (int k = 0; k < 8; k++) d[k] *= gelu_grad_f(v[k]);
+    Vec8<T>::store(dx + i * 8, d);
+  }
+}
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T *__restrict__ gate, const T *__restrict__ up,
+                                                         T *__restrict__ y, size_t n8) {
+  for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+    float g[8], u[8];
+    Vec8<T>::load(gate + i * 8, g);
+    Vec8<T>::load(up + i * 8, u);
+#pragma unroll
+    for (int k = 0; k < 8; k++) g[k] = g[k] * sigmoid_f(g[k]) * u[k];
+    Vec8<T>::store(y + i * 8, g);
+  }
+}
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T *__restrict__ gate, const T *__restrict__ up,
+                                                         const T *__restrict__ dy, T *__restrict__ dgate,
+                                                         T *__restrict__ dup, size_t n8) {
+  for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+    float g[8], u[8], d[8], dg[8], du[8];
+    Vec8<T>::load(gate + i * 8, g);
+    Vec8<T>::load(up + i * 8, u);
+    Vec8<T>::load(dy + i * 8, d);
+#pragma unroll
+    for (int k = 0; k < 8; k++) {
+      float sg = sigmoid_f(g[k]);
+      du[k] = d[k] * g[k] * sg;
+      dg[k] = d[k] * u[k] * sg * (1.0f + g[k] * (1.0f - sg));
+    }
+    Vec8<T>::store(dgate + i * 8, dg);
+    Vec8<T>::store(dup + i * 8, du);
+  }
+}
+
+// ======================================================================
+// Rotary embedding, in place on the Q and K thirds of qkv [T, 3a].
+// One thread rotates 8 pairs (i, i + d/2) of one head of one token.
+// ======================================================================
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int tokens, int seq, int n, int d,
+                                                   float log2_base, float sign) {
+  const int half = d / 2, per_head = half / 8;
+  size_t total = (size_t)tokens * 2 * n * per_head;
+  size_t idx = blockIdx.x * (size_t)256 + threadIdx.x;
+  if (idx >= total) return;
+  int c = idx % per_head;
+  size_t r = idx / per_head;
+  int head = r % (2 * n);  // 0..n-1: Q heads, n..2n-1: K heads (contiguous thirds)
+  size_t tok = r / (2 * n);
+  int pos = tok % seq;
+  T *p = qkv + tok * (size_t)(3 * n * d) + (size_t)head * d + c * 8;
+  float a[8], b[8], oa[8], ob[8];
+  Vec8<T>::load(p, a);
+  Vec8<T>::load(p + half, b);
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    float inv_freq = exp2f(-2.0f * (float)(c * 8 + i) / (float)d * log2_base);
+    float ang = (float)pos * inv_freq;
+    float sn, cs;
+    sincosf(ang, &sn, &cs);
+    sn *= sign;
+    oa[i] = a[i] * cs - b[i] * sn;
+    ob[i] = b[i] * cs + a[i] * sn;
+  }
+  Vec8<T>::store(p, oa);
+  Vec8<T>::store(p + half, ob);
+}
+
+// ======================================================================
+// delta[b, head, i] = sum_c dctx[tok, head*d + c] * ctx[tok, head*d + c]
+// (the rowsum(dP o P) term of the softmax backward).  One wave per (token, head).
+// ======================================================================
+template <typename T>
+__global__ __launch_bounds__(256) void rowdot_kernel(const T *__restrict__ a, const T *__restrict__ b,
+                                                     float *__restrict__ delta, int tokens, int seq, int n, int d) {
+  const int lane = threadIdx.x & 63;
+  size_t w = blockIdx.x * (size_t)4 + (threadIdx.x >> 6);
+  if (w >= (size_t)tokens * n) return;
+  int head = w % n;
+  size_t tok = w / n;
+  float s = 0.f;
+  int col = lane * 8;
+  if (col < d) {
+    float u[8], v[8];
+    Vec8<T>::load(a + tok * (size_t)(n * d) + head * d + col, u);
+    Vec8<T>::load(b + tok * (size_t)(n * d) + head * d + col, v);
+#pragma unroll
+    for (int i = 0; i < 8; i++) s += u[i] * v[i];
+  }
+  s = wave_sum(s);
+  if (lane == 0) {
+    size_t bidx = tok / seq, i = tok % seq;
+    delta[(bidx * n + head) * seq + i] = s;
+  }
+}
+
+// ======================================================================
+// Host launchers
+// ======================================================================
+static inline int ew_grid(size_t n8) {
+  size_t g = (n8 + 255) / 256;
+  return (int)(g > 4096 ? 4096 : (g ? g : 1));
+}
+
+template <typename T>
+static int norm_fwd_dispatch(stp_ctx *ctx, int norm, int rows, int h, float eps, const void *x, const void *gamma,
+                             const void *beta, void *y, float *stats, hipStream_t s) {
+  dim3 grid((rows + 3) / 4), block(256);
+  int nch = (h + 511) / 512;
+#define LAUNCH(NORM, NCH)                                                                               \
+  hipLaunchKernelGGL((norm_fwd_kernel<T, NORM, NCH>), grid, block, 0, s, (const T *)x, (const T *)gamma, \
+                     (const T *)beta, (T *)y, stats, rows, h, eps)
+#define BY_NCH(NORM)                                   \
+  if (nch <= 1) LAUNCH(NORM, 1);                       \
+  else if (nch <= 2) LAUNCH(NORM, 2);                  \
+  else if (nch <= 4) LAUNCH(NORM, 4);                  \
+  else if (nch <= 8) LAUNCH(NORM, 8);                  \
+  else if (nch <= 12) LAUNCH(NORM, 12);                \
+  else LAUNCH(NORM, 16);
+  if (norm == STP_NORM_LN) { BY_NCH(STP_NORM_LN) } else { BY_NCH(STP_NORM_RMS) }
+#undef BY_NCH
+#undef LAUNCH
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+
+extern "C" int stp_norm_forward(stp_ctx *ctx, int dtype, int norm, int32_t T, int32_t h, float eps, const void *x,
+                                const void *gamma, const void *beta, void *y, float *stats, void *hip_stream) {
+  if (!ctx) return STP_EINVAL;
+  if (!x || !gamma || !y || !stats) return stp_fail(ctx, STP_EINVAL, "stp_norm_forward: null pointer%s");
+  if (T < 0 || h <= 0 || h % 8 || h > 8192) return stp_fail(ctx, STP_ESHAPE, "stp_norm_forward: h must be a multiple of 8, <= 8192%s");
+  if (!stp_aligned16(x) || !stp_aligned16(gamma) || !stp_aligned16(y) || (beta && !stp_aligned16(beta)))
+    return stp_fail(ctx, STP_EALIGN, "stp_norm_forward: pointers must be 16-byte aligned%s");
+  if (norm != STP_NORM_LN && norm != STP_NORM_RMS) return stp_fail(ctx, STP_EINVAL, "stp_norm_forward: bad norm%s");
+  if (T == 0) return STP_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (dtype == STP_BF16) return norm_fwd_dispatch<bf16_t>(ctx, norm, T, h, eps, x, gamma, beta, y, stats, s);
+  if (dtype == STP_F32) return norm_fwd_dispatch<float>(ctx, norm, T, h, eps, x, gamma, beta, y, stats, s);
+  return stp_fail(ctx, STP_EINVAL, "stp_norm_forward: bad dtype%s");
+}
+
+static inline int norm_bwd_groups(int rows) { return rows < 512 ? rows : 512; }
+
+template <typename T>
+static int norm_bwd_dispatch(stp_ctx *ctx, int norm, int rows, int h, const void *x, const void *gamma,
+                             const float *stats, const void *dy, const void *dres, void *dx, float *partial,
+                             int groups, hipStream_t s) {
+  dim3 grid(groups), block(256);
+  int nch = (h + 2047) / 2048;
+#define LAUNCH(NORM, NCH)                                                                               \
+  hipLaunchKernelGGL((norm_bwd_kernel<T, NORM, NCH>), grid, block, 0, s, (const T *)x, (const T *)gamma, \
+                     stats, (const T *)dy, (const T *)dres, (T *)dx, partial, rows, h)
+#define BY_NCH(NORM)                                   \
+  if (nch <= 1) LAUNCH(NORM, 1);                       \
+  else if (nch <= 2) LAUNCH(NORM, 2);                  \
+  else if (nch <= 3) LAUNCH(NORM, 3);                  \
+  else LAUNCH(NORM, 4);
+  if (norm == STP_NORM_LN) { BY_NCH(STP_NORM_LN) } else { BY_NCH(STP_NORM_RMS) }
+#undef BY_NCH
+#undef LAUNCH
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+
+extern "C" int stp_norm_backward(stp_ctx *ctx, int dtype, int norm, int32_t T, int32_t h, const void *x,
+                                 const void *gamma, const float *stats, const void *dy, const void *d_resid,
+                                 void *dx, float *dgamma, float *dbeta, int lane, void *hip_stream) {
+  if (!ctx) return STP_EINVAL;
+  if (!x || !gamma || !stats || !dy || !dx) return stp_fail(ctx, STP_EINVAL, "stp_norm_backward: null pointer%s");
+  if (T < 0 || h <= 0 || h % 8 || h > 8192) return stp_fail(ctx, STP_ESHAPE, "stp_norm_backward: h must be a multiple of 8, <= 8192%s");
+  if (!stp_aligned16(x) || !stp_aligned16(gamma) || !stp_aligned16(dy) || !stp_aligned16(dx) ||
+      (d_resid && !stp_aligned16(d_resid)))
+    return stp_fail(ctx, STP_EALIGN, "stp_norm_backward: pointers must be 16-byte aligned%s");
+  if (norm != STP_NORM_LN && norm != STP_NORM_RMS) return stp_fail(ctx, STP_EINVAL, "stp_norm_backward: bad norm%s");
+  if (lane < 0 || lane > 2) return stp_fail(ctx, STP_EINVAL, "stp_norm_backward: lane must be 0..2%s");
+  if (dtype != STP_BF16 && dtype != STP_F32) return stp_fail(ctx, STP_EINVAL, "stp_norm_backward: bad dtype%s");
+  if (T == 0) return STP_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  int groups = norm_bwd_groups(T);
+  float *partial = nullptr;
+  bool want = dgamma || dbeta;
+  if (want) {
+    size_t lane_bytes;
+    char *ws = stp_ws_lane(ctx, lane, &lane_bytes);
+    size_t need = (size_t)groups * 2 * h * sizeof(float);
+    if (!ws || lane_bytes < need) return stp_fail(ctx, STP_ENOSPACE, "stp_norm_backward: workspace lane too small%s (need %ld bytes)", "", (long)need);
+    partial = (float *)ws;
+  }
+  int rc = dtype == STP_BF16 ? norm_bwd_dispatch<bf16_t>(ctx, norm, T, h, x, gamma, stats, dy, d_resid, dx, partial, groups, s)
+                             : norm_bwd_dispatch<float>(ctx, norm, T, h, x, gamma, stats, dy, d_resid, dx, partial, groups, s);
+  if (rc != STP_OK) return rc;
+  if (dgamma) {
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 255) / 256), dim3(256), 0, s, partial, groups, (size_t)2 * h, h, 1.0f, dgamma);
+    STP_LAUNCH_CHECK(ctx);
+  }
+  if (dbeta && norm == STP_NORM_LN) {
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 255) / 256), dim3(256), 0, s, partial + h, groups, (size_t)2 * h, h, 1.0f, dbeta);
+    STP_LAUNCH_CHECK(ctx);
+  }
+  return STP_OK;
+}
+
+extern "C" int stp_colsum(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const void *x, float scale, float *out,
+                          int lane, void *hip_stream) {
+  if (!ctx) return STP_EINVAL;
+  if (!x || !out) return stp_fail(ctx, STP_EINVAL, "stp_colsum: null pointer%s");
+  if (T < 0 || N <= 0 || N % 8) return stp_fail(ctx, STP_ESHAPE, "stp_colsum: N must be a multiple of 8%s");
+  if (!stp_aligned16(x)) return stp_fail(ctx, STP_EALIGN, "stp_colsum: x must be 16-byte aligned%s");
+  if (lane < 0 || lane > 2) return stp_fail(ctx, STP_EINVAL, "stp_colsum: lane must be 0..2%s");
+  if (dtype != STP_BF16 && dtype != STP_F32) return stp_fail(ctx, STP_EINVAL, "stp_colsum: bad dtype%s");
+  if (T == 0) return STP_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  int slabs = (T + 63) / 64;
+  size_t lane_bytes;
+  char *ws = stp_ws_lane(ctx, lane, &lane_bytes);
+  size_t need = (size_t)slabs * N * sizeof(float);
+  if (!ws || lane_bytes < need) return stp_fail(ctx, STP_ENOSPACE, "stp_colsum: workspace lane too small%s (need %ld bytes)", "", (long)need);
+  float *partial = (float *)ws;
+  dim3 grid((N / 8 + 255) / 256, slabs), block(256);
+  if (dtype == STP_BF16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)x, T, N, partial);
+  else hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float *)x, T, N, partial);
+  STP_LAUNCH_CHECK(ctx);
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3((N + 255) / 256), dim3(256), 0, s, partial, slabs, (size_t)N, N, scale, out);
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+
+#define EW_CHECK(name, cond_null)                                                                          \
+  if (!ctx) return STP_EINVAL;                                                                             \
+  if (cond_null) return stp_fail(ctx, STP_EINVAL, name ": null pointer%s");                                \
+  if (n % 8) return stp_fail(ctx, STP_ESHAPE, name ": element count must be a multiple of 8%s");           \
+  if (dtype != STP_BF16 && dtype != STP_F32) return stp_fail(ctx, STP_EINVAL, name ": bad dtype%s");       \
+  if (n == 0) return STP_OK;                                                                               \
+  hipStream_t s = (hipStream_t)hip_stream;                                                                 \
+  size_t n8 = n / 8;
+
+extern "C" int stp_gelu_forward(stp_ctx *ctx, int dtype, size_t n, const void *x, void *y, void *hip_stream) {
+  EW_CHECK("stp_gelu_forward", !x || !y)
+  if (!stp_aligned16(x) || !stp_aligned16(y)) return stp_fail(ctx, STP_EALIGN, "stp_gelu_forward: alignment%s");
+  if (dtype == STP_BF16) hipLaunchKernelGGL(gelu_fwd_kernel<bf16_t>, dim3(ew_grid(n8)), dim3(256), 0, s, (const bf16_t *)x, (bf16_t *)y, n8);
+  else hipLaunchKernelGGL(gelu_fwd_kernel<float>, dim3(ew_grid(n8)), dim3(256), 0, s, (const float *)x, (float *)y, n8);
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+extern "C" int stp_gelu_backward(stp_ctx *ctx, int dtype, size_t n, const void *x, const void *dy, void *dx, void *hip_stream) {
+  EW_CHECK("stp_gelu_backward", !x || !dy || !dx)
+  if (!stp_aligned16(x) || !stp_aligned16(dy) || !stp_aligned16(dx)) return stp_fail(ctx, STP_EALIGN, "stp_gelu_backward: alignment%s");
+  if (dtype == STP_BF16) hipLaunchKernelGGL(gelu_bwd_kernel<bf16_t>, dim3(ew_grid(n8)), dim3(256), 0, s, (const bf16_t *)x, (const bf16_t *)dy, (bf16_t *)dx, n8);
+  else hipLaunchKernelGGL(gelu_bwd_kernel<float>, dim3(ew_grid(n8)), dim3(256), 0, s, (const float *)x, (const float *)dy, (float *)dx, n8);
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+extern "C" int stp_swiglu_forward(stp_ctx *ctx, int dtype, size_t n, const void *gate, const void *up, void *y, void *hip_stream) {
+  EW_CHECK("stp_swiglu_forward", !gate || !up || !y)
+  if (!stp_aligned16(gate) || !stp_aligned16(up) || !stp_aligned16(y)) return stp_fail(ctx, STP_EALIGN, "stp_swiglu_forward: alignment%s");
+  if (dtype == STP_BF16) hipLaunchKernelGGL(swiglu_fwd_kernel<bf16_t>, dim3(ew_grid(n8)), dim3(256), 0, s, (const bf16_t *)gate, (const bf16_t *)up, (bf16_t *)y, n8);
+  else hipLaunchKernelGGL(swiglu_fwd_kernel<float>, dim3(ew_grid(n8)), dim3(256), 0, s, (const float *)gate, (const float *)up, (float *)y, n8);
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+extern "C" int stp_swiglu_backward(stp_ctx *ctx, int dtype, size_t n, const void *gate, const void *up, const void *dy,
+                                   void *dgate, void *dup, void *hip_stream) {
+  EW_CHECK("stp_swiglu_backward", !gate || !up || !dy || !dgate || !dup)
+  if (!stp_aligned16(gate) || !stp_aligned16(up) || !stp_aligned16(dy) || !stp_aligned16(dgate) || !stp_aligned16(dup))
+    return stp_fail(ctx, STP_EALIGN, "stp_swiglu_backward: alignment%s");
+  if (dtype == STP_BF16)
+    hipLaunchKernelGGL(swiglu_bwd_kernel<bf16_t>, dim3(ew_grid(n8)), dim3(256), 0, s, (const bf16_t *)gate, (const bf16_t *)up,
+                       (const bf16_t *)dy, (bf16_t *)dgate, (bf16_t *)dup, n8);
+  else
+    hipLaunchKernelGGL(swiglu_bwd_kernel<float>, dim3(ew_grid(n8)), dim3(256), 0, s, (const float *)gate, (const float *)up,
+                       (const float *)dy, (float *)dgate, (float *)dup, n8);
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+
+extern "C" int stp_rope(stp_ctx *ctx, const stp_layer_desc *d, void *qkv, int inverse, void *hip_stream) {
+  if (!ctx) return STP_EINVAL;
+  if (!d || !qkv) return stp_fail(ctx, STP_EINVAL, "stp_rope: null pointer%s");
+  int rc = stp_check_desc(d);
+  if (rc != STP_OK) return stp_fail(ctx, rc, "stp_rope: bad layer description%s");
+  if (d->head_dim % 16) return stp_fail(ctx, STP_ESHAPE, "stp_rope: head_dim must be a multiple of 16%s");
+  if (!stp_aligned16(qkv)) return stp_fail(ctx, STP_EALIGN, "stp_rope: alignment%s");
+  int tokens = d->seq * d->mbsz;
+  if (tokens == 0) return STP_OK;
+  size_t total = (size_t)tokens * 2 * d->heads_local * (d->head_dim / 16);
+  dim3 grid((total + 255) / 256), block(256);
+  float log2_base = log2f(d->rope_base), sign = inverse ? -1.0f : 1.0f;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (d->dtype == STP_BF16)
+    hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, block, 0, s, (bf16_t *)qkv, tokens, d->seq, d->heads_local, d->head_dim, log2_base, sign);
+  else
+    hipLaunchKernelGGL(rope_kernel<float>, grid, block, 0, s, (float *)qkv, tokens, d->seq, d->heads_local, d->head_dim, log2_base, sign);
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+
+// used by the attention backward launchers
+int stp_launch_rowdot(stp_ctx *ctx, const stp_layer_desc *d, const void *a, const void *b, float *delta, hipStream_t s) {
+  int tokens = d->seq * d->mbsz;
+  size_t waves = (size_t)tokens * d->heads_local;
+  dim3 grid((waves + 3) / 4), block(256);
+  if (d->dtype == STP_BF16)
+    hipLaunchKernelGGL(rowdot_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)a, (const bf16_t *)b, delta, tokens, d->seq, d->heads_local, d->head_dim);
+  else
+    hipLaunchKernelGGL(rowdot_kernel<float>, grid, block, 0, s, (const float *)a, (const float *)b, delta, tokens, d->seq, d->heads_local, d->head_dim);
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}

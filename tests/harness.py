@@ -1,0 +1,73 @@
+"""Shared plumbing of the GPU parity tests: moves the seeded host tensors to the device
+in the workload's storage type, owns stashes / gradient buffers, and runs the oracle on
+the very same (already rounded) values."""
+from __future__ import annotations
+
+import ctypes as C
+from dataclasses import replace
+
+import numpy as np
+import torch
+
+import paper_2510_27257_amd as stp
+from paper_2510_27257_amd import synth
+from oracle import stp_oracle as O
+
+
+def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    """fp32 host values -> device tensor of the storage type (bf16 by bit pattern: no second rounding)."""
+    if dtype == "bf16":
+        bits = synth.to_bf16_bits(x).view(np.int16)
+        return torch.from_numpy(bits.copy()).cuda().view(torch.bfloat16).reshape(x.shape)
+    return torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max|got - ref| / max|ref| (the tolerance definition used for every parity check)."""
+    den = float(np.max(np.abs(ref)))
+    return float(np.max(np.abs(np.asarray(got, np.float64) - ref))) / (den if den > 0 else 1.0)
+
+
+def oracle_cfg(wl: synth.Workload) -> O.LayerCfg:
+    return O.LayerCfg(hidden=wl.hidden, heads_local=wl.heads_local, head_dim=wl.head_dim, ffn_local=wl.ffn_local,
+                      tp=wl.tp, norm=wl.norm, act=wl.act, causal=wl.causal, rope=wl.rope, has_bias=wl.has_bias,
+                      eps=wl.eps, rope_base=wl.rope_base)
+
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+class LayerOnDevice:
+    """One layer's weights, fp32 gradient accumulators and per-microbatch stashes on the GPU."""
+
+    def __init__(self, ctx: stp.Context, wl: synth.Workload, seed: int, layer: int = 0, n_mb: int = 1):
+        self.ctx, self.wl = ctx, wl
+        self.desc = stp.make_desc(wl)
+        self.tdtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        self.w_host = synth.make_weights(wl, seed, layer)
+        self.w_dev = {k: to_dev(v, wl.dtype) for k, v in self.w_host.items()}
+        self.g_dev = {k: torch.zeros(v.shape, dtype=torch.float32, device="cuda") for k, v in self.w_host.items()}
+        self.w = stp.Weights(**{k: v.data_ptr() for k, v in self.w_dev.items()})
+        self.g = stp.WGrads(**{k: v.data_ptr() for k, v in self.g_dev.items()})
+        nbytes = ctx.stash_bytes(self.desc)
+        self.stash_mem = [torch.zeros(nbytes, dtype=torch.uint8, device="cuda") for _ in range(n_mb)]
+        self.stash = [stp.Stash(base=m.data_ptr(), bytes=nbytes) for m in self.stash_mem]
+        ctx.ensure_workspace([self.desc])
+
+    def field(self, name: str, mb: int = 0) -> torch.Tensor:
+        """View of a stash field as a typed tensor."""
+        off, n = self.ctx.stash_field(self.desc, name)
+        raw = self.stash_mem[mb][off:off + n]
+        if name in ("STATS1", "STATS2", "LSE", "DELTA"):
+            return raw.view(torch.float32)
+        return raw.view(self.tdtype)
+
+    def new_act(self) -> torch.Tensor:
+        return torch.empty((self.wl.seq, self.wl.hidden), dtype=self.tdtype, device="cuda")
+
+    def w64(self):
+        return {k: v.astype(np.float64) for k, v in self.w_host.items()}

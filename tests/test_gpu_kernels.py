@@ -1,0 +1,249 @@
+"""Per-kernel parity against pieces of the fp64 oracle, through the C ABI."""
+import ctypes as C
+import math
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2510_27257_amd as stp
+from paper_2510_27257_amd import synth
+from oracle import stp_oracle as O
+from harness import to_dev, to_host, rel_err, TOL
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = stp.Context(0)
+    c.set_workspace(torch.empty(64 << 20, dtype=torch.uint8, device="cuda"))
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def q(x, dtype):
+    return synth.quantize(x, dtype)
+
+
+# ------------------------------------------------------------------ GEMM
+GEMM_SHAPES = [(128, 128, 64), (256, 256, 128), (384, 520, 200), (1000, 264, 72), (520, 1288, 328), (8, 8, 8)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("a_trans,b_trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_layouts(ctx, dtype, a_trans, b_trans, M, N, K):
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    A = q(rng.standard_normal((M, K), dtype=np.float32), dtype)
+    B = q(rng.standard_normal((K, N), dtype=np.float32) * 0.05, dtype)
+    Ad = to_dev(np.ascontiguousarray(A.T) if a_trans else A, dtype)
+    Bd = to_dev(np.ascontiguousarray(B.T) if b_trans else B, dtype)
+    Cd = torch.zeros((M, N), dtype=Ad.dtype, device="cuda")
+    g = stp.GemmArgs(dtype=stp.BF16 if dtype == "bf16" else stp.F32, M=M, N=N, K=K,
+                     A=Ad.data_ptr(), lda=M if a_trans else K, a_trans=a_trans,
+                     B=Bd.data_ptr(), ldb=K if b_trans else N, b_trans=b_trans,
+                     C=Cd.data_ptr(), ldc=N, bias_scale=1.0, resid_scale=1.0)
+    ctx.gemm(g)
+    torch.cuda.synchronize()
+    ref = A.astype(np.float64) @ B.astype(np.float64)
+    assert rel_err(to_host(Cd), ref) < (4e-3 if dtype == "bf16" else 2e-6)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_gemm_epilogues(ctx, dtype):
+    M, N, K = 392, 456, 136
+    rng = np.random.default_rng(5)
+    tol = 6e-3 if dtype == "bf16" else 3e-6
+    A = q(rng.standard_normal((M, K), dtype=np.float32), dtype)
+    B = q(rng.standard_normal((K, N), dtype=np.float32) * 0.1, dtype)
+    bias = q(rng.standard_normal(N, dtype=np.float32), dtype)
+    R = q(rng.standard_normal((M, N), dtype=np.float32), dtype)
+    Ad, Bd, bd, Rd = (to_dev(x, dtype) for x in (A, B, bias, R))
+    code = stp.BF16 if dtype == "bf16" else stp.F32
+    base = dict(dtype=code, M=M, N=N, K=K, A=Ad.data_ptr(), lda=K, B=Bd.data_ptr(), ldb=N, ldc=N)
+    AB = A.astype(np.float64) @ B.astype(np.float64)
+    # bias*scale + resid*scale
+    Cd = torch.zeros((M, N), dtype=Ad.dtype, device="cuda")
+    ctx.gemm(stp.GemmArgs(**base, C=Cd.data_ptr(), bias=bd.data_ptr(), bias_scale=0.25, resid=Rd.data_ptr(), ldr=N,
+                          resid_scale=0.125))
+    torch.cuda.synchronize()
+    assert rel_err(to_host(Cd), AB + 0.25 * bias + 0.125 * R) < tol
+    # dual output: C = v, C2 = gelu(v)
+    C2 = torch.zeros_like(Cd)
+    ctx.gemm(stp.GemmArgs(**base, C=Cd.data_ptr(), bias=bd.data_ptr(), bias_scale=1.0, resid_scale=1.0, epilogue=1,
+                          C2=C2.data_ptr(), ld2=N))
+    torch.cuda.synchronize()
+    assert rel_err(to_host(Cd), AB + bias) < tol
+    assert rel_err(to_host(C2), O.gelu(AB + bias)) < tol
+    # C = v * gelu'(aux)
+    ctx.gemm(stp.GemmArgs(**base, C=Cd.data_ptr(), bias_scale=1.0, resid_scale=1.0, epilogue=2, aux=Rd.data_ptr(), ld2=N))
+    torch.cuda.synchronize()
+    assert rel_err(to_host(Cd), AB * O.gelu_grad(R.astype(np.float64))) < tol
+    # fp32 accumulate: C32 += v, twice
+    C32 = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        ctx.gemm(stp.GemmArgs(**base | dict(ldc=N), C=C32.data_ptr(), c_f32_accum=1, bias_scale=1.0, resid_scale=1.0))
+    torch.cuda.synchronize()
+    assert rel_err(to_host(C32), 0.5 + 2 * AB) < (3e-6 if dtype == "f32" else 1e-5)
+
+
+def test_gemm_rejects_bad_arguments(ctx):
+    x = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
+    ok = dict(dtype=stp.BF16, M=64, N=64, K=64, A=x.data_ptr(), lda=64, B=x.data_ptr(), ldb=64, C=x.data_ptr(), ldc=64)
+    for bad, status in [(dict(M=63), 2), (dict(A=None), 1), (dict(A=x.data_ptr() + 2), 3), (dict(lda=32), 2),
+                        (dict(dtype=7), 1), (dict(epilogue=1), 1)]:
+        with pytest.raises(stp.StpError) as e:
+            ctx.gemm(stp.GemmArgs(**(ok | bad)))
+        assert e.value.status == status
+    ctx.gemm(stp.GemmArgs(**(ok | dict(M=0))))  # empty problem is a no-op
+
+
+# ------------------------------------------------------------------ norms
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("norm", ["ln", "rms"])
+@pytest.mark.parametrize("T,h", [(37, 256), (130, 4096), (64, 5120), (9, 1024), (5, 8), (600, 2056)])
+def test_norm_forward_backward(ctx, dtype, norm, T, h):
+    rng = np.random.default_rng(T + h)
+    cfg = O.LayerCfg(h, 1, 8, 8, norm=norm)
+    x = q(rng.standard_normal((T, h), dtype=np.float32) * 2 + 0.5, dtype)
+    gam = q(1 + 0.1 * rng.standard_normal(h, dtype=np.float32), dtype)
+    bet = q(0.1 * rng.standard_normal(h, dtype=np.float32), dtype)
+    dy = q(rng.standard_normal((T, h), dtype=np.float32), dtype)
+    dres = q(rng.standard_normal((T, h), dtype=np.float32), dtype)
+    xd, gd, bd, dyd, drd = (to_dev(v, dtype) for v in (x, gam, bet, dy, dres))
+    y = torch.empty_like(xd)
+    stats = torch.empty((T, 2), dtype=torch.float32, device="cuda")
+    code = stp.BF16 if dtype == "bf16" else stp.F32
+    ncode = stp.NORM_LN if norm == "ln" else stp.NORM_RMS
+    ctx.norm_forward(code, ncode, T, h, cfg.eps, xd, gd, bd if norm == "ln" else None, y, stats)
+    torch.cuda.synchronize()
+    ref = O.norm_fwd(cfg, x.astype(np.float64), gam.astype(np.float64), bet.astype(np.float64) if norm == "ln" else None)
+    tol = 8e-3 if dtype == "bf16" else 2e-6
+    assert rel_err(to_host(y), ref) < tol
+    dx = torch.empty_like(xd)
+    dgam = torch.full((h,), 1.0, dtype=torch.float32, device="cuda")
+    dbet = torch.full((h,), -1.0, dtype=torch.float32, device="cuda")
+    ctx.norm_backward(code, ncode, T, h, xd, gd, stats, dyd, drd, dx, dgam, dbet, lane=1)
+    torch.cuda.synchronize()
+    rdx, rdg, rdb = O.norm_bwd(cfg, dy.astype(np.float64), x.astype(np.float64), gam.astype(np.float64))
+    assert rel_err(to_host(dx), rdx + dres) < tol
+    assert rel_err(to_host(dgam), 1.0 + rdg) < 1e-5
+    if norm == "ln":
+        assert rel_err(to_host(dbet), -1.0 + rdb) < 1e-5
+    # no residual, no parameter gradients
+    ctx.norm_backward(code, ncode, T, h, xd, gd, stats, dyd, None, dx, None, None)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(dx), rdx) < tol
+
+
+# ------------------------------------------------------------------ activations, rope, colsum
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_activations(ctx, dtype):
+    n = 8 * 12345
+    rng = np.random.default_rng(1)
+    code = stp.BF16 if dtype == "bf16" else stp.F32
+    tol = 8e-3 if dtype == "bf16" else 2e-6
+    x, u, dy = (q(rng.standard_normal(n, dtype=np.float32) * 2, dtype) for _ in range(3))
+    xd, ud, dyd = (to_dev(v, dtype) for v in (x, u, dy))
+    y, y2 = torch.empty_like(xd), torch.empty_like(xd)
+    ctx.gelu_forward(code, n, xd, y)
+    ctx.gelu_backward(code, n, xd, dyd, y2)
+    torch.cuda.synchronize()
+    x64, u64, dy64 = (v.astype(np.float64) for v in (x, u, dy))
+    assert rel_err(to_host(y), O.gelu(x64)) < tol
+    assert rel_err(to_host(y2), dy64 * O.gelu_grad(x64)) < tol
+    ctx.swiglu_forward(code, n, xd, ud, y)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(y), O.silu(x64) * u64) < tol
+    ctx.swiglu_backward(code, n, xd, ud, dyd, y, y2)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(y), dy64 * u64 * O.silu_grad(x64)) < tol
+    assert rel_err(to_host(y2), dy64 * O.silu(x64)) < tol
+    ctx.gelu_forward(code, 0, xd, y)  # empty input
+    with pytest.raises(stp.StpError):
+        ctx.gelu_forward(code, 12, xd, y)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("seq,mbsz,n,d", [(104, 1, 3, 64), (64, 2, 2, 128), (8, 1, 1, 16)])
+def test_rope(ctx, dtype, seq, mbsz, n, d):
+    if dtype == "bf16" and d not in (64, 128):
+        pytest.skip("bf16 layers take head_dim 64 or 128")
+    rng = np.random.default_rng(seq)
+    a = n * d
+    T = seq * mbsz
+    x = q(rng.standard_normal((T, 3 * a), dtype=np.float32), dtype)
+    xd = to_dev(x, dtype)
+    wl = synth.Workload("r", 64, n, d, 64, seq, 1, dtype=dtype, rope=True)
+    desc = stp.make_desc(wl, mbsz=mbsz)
+    for inverse in (False, True):
+        buf = xd.clone()
+        ctx.rope(desc, buf, inverse=inverse)
+        torch.cuda.synchronize()
+        got = to_host(buf)
+        ref = x.astype(np.float64).copy()
+        for b in range(mbsz):
+            rows = slice(b * seq, (b + 1) * seq)
+            for part in (0, 1):
+                blk = ref[rows, part * a:(part + 1) * a].reshape(seq, n, d)
+                ref[rows, part * a:(part + 1) * a] = O.rope(blk, 10000.0, inverse).reshape(seq, a)
+        assert rel_err(got, ref) < (8e-3 if dtype == "bf16" else 3e-6)
+        np.testing.assert_array_equal(got[:, 2 * a:], x[:, 2 * a:])  # V untouched
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("T,N", [(200, 512), (64, 8), (1000, 1544)])
+def test_colsum(ctx, dtype, T, N):
+    rng = np.random.default_rng(T)
+    x = q(rng.standard_normal((T, N), dtype=np.float32), dtype)
+    xd = to_dev(x, dtype)
+    out = torch.full((N,), 2.0, dtype=torch.float32, device="cuda")
+    ctx.colsum(stp.BF16 if dtype == "bf16" else stp.F32, T, N, xd, 0.125, out, lane=2)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(out), 2.0 + 0.125 * x.astype(np.float64).sum(0)) < 1e-5
+
+
+# ------------------------------------------------------------------ attention core
+ATTN_CASES = [("f32", 128, 1, 4, 64, True), ("f32", 52, 2, 2, 32, False), ("f32", 72, 1, 1, 128, True),
+              ("bf16", 128, 1, 2, 128, True), ("bf16", 200, 1, 3, 128, True), ("bf16", 456, 2, 2, 64, True),
+              ("bf16", 328, 1, 2, 64, False), ("bf16", 1000, 1, 1, 128, False), ("bf16", 8, 1, 1, 128, True)]
+
+
+@pytest.mark.parametrize("dtype,seq,mbsz,n,d,causal", ATTN_CASES)
+def test_attention_forward_backward(ctx, dtype, seq, mbsz, n, d, causal):
+    rng = np.random.default_rng(seq * 3 + d)
+    a, T = n * d, seq * mbsz
+    qkv = q(rng.standard_normal((T, 3 * a), dtype=np.float32), dtype)
+    dctx = q(rng.standard_normal((T, a), dtype=np.float32), dtype)
+    qkvd, dctxd = to_dev(qkv, dtype), to_dev(dctx, dtype)
+    wl = synth.Workload("a", 64, n, d, 64, seq, 1, dtype=dtype, causal=causal)
+    desc = stp.make_desc(wl, mbsz=mbsz)
+    out = torch.zeros((T, a), dtype=qkvd.dtype, device="cuda")
+    lse = torch.zeros((mbsz, n, seq), dtype=torch.float32, device="cuda")
+    delta = torch.zeros_like(lse)
+    dqkv = torch.zeros_like(qkvd)
+    ctx.attention_forward(desc, qkvd, out, lse)
+    ctx.attention_backward(desc, qkvd, out, lse, dctxd, delta, dqkv)
+    torch.cuda.synchronize()
+    tol = 1e-2 if dtype == "bf16" else 3e-6
+    q64 = qkv.astype(np.float64)
+    got_o, got_d, got_l = to_host(out), to_host(dqkv), to_host(lse)
+    for b in range(mbsz):
+        rows = slice(b * seq, (b + 1) * seq)
+        Q, K, V = (q64[rows, i * a:(i + 1) * a].reshape(seq, n, d) for i in range(3))
+        ref = O.attention_fwd(Q, K, V, causal)
+        assert rel_err(got_o[rows], ref.reshape(seq, a)) < tol
+        dq, dk, dv = O.attention_bwd(Q, K, V, dctx.astype(np.float64)[rows].reshape(seq, n, d), causal)
+        ref_d = np.concatenate([x.reshape(seq, a) for x in (dq, dk, dv)], axis=1)
+        for part, name in enumerate("qkv"):
+            sl = slice(part * a, (part + 1) * a)
+            assert rel_err(got_d[rows, sl], ref_d[:, sl]) < tol, name
+        for hd in range(n):  # log-sum-exp of the scaled, masked scores
+            S = Q[:, hd] @ K[:, hd].T / math.sqrt(d)
+            if causal:
+                S = np.where(np.tril(np.ones((seq, seq), bool)), S, -np.inf)
+            mx = S.max(1)
+            ref_l = mx + np.log(np.exp(S - mx[:, None]).sum(1))
+            assert np.max(np.abs(got_l[b, hd] - ref_l)) < (2e-2 if dtype == "bf16" else 1e-5)
