@@ -1,0 +1,161 @@
+"""Device-side container for one pipeline stage's model chunk (Section 4.2): per-layer weights
+and gradient accumulators, per (layer, microbatch) stashes, the activation / gradient slots
+between layers, and the ctypes tables stp_braid_step reads.  Also the canonical op lists of the
+braided blocks.  Argument marshalling and torch allocations only: no arithmetic of the method."""
+from __future__ import annotations
+
+import ctypes as C
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+from . import synth
+
+
+def _to_dev(x, dtype: str) -> torch.Tensor:
+    import numpy as np
+    if dtype == "bf16":
+        bits = synth.to_bf16_bits(x).view(np.int16)
+        return torch.from_numpy(bits.copy()).cuda().view(torch.bfloat16).reshape(x.shape)
+    return torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda()
+
+
+class StageOnDevice:
+    def __init__(self, ctx: B.Context, layers: Sequence[synth.Workload], n_mb: int, seed: int = 0,
+                 chain_break: Optional[Sequence[int]] = None):
+        self.ctx, self.layers, self.n_mb, self.seed = ctx, list(layers), n_mb, seed
+        L = len(self.layers)
+        self.descs = (B.LayerDesc * L)(*[B.make_desc(wl) for wl in self.layers])
+        self.w_host, self.w_dev, self.g_dev = [], [], []
+        w_arr, g_arr = (B.Weights * L)(), (B.WGrads * L)()
+        for l, wl in enumerate(self.layers):
+            wh = synth.make_weights(wl, seed, l)
+            wd = {k: _to_dev(v, wl.dtype) for k, v in wh.items()}
+            gd = {k: torch.zeros(v.shape, dtype=torch.float32, device="cuda") for k, v in wh.items()}
+            self.w_host.append(wh); self.w_dev.append(wd); self.g_dev.append(gd)
+            w_arr[l] = B.Weights(**{k: v.data_ptr() for k, v in wd.items()})
+            g_arr[l] = B.WGrads(**{k: v.data_ptr() for k, v in gd.items()})
+        self.w_arr, self.g_arr = w_arr, g_arr
+        self.stash_mem, stash_arr = [], (B.Stash * (L * n_mb))()
+        for l in range(L):
+            nbytes = ctx.stash_bytes(self.descs[l])
+            for mb in range(n_mb):
+                m = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+                self.stash_mem.append(m)
+                stash_arr[l * n_mb + mb] = B.Stash(base=m.data_ptr(), bytes=nbytes)
+        self.stash_arr = stash_arr
+        self.chain_break = list(chain_break) if chain_break is not None else [0] * (L + 1)
+        # slot l holds the input of layer l; at a chain break the slot of layer l is an independent input
+        # and the previous chain's output goes to a separate tensor kept in out_of_chain
+        self.act, self.grad = [], []
+        act_arr, grad_arr = (C.c_void_p * ((L + 1) * n_mb))(), (C.c_void_p * ((L + 1) * n_mb))()
+        for l in range(L + 1):
+            wl = self.layers[min(l, L - 1)]
+            if l == L or (l > 0 and not self.chain_break[l]):
+                wl_shape = self.layers[l - 1] if l > 0 else wl
+            else:
+                wl_shape = wl
+            td = torch.bfloat16 if wl_shape.dtype == "bf16" else torch.float32
+            for mb in range(n_mb):
+                a = torch.zeros((wl_shape.seq, wl_shape.hidden), dtype=td, device="cuda")
+                g = torch.zeros_like(a)
+                self.act.append(a); self.grad.append(g)
+                act_arr[l * n_mb + mb] = a.data_ptr()
+                grad_arr[l * n_mb + mb] = g.data_ptr()
+        self.act_arr, self.grad_arr = act_arr, grad_arr
+        self.cb_arr = (C.c_int32 * (L + 1))(*self.chain_break)
+        self.stage = B.Stage(n_layers=L, n_microbatches=n_mb, desc=self.descs, w=w_arr, g=g_arr, stash=stash_arr,
+                             act=act_arr, grad=grad_arr, chain_break=self.cb_arr)
+        ctx.ensure_workspace(list(self.descs))
+
+    # ---- slots ----------------------------------------------------------------
+    def act_slot(self, l: int, mb: int) -> torch.Tensor:
+        return self.act[l * self.n_mb + mb]
+
+    def grad_slot(self, l: int, mb: int) -> torch.Tensor:
+        return self.grad[l * self.n_mb + mb]
+
+    def field(self, l: int, mb: int, name: str) -> torch.Tensor:
+        off, n = self.ctx.stash_field(self.descs[l], name)
+        raw = self.stash_mem[l * self.n_mb + mb][off:off + n]
+        if name in ("STATS1", "STATS2", "LSE", "DELTA"):
+            return raw.view(torch.float32)
+        return raw.view(torch.bfloat16 if self.layers[l].dtype == "bf16" else torch.float32)
+
+    def load_inputs(self):
+        """Seeded N(0,1) stage inputs (slot 0) and upstream gradients (slot L) for every microbatch."""
+        L = len(self.layers)
+        for mb in range(self.n_mb):
+            x = synth.make_activation(self.layers[0], self.seed, f"x.mb{mb}")
+            dy = synth.make_activation(self.layers[-1], self.seed, f"dy.mb{mb}")
+            self.act_slot(0, mb).copy_(_to_dev(x, self.layers[0].dtype))
+            self.grad_slot(L, mb).copy_(_to_dev(dy, self.layers[-1].dtype))
+
+    def zero_grads(self):
+        for gd in self.g_dev:
+            for v in gd.values():
+                v.zero_()
+
+
+# ---- op lists -------------------------------------------------------------------
+def forward_ops(n_layers: int, mb: int) -> List[B.Op]:
+    return [B.Op(B.OP_F, u, l, mb) for l in range(n_layers) for u in (B.PRE_ATTN, B.ATTN, B.PRE_MLP, B.MLP)]
+
+
+def backward_ops(n_layers: int, mb: int, kind: int = B.OP_BW) -> List[B.Op]:
+    return [B.Op(kind, u, l, mb) for l in reversed(range(n_layers)) for u in (B.MLP, B.PRE_MLP, B.ATTN, B.PRE_ATTN)]
+
+
+def weight_ops(n_layers: int, mb: int) -> List[B.Op]:
+    return [B.Op(B.OP_W, u, l, mb) for l in reversed(range(n_layers)) for u in (B.MLP, B.ATTN)]
+
+
+def braid(f_ops: List[B.Op], b_ops: List[B.Op]) -> List[B.Op]:
+    """Interleaves a forward and a backward-side list so that the direction changes at every
+    TP boundary (Fig. 3): F.PreAttn F.Attn | B.MLP | F.PreMLP F.MLP | B.PreMLP B.Attn | B.PreAttn ...
+    W ops in b_ops ride along with the group they are listed in."""
+    def groups(ops, enders):
+        out, cur = [], []
+        only_w = all(o.kind == B.OP_W for o in ops)
+        for o in ops:
+            cur.append(o)
+            if only_w or (o.unit in enders and o.kind != B.OP_W):
+                out.append(cur); cur = []
+        if cur:
+            out.append(cur)
+        return out
+    fg = groups(f_ops, (B.ATTN, B.MLP))
+    bg = groups(b_ops, (B.MLP, B.ATTN))
+    out = []
+    for i in range(max(len(fg), len(bg))):
+        if i < len(fg):
+            out += fg[i]
+        if i < len(bg):
+            out += bg[i]
+    return out
+
+
+def stage_sequence(n_layers: int, n_mb: int) -> List[List[B.Op]]:
+    """One stage's projection of the three-phase schedule (Section 4.2), as a list of braid steps
+    exercising every block kind the paper names: warm-up F, F&B with W separated, F&W, steady
+    F&BW (W separation off), degraded BW / B, cool-down W.  For 8 microbatches:
+        F0; F1|B0; F2|B1; F3|W0; F4|BW2; F5|BW3; F6|BW4; F7|BW5; BW6; B7; W1; W7
+    Shorter runs keep the same pattern truncated."""
+    F = lambda i: forward_ops(n_layers, i)
+    Bk = lambda j, k: backward_ops(n_layers, j, k)
+    W = lambda j: weight_ops(n_layers, j)
+    if n_mb < 4:
+        steps = [F(0)]
+        for i in range(1, n_mb):
+            steps.append(braid(F(i), Bk(i - 1, B.OP_BW)))
+        steps.append(Bk(n_mb - 1, B.OP_BW))
+        return steps
+    steps = [F(0), braid(F(1), Bk(0, B.OP_B)), braid(F(2), Bk(1, B.OP_B)), braid(F(3), W(0))]
+    for i in range(4, n_mb):
+        steps.append(braid(F(i), Bk(i - 2, B.OP_BW)))
+    steps.append(Bk(n_mb - 2, B.OP_BW))
+    steps.append(Bk(n_mb - 1, B.OP_B))
+    steps.append(W(1))
+    steps.append(W(n_mb - 1))
+    return steps

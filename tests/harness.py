@@ -71,3 +71,39 @@ class LayerOnDevice:
 
     def w64(self):
         return {k: v.astype(np.float64) for k, v in self.w_host.items()}
+
+
+def gpu_layer_pass(ctx, lay: LayerOnDevice, X: torch.Tensor, dO: torch.Tensor, mb: int = 0, stream=None):
+    """F units, then B units, then W units of one rank with identity at the AR points."""
+    d, w, st = lay.desc, lay.w, lay.stash[mb]
+    out = {k: lay.new_act() for k in ("x_attn", "x_out", "dz", "dx_attn", "dx_ln", "dx")}
+    ctx.forward_unit(d, stp.PRE_ATTN, w, st, x_in=X, stream=stream)
+    ctx.forward_unit(d, stp.ATTN, w, st, x_resid=X, y_out=out["x_attn"], stream=stream)
+    ctx.forward_unit(d, stp.PRE_MLP, w, st, x_in=out["x_attn"], stream=stream)
+    ctx.forward_unit(d, stp.MLP, w, st, x_resid=out["x_attn"], y_out=out["x_out"], stream=stream)
+    ctx.backward_input_unit(d, stp.MLP, w, st, dy=dO, dx=out["dz"], stream=stream)
+    ctx.backward_input_unit(d, stp.PRE_MLP, w, st, x_in=out["x_attn"], dy=out["dz"], d_resid=dO, dx=out["dx_attn"],
+                            wgrads=lay.g, stream=stream)
+    ctx.backward_input_unit(d, stp.ATTN, w, st, dy=out["dx_attn"], dx=out["dx_ln"], stream=stream)
+    ctx.backward_input_unit(d, stp.PRE_ATTN, w, st, x_in=X, dy=out["dx_ln"], d_resid=out["dx_attn"], dx=out["dx"],
+                            wgrads=lay.g, stream=stream)
+    ctx.backward_weight_unit(d, stp.MLP, st, dO, lay.g, stream=stream)
+    ctx.backward_weight_unit(d, stp.ATTN, st, out["dx_attn"], lay.g, stream=stream)
+    return out
+
+
+def oracle_layer_pass(cfg: O.LayerCfg, W: dict, X: np.ndarray, dO: np.ndarray, grads: dict = None):
+    """The same sequence in the fp64 oracle; returns activations, stash and gradients."""
+    st, g = {}, ({} if grads is None else grads)
+    r = {}
+    O.forward_unit(cfg, O.PRE_ATTN, W, st, x_in=X)
+    r["x_attn"] = O.forward_unit(cfg, O.ATTN, W, st, x_resid=X)
+    O.forward_unit(cfg, O.PRE_MLP, W, st, x_in=r["x_attn"])
+    r["x_out"] = O.forward_unit(cfg, O.MLP, W, st, x_resid=r["x_attn"])
+    r["dz"] = O.backward_input_unit(cfg, O.MLP, W, st, dO)
+    r["dx_attn"] = O.backward_input_unit(cfg, O.PRE_MLP, W, st, r["dz"], d_resid=dO, grads=g)
+    r["dx_ln"] = O.backward_input_unit(cfg, O.ATTN, W, st, r["dx_attn"])
+    r["dx"] = O.backward_input_unit(cfg, O.PRE_ATTN, W, st, r["dx_ln"], d_resid=r["dx_attn"], grads=g)
+    O.backward_weight_unit(cfg, O.MLP, st, dO, g)
+    O.backward_weight_unit(cfg, O.ATTN, st, r["dx_attn"], g)
+    return r, st, g

@@ -1,0 +1,131 @@
+"""The braided block on the GPU: same bits as the serialized order, parity with the oracle over a
+multi-layer, multi-microbatch stage sequence, boundary callbacks, W-before-B rejection."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2510_27257_amd as stp
+from paper_2510_27257_amd import synth
+from paper_2510_27257_amd.binding import Op, OP_F, OP_B, OP_W, OP_BW, PRE_ATTN, ATTN, PRE_MLP, MLP
+from paper_2510_27257_amd.stage import StageOnDevice, stage_sequence, braid, forward_ops, backward_ops
+from paper_2510_27257_amd.synth import Workload
+from oracle import stp_oracle as O
+from harness import TOL, oracle_cfg, oracle_layer_pass, rel_err, to_host
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = stp.Context(0)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def run_sequence(ctx, stg, streams):
+    ctx.braid_reset()
+    stg.zero_grads()
+    for step in stage_sequence(len(stg.layers), stg.n_mb):
+        ctx.braid_step(stg.stage, step, *streams)
+    torch.cuda.synchronize()
+
+
+def snapshot(stg):
+    out = [t.clone() for t in stg.act] + [t.clone() for t in stg.grad]
+    for gd in stg.g_dev:
+        out += [gd[k].clone() for k in sorted(gd)]
+    return out
+
+
+STAGES = {
+    "tiny_fp32_x2": ([synth.WORKLOADS["tiny"]] * 2, 4),
+    "gpt_bf16_x2": ([Workload("g", 512, 2, 128, 1024, 264, 8)] * 2, 5),
+    "llama_bf16_x1": ([Workload("l", 384, 3, 64, 520, 136, 4, norm="rms", act="swiglu", rope=True, has_bias=False)], 4),
+}
+
+
+@pytest.mark.parametrize("name", list(STAGES))
+def test_braided_equals_serialized_bitwise_and_matches_oracle(ctx, name):
+    layers, n_mb = STAGES[name]
+    stg = StageOnDevice(ctx, layers, n_mb, seed=2)
+    stg.load_inputs()
+    s0 = torch.cuda.current_stream()
+    run_sequence(ctx, stg, (s0, s0, s0))
+    serial = snapshot(stg)
+    sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(2):
+        run_sequence(ctx, stg, (sF, sB, sW))
+        for a, b in zip(serial, snapshot(stg)):
+            assert torch.equal(a, b), f"{name}: braided run {rep} differs from the serialized order"
+    # oracle: chain the layers with identity at the AR points, accumulate weight grads over microbatches
+    L = len(layers)
+    tol = TOL[layers[0].dtype]
+    g_ref = [dict() for _ in range(L)]
+    for mb in range(n_mb):
+        xs = [synth.make_activation(layers[0], 2, f"x.mb{mb}").astype(np.float64)]
+        stashes = []
+        for l in range(L):
+            cfg, W = oracle_cfg(layers[l]), {k: v.astype(np.float64) for k, v in stg.w_host[l].items()}
+            st = {}
+            O.forward_unit(cfg, O.PRE_ATTN, W, st, x_in=xs[-1])
+            xa = O.forward_unit(cfg, O.ATTN, W, st, x_resid=xs[-1])
+            O.forward_unit(cfg, O.PRE_MLP, W, st, x_in=xa)
+            xs.append(O.forward_unit(cfg, O.MLP, W, st, x_resid=xa))
+            stashes.append(st)
+        assert rel_err(to_host(stg.act_slot(L, mb)), xs[-1]) < tol
+        dy = synth.make_activation(layers[-1], 2, f"dy.mb{mb}").astype(np.float64)
+        for l in reversed(range(L)):
+            cfg, W = oracle_cfg(layers[l]), {k: v.astype(np.float64) for k, v in stg.w_host[l].items()}
+            st = stashes[l]
+            dz = O.backward_input_unit(cfg, O.MLP, W, st, dy)
+            dxa = O.backward_input_unit(cfg, O.PRE_MLP, W, st, dz, d_resid=dy, grads=g_ref[l])
+            dxl = O.backward_input_unit(cfg, O.ATTN, W, st, dxa)
+            dx = O.backward_input_unit(cfg, O.PRE_ATTN, W, st, dxl, d_resid=dxa, grads=g_ref[l])
+            O.backward_weight_unit(cfg, O.MLP, st, dy, g_ref[l])
+            O.backward_weight_unit(cfg, O.ATTN, st, dxa, g_ref[l])
+            dy = dx
+        assert rel_err(to_host(stg.grad_slot(0, mb)), dy) < tol
+    for l in range(L):
+        for k, r in g_ref[l].items():
+            assert rel_err(to_host(stg.g_dev[l][k]), r) < tol, (l, k)
+
+
+def test_boundary_callback_sees_every_all_reduce_point(ctx):
+    stg = StageOnDevice(ctx, [synth.WORKLOADS["tiny"]] * 2, 2, seed=1)
+    stg.load_inputs()
+    seen = []
+
+    @stp.BOUNDARY_FN
+    def cb(user, which, buf, nbytes, layer, mb, stream):
+        seen.append((which, layer, mb, nbytes))
+
+    s = torch.cuda.current_stream()
+    ctx.braid_reset()
+    ctx.braid_step(stg.stage, forward_ops(2, 0), s, s, s, cb=cb)
+    ctx.braid_step(stg.stage, braid(forward_ops(2, 1), backward_ops(2, 0, OP_BW)), s, s, s, cb=cb)
+    torch.cuda.synchronize()
+    nbytes = 128 * 256 * 4
+    assert seen[:4] == [(0, 0, 0, nbytes), (1, 0, 0, nbytes), (0, 1, 0, nbytes), (1, 1, 0, nbytes)]
+    second = seen[4:]
+    assert second == [(0, 0, 1, nbytes), (2, 1, 0, nbytes), (1, 0, 1, nbytes), (3, 1, 0, nbytes),
+                      (0, 1, 1, nbytes), (2, 0, 0, nbytes), (1, 1, 1, nbytes), (3, 0, 0, nbytes)]
+
+
+def test_weight_unit_before_its_backward_is_rejected(ctx):
+    stg = StageOnDevice(ctx, [synth.WORKLOADS["tiny"]], 2, seed=1)
+    stg.load_inputs()
+    s = torch.cuda.current_stream()
+    ctx.braid_reset()
+    ctx.braid_step(stg.stage, forward_ops(1, 0), s, s, s)
+    with pytest.raises(stp.StpError) as e:
+        ctx.braid_step(stg.stage, [Op(OP_W, MLP, 0, 0)], s, s, s)
+    assert e.value.status == 5
+    ctx.braid_step(stg.stage, backward_ops(1, 0, OP_B), s, s, s)
+    ctx.braid_step(stg.stage, [Op(OP_W, MLP, 0, 0), Op(OP_W, ATTN, 0, 0)], s, s, s)   # now legal
+    ctx.braid_reset()
+    with pytest.raises(stp.StpError):
+        ctx.braid_step(stg.stage, [Op(OP_W, MLP, 0, 0)], s, s, s)
+    torch.cuda.synchronize()
