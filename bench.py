@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the braided F/B/W units of one TP shard on one MI355X.
+
+A "step" is one braided execution block (paper Section 3, Fig. 3a): the four forward units
+of microbatch 1 interleaved with the full backward (B and W units) of microbatch 0 of the
+same layer, on three HIP streams.  One step therefore performs exactly the F + B + W work of
+one layer-microbatch.  Headline workload: GPT-7B-style layer, TP=8 shard (hidden 4096, 4 of 32
+heads x 128, FFN shard 2048), sequence 6144, microbatch 1, bf16 storage with fp32 accumulation.
+
+Prints one JSON line (see the repository's design notes for the field definitions).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak (256 CU x 4096 flop/clk x 2.4 GHz ~ 2.5e15)
+
+
+def unit_flops(wl):
+    """Algorithmic flops of the F, B and W units of one layer-microbatch: GEMMs as 2MNK; causal
+    attention counts only the unmasked pairs s(s+1)/2; attention backward counts its four
+    matmuls (no recomputation)."""
+    T, h, a, f = wl.seq, wl.hidden, wl.attn_local, wl.ffn_local
+    pairs = T * (T + 1) // 2 if wl.causal else T * T
+    n_in = 2 if wl.act == "swiglu" else 1
+    qkv, outp = 2 * T * h * 3 * a, 2 * T * a * h
+    fc1, fc2 = n_in * 2 * T * h * f, 2 * T * f * h
+    F = qkv + 4 * a * pairs + outp + fc1 + fc2
+    B = fc2 + fc1 + outp + 8 * a * pairs + qkv
+    W = fc2 + fc1 + outp + qkv
+    return {"F": F, "B": B, "W": W, "gemm_fwd": [qkv, outp, fc1 // n_in, fc2]}
+
+
+def time_steps(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gpt7b_tp8")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the TP all-reduce points are marked boundaries, "
+              "no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2510_27257_amd as stp
+    from paper_2510_27257_amd import synth
+    from paper_2510_27257_amd.binding import OP_B, OP_BW
+    from paper_2510_27257_amd.stage import StageOnDevice, backward_ops, braid, forward_ops, weight_ops
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (no CPU fallback exists)")
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    fl = unit_flops(wl)
+    total_flops = fl["F"] + fl["B"] + fl["W"]
+
+    ctx = stp.Context(0)
+    stg = StageOnDevice(ctx, [wl], n_mb=2, seed=0)
+    stg.load_inputs()
+    sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    s0 = torch.cuda.current_stream()
+
+    # prime: forward of microbatch 0 leaves the stash its backward needs
+    ctx.braid_reset()
+    ctx.braid_step(stg.stage, forward_ops(1, 0), s0, s0, s0)
+    torch.cuda.synchronize()
+    step_ops = braid(forward_ops(1, 1), backward_ops(1, 0, OP_BW))
+    arr = (stp.Op * len(step_ops))(*step_ops)
+
+    # ---- the timed region: K braided steps ------------------------------------------
+    ms_braided = time_steps(lambda: ctx.braid_step(stg.stage, arr, sF, sB, sW), args.steps, args.warmup, torch)
+
+    # ---- the same op list on one stream, and the isolated units ----------------------
+    ms_serial = time_steps(lambda: ctx.braid_step(stg.stage, arr, s0, s0, s0), args.steps, args.warmup, torch)
+    f_ops = (stp.Op * 4)(*forward_ops(1, 1))
+    b_ops = (stp.Op * 4)(*backward_ops(1, 0, OP_B))
+    w_ops = (stp.Op * 2)(*weight_ops(1, 0))
+    ms_F = time_steps(lambda: ctx.braid_step(stg.stage, f_ops, s0, s0, s0), args.steps, args.warmup, torch)
+    ms_B = time_steps(lambda: ctx.braid_step(stg.stage, b_ops, s0, s0, s0), args.steps, args.warmup, torch)
+    ms_W = time_steps(lambda: ctx.braid_step(stg.stage, w_ops, s0, s0, s0), args.steps, args.warmup, torch)
+
+    # ---- dominant kernel: the bf16 MFMA GEMM in its forward layout (A row-major, B = W[in,out]).
+    # Its four launches per step (QKV, out-proj, FC1, FC2) are replayed alone on the current
+    # stream between HIP events recorded on that same stream.
+    T, h, a, f = wl.seq, wl.hidden, wl.attn_local, wl.ffn_local
+    td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    code = stp.BF16 if wl.dtype == "bf16" else stp.F32
+    shapes = [(T, 3 * a, h), (T, h, a), (T, f, h), (T, h, f)]
+    bufs = []
+    for (M, N, K) in shapes:
+        A = torch.randn((M, K), device="cuda").to(td)
+        Bm = (torch.randn((K, N), device="cuda") * 0.02).to(td)
+        Cm = torch.empty((M, N), device="cuda", dtype=td)
+        bufs.append((stp.GemmArgs(dtype=code, M=M, N=N, K=K, A=A.data_ptr(), lda=K, B=Bm.data_ptr(), ldb=N,
+                                  C=Cm.data_ptr(), ldc=N, bias_scale=1.0, resid_scale=1.0), A, Bm, Cm))
+    reps = max(10, args.steps)
+    for g, *_ in bufs:
+        ctx.gemm(g)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        for g, *_ in bufs:
+            ctx.gemm(g)
+    e1.record()
+    torch.cuda.synchronize()
+    gemm_avg_ms = e0.elapsed_time(e1) / (reps * len(bufs))
+    gemm_flops_per_launch = sum(2 * M * N * K for (M, N, K) in shapes) / len(shapes)
+    achieved = gemm_flops_per_launch / (gemm_avg_ms * 1e-3) / 1e12
+
+    result = {
+        "metric": "braided F/B/W TFLOP/s, 7B layer TP=8 shard, seq 6144, 1 GPU",
+        "value": total_flops / (ms_braided * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_braided,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: hidden {h}, {wl.heads_local} local heads x {wl.head_dim}, ffn shard {f}, "
+                               f"seq {T}, microbatch 1, tp {wl.tp}; step = F(mb1) braided with B+W(mb0), 1 layer",
+                   "flops_per_step": total_flops},
+        "mfma_util_frac_of_bf16_peak": total_flops / (ms_braided * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
+        "units": {
+            "F": {"ms": ms_F, "tflops": fl["F"] / (ms_F * 1e-3) / 1e12},
+            "B": {"ms": ms_B, "tflops": fl["B"] / (ms_B * 1e-3) / 1e12},
+            "W": {"ms": ms_W, "tflops": fl["W"] / (ms_W * 1e-3) / 1e12},
+        },
+        "braid": {"makespan_ms": ms_braided, "serialized_ms": ms_serial, "sum_isolated_ms": ms_F + ms_B + ms_W,
+                  "makespan_over_sum_isolated": ms_braided / (ms_F + ms_B + ms_W)},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel<256,256,A k-contiguous,B row-contiguous>",
+                     "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "avg_launch_ms": gemm_avg_ms,
+                     "flops_per_launch": gemm_flops_per_launch, "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        # the fp64 oracle, as it stands, on this machine's host cores: one full layer-microbatch (F+B+W)
+        import numpy as np
+        from oracle import stp_oracle as O
+        cfg = O.LayerCfg(hidden=h, heads_local=wl.heads_local, head_dim=wl.head_dim, ffn_local=f, tp=wl.tp,
+                         norm=wl.norm, act=wl.act, causal=wl.causal, rope=wl.rope, has_bias=wl.has_bias,
+                         eps=wl.eps, rope_base=wl.rope_base)
+        W64 = {k: v.astype(np.float64) for k, v in stg.w_host[0].items()}
+        X = synth.make_activation(wl, 0, "x.mb0").astype(np.float64)
+        dO = synth.make_activation(wl, 0, "dy.mb0").astype(np.float64)
+        t0 = time.perf_counter()
+        st, g = {}, {}
+        O.forward_unit(cfg, O.PRE_ATTN, W64, st, x_in=X)
+        xa = O.forward_unit(cfg, O.ATTN, W64, st, x_resid=X)
+        O.forward_unit(cfg, O.PRE_MLP, W64, st, x_in=xa)
+        O.forward_unit(cfg, O.MLP, W64, st, x_resid=xa)
+        dz = O.backward_input_unit(cfg, O.MLP, W64, st, dO)
+        dxa = O.backward_input_unit(cfg, O.PRE_MLP, W64, st, dz, d_resid=dO, grads=g)
+        dxl = O.backward_input_unit(cfg, O.ATTN, W64, st, dxa)
+        O.backward_input_unit(cfg, O.PRE_ATTN, W64, st, dxl, d_resid=dxa, grads=g)
+        O.backward_weight_unit(cfg, O.MLP, st, dO, g)
+        O.backward_weight_unit(cfg, O.ATTN, st, dxa, g)
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": total_flops / cpu_s / 1e12, "unit": "TFLOP/s",
+                                  "cores": len(os.sched_getaffinity(0)), "kind": "oracle",
+                                  "sample": "one full layer-microbatch (F+B+W units, all of the step's work) of the "
+                                            "same workload in numpy fp64", "seconds": cpu_s}
+    print(json.dumps(result))
+    torch.cuda.synchronize()
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()
