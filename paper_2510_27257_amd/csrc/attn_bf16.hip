@@ -63,11 +63,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(const bf16_t *__r
                                                                float scale_log2) {
   using G = AttnGeom<D>;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  bf16_t *ks[2], *vs[2];
-  ks[0] = reinterpret_cast<bf16_t *>(smem_raw);
-  ks[1] = ks[0] + G::k_elems;
-  vs[0] = ks[1] + G::k_elems;
-  vs[1] = vs[0] + G::v_elems;
+  // stage s: K tile at s*STAGE, V tile at s*STAGE + k_elems (offsets from the LDS base, no pointer tables)
+  constexpr int STAGE = G::k_elems + G::v_elems;
+  bf16_t *const sbase = reinterpret_cast<bf16_t *>(smem_raw);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lg = lane >> 5;
@@ -101,11 +99,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(const bf16_t *__r
 
   uint4 rk[G::nld], rv[G::nld];
   kv_load<D>(rk, rv, kbase, ld, 0, seq, tid);
-  kv_store<D>(rk, rv, ks[0], vs[0], tid);
+  kv_store<D>(rk, rv, sbase, sbase + G::k_elems, tid);
   __syncthreads();
 
   for (int kb = 0; kb < nkb; kb++) {
     const int cur = kb & 1;
+    const bf16_t *ks_cur = sbase + cur * STAGE, *vs_cur = ks_cur + G::k_elems;
     const int kv0 = kb * KB;
     if (kb + 1 < nkb) kv_load<D>(rk, rv, kbase, ld, kv0 + KB, seq, tid);
 
@@ -120,7 +119,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(const bf16_t *__r
         for (int v = 0; v < 16; v++) st[jb][v] = 0.f;
 #pragma unroll
         for (int s = 0; s < D / 16; s++) {
-          bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(ks[cur] + (32 * jb + lr) * G::kp + 16 * s + 8 * lg);
+          bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(ks_cur + (32 * jb + lr) * G::kp + 16 * s + 8 * lg);
           st[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], st[jb], 0, 0, 0);
         }
       }
@@ -171,7 +170,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(const bf16_t *__r
           const int krow = 32 * jb + 16 * t + 4 * lg + ((lane & 15) >> 2);
 #pragma unroll
           for (int db = 0; db < D / 32; db++) {
-            const bf16_t *p = vs[cur] + krow * G::vp + 32 * db + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+            const bf16_t *p = vs_cur + krow * G::vp + 32 * db + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
             s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
             s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 8 * G::vp));
             s16x8_t vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -179,7 +178,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(const bf16_t *__r
           }
         }
     }
-    if (kb + 1 < nkb) kv_store<D>(rk, rv, ks[cur ^ 1], vs[cur ^ 1], tid);
+    if (kb + 1 < nkb) kv_store<D>(rk, rv, sbase + (cur ^ 1) * STAGE, sbase + (cur ^ 1) * STAGE + G::k_elems, tid);
     __syncthreads();
   }
 
@@ -222,10 +221,4 @@ int stp_launch_attn_fwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *
   if (d->head_dim == 128) return launch_fwd<128>(ctx, d, qkv, out, lse, s);
   if (d->head_dim == 64) return launch_fwd<64>(ctx, d, qkv, out, lse, s);
   return stp_fail(ctx, STP_ESHAPE, "bf16 attention needs head_dim 64 or 128%s");
-}
-
-// TEMPORARY: backward through the plain kernels until the MFMA backward lands.
-int stp_launch_attn_bwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const void *out, const float *lse,
-                             const void *dout, float *delta, void *dqkv, hipStream_t s) {
-  return stp_launch_attn_bwd_generic(ctx, d, qkv, out, lse, dout, delta, dqkv, s);
 }

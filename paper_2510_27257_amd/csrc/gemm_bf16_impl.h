@@ -39,14 +39,16 @@ template <int ROWS, bool KC> struct TileGeom {
 
 // Loads this thread's share of a ROWS x 64 operand tile from global memory into registers.
 // KC: memory is [row][k] (ld = row pitch);  !KC: memory is [k][row].  Out-of-range chunks are
-// read from the (always valid) first element and replaced by zeros: no divergent branches.
+// read from the (always valid) first element; bit i of the returned mask says chunk i is real.
+// The zero-fill happens when the registers are written to LDS, after the MFMAs of the current
+// tile, so that all loads stay in flight together (no wait between them).
 template <int ROWS, bool KC, int NREG>
-__device__ __forceinline__ void tile_load(uint4 (&reg)[NREG], const bf16_t *__restrict__ base,
-                                          int ld, int row0, int row_lim, int k0, int k_lim, int tid) {
-  constexpr int NT = NREG;
+__device__ __forceinline__ unsigned tile_load(uint4 (&reg)[NREG], const bf16_t *__restrict__ base,
+                                              int ld, int row0, int row_lim, int k0, int k_lim, int tid) {
   static_assert(NREG == TileGeom<ROWS, KC>::per_thread, "register tile size");
+  unsigned mask = 0;
 #pragma unroll
-  for (int i = 0; i < NT; i++) {
+  for (int i = 0; i < NREG; i++) {
     int q = tid + 256 * i;
     int r, k;
     if (KC) { r = q >> 3; k = (q & 7) * 8; }
@@ -54,24 +56,26 @@ __device__ __forceinline__ void tile_load(uint4 (&reg)[NREG], const bf16_t *__re
     const bool ok = (row0 + r < row_lim) && (k0 + k < k_lim);
     size_t off = KC ? (size_t)(row0 + r) * ld + (k0 + k) : (size_t)(k0 + k) * ld + (row0 + r);
     off = ok ? off : 0;
-    uint4 v = *reinterpret_cast<const uint4 *>(base + off);
-    reg[i].x = ok ? v.x : 0u; reg[i].y = ok ? v.y : 0u; reg[i].z = ok ? v.z : 0u; reg[i].w = ok ? v.w : 0u;
+    mask |= ok ? (1u << i) : 0u;
+    reg[i] = *reinterpret_cast<const uint4 *>(base + off);
   }
+  return mask;
 }
 
 template <int ROWS, bool KC, int NREG>
-__device__ __forceinline__ void tile_store(const uint4 (&reg)[NREG], bf16_t *lds, int tid) {
-  constexpr int NT = NREG;
-  static_assert(NREG == TileGeom<ROWS, KC>::per_thread, "register tile size");
+__device__ __forceinline__ void tile_store(const uint4 (&reg)[NREG], unsigned mask, bf16_t *lds, int tid) {
   constexpr int P = TileGeom<ROWS, KC>::pitch;
 #pragma unroll
-  for (int i = 0; i < NT; i++) {
+  for (int i = 0; i < NREG; i++) {
     int q = tid + 256 * i;
     int r, k;
     if (KC) { r = q >> 3; k = (q & 7) * 8; }
     else { k = q / (ROWS / 8); r = (q % (ROWS / 8)) * 8; }
     bf16_t *p = KC ? lds + r * P + k : lds + k * P + r;
-    *reinterpret_cast<uint4 *>(p) = reg[i];
+    const bool ok = (mask >> i) & 1u;
+    uint4 v;
+    v.x = ok ? reg[i].x : 0u; v.y = ok ? reg[i].y : 0u; v.z = ok ? reg[i].z : 0u; v.w = ok ? reg[i].w : 0u;
+    *reinterpret_cast<uint4 *>(p) = v;
   }
 }
 
@@ -111,11 +115,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
   using GA = TileGeom<BM, A_KC>;
   using GB = TileGeom<BN, B_KC>;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  bf16_t *sA[2], *sB[2];
-  sA[0] = reinterpret_cast<bf16_t *>(smem_raw);
-  sA[1] = sA[0] + GA::elems;
-  sB[0] = sA[1] + GA::elems;
-  sB[1] = sB[0] + GB::elems;
+  // stage s of A at s*STAGE, of B at s*STAGE + GA::elems (plain offsets from the LDS base keep the
+  // accesses in the LDS address space; pointer tables would decay to flat addressing)
+  constexpr int STAGE = GA::elems + GB::elems;
+  bf16_t *const sbase = reinterpret_cast<bf16_t *>(smem_raw);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -146,19 +149,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
 
   uint4 ra[GA::per_thread], rb[GB::per_thread];
   const int KT = (K + BK - 1) / BK;
-  tile_load<BM, A_KC>(ra, A, lda, m0, M, 0, K, tid);
-  tile_load<BN, B_KC>(rb, B, ldb, n0, N, 0, K, tid);
-  tile_store<BM, A_KC>(ra, sA[0], tid);
-  tile_store<BN, B_KC>(rb, sB[0], tid);
+  unsigned ma = tile_load<BM, A_KC>(ra, A, lda, m0, M, 0, K, tid);
+  unsigned mb = tile_load<BN, B_KC>(rb, B, ldb, n0, N, 0, K, tid);
+  tile_store<BM, A_KC>(ra, ma, sbase, tid);
+  tile_store<BN, B_KC>(rb, mb, sbase + GA::elems, tid);
   __syncthreads();
 
   for (int kt = 0; kt < KT; kt++) {
     const int cur = kt & 1;
     if (kt + 1 < KT) {
-      tile_load<BM, A_KC>(ra, A, lda, m0, M, (kt + 1) * BK, K, tid);
-      tile_load<BN, B_KC>(rb, B, ldb, n0, N, (kt + 1) * BK, K, tid);
+      ma = tile_load<BM, A_KC>(ra, A, lda, m0, M, (kt + 1) * BK, K, tid);
+      mb = tile_load<BN, B_KC>(rb, B, ldb, n0, N, (kt + 1) * BK, K, tid);
     }
-    const bf16_t *a_s = sA[cur], *b_s = sB[cur];
+    const bf16_t *a_s = sbase + cur * STAGE, *b_s = sbase + cur * STAGE + GA::elems;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8_t fa[MI], fb[NI];
@@ -173,8 +176,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < KT) {
-      tile_store<BM, A_KC>(ra, sA[cur ^ 1], tid);
-      tile_store<BN, B_KC>(rb, sB[cur ^ 1], tid);
+      tile_store<BM, A_KC>(ra, ma, sbase + (cur ^ 1) * STAGE, tid);
+      tile_store<BN, B_KC>(rb, mb, sbase + (cur ^ 1) * STAGE + GA::elems, tid);
     }
     __syncthreads();
   }
