@@ -49,6 +49,36 @@ def time_steps(fn, steps, warmup, torch):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def gemm_leg(ctx, wl, reps, torch, stp):
+    """Dominant kernel: the bf16 MFMA GEMM in its forward layout (A row-major, B = W[in,out]).  Its four
+    launches per step (QKV, out-proj, FC1, FC2 shapes of the workload) are replayed alone on the current
+    stream between HIP events recorded on that same stream.  Returns (average ms per launch, average
+    algorithmic flops per launch)."""
+    T, h, a, f = wl.seq, wl.hidden, wl.attn_local, wl.ffn_local
+    td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    code = stp.BF16 if wl.dtype == "bf16" else stp.F32
+    shapes = [(T, 3 * a, h), (T, h, a), (T, f, h), (T, h, f)]
+    bufs = []
+    for (M, N, K) in shapes:
+        A = torch.randn((M, K), device="cuda").to(td)
+        Bm = (torch.randn((K, N), device="cuda") * 0.02).to(td)
+        Cm = torch.empty((M, N), device="cuda", dtype=td)
+        bufs.append((stp.GemmArgs(dtype=code, M=M, N=N, K=K, A=A.data_ptr(), lda=K, B=Bm.data_ptr(), ldb=N,
+                                  C=Cm.data_ptr(), ldc=N, bias_scale=1.0, resid_scale=1.0), A, Bm, Cm))
+    for g, *_ in bufs:
+        ctx.gemm(g)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        for g, *_ in bufs:
+            ctx.gemm(g)
+    e1.record()
+    torch.cuda.synchronize()
+    avg_ms = e0.elapsed_time(e1) / (reps * len(bufs))
+    return avg_ms, sum(2 * M * N * K for (M, N, K) in shapes) / len(shapes)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,6 +86,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="gpt7b_tp8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-gemm", action="store_true",
+                    help="run only the dominant-kernel leg plus a 1 GiB device copy (counter calibration runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the TP all-reduce points are marked boundaries, "
@@ -76,6 +108,15 @@ def main():
     total_flops = fl["F"] + fl["B"] + fl["W"]
 
     ctx = stp.Context(0)
+    if args.only_gemm:
+        gemm_leg(ctx, wl, max(10, args.steps), torch, stp)
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)          # plain copy of known size: 1 GiB read + 1 GiB written per launch
+        torch.cuda.synchronize()
+        ctx.close()
+        return
     stg = StageOnDevice(ctx, [wl], n_mb=2, seed=0)
     stg.load_inputs()
     sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
@@ -100,33 +141,8 @@ def main():
     ms_B = time_steps(lambda: ctx.braid_step(stg.stage, b_ops, s0, s0, s0), args.steps, args.warmup, torch)
     ms_W = time_steps(lambda: ctx.braid_step(stg.stage, w_ops, s0, s0, s0), args.steps, args.warmup, torch)
 
-    # ---- dominant kernel: the bf16 MFMA GEMM in its forward layout (A row-major, B = W[in,out]).
-    # Its four launches per step (QKV, out-proj, FC1, FC2) are replayed alone on the current
-    # stream between HIP events recorded on that same stream.
     T, h, a, f = wl.seq, wl.hidden, wl.attn_local, wl.ffn_local
-    td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
-    code = stp.BF16 if wl.dtype == "bf16" else stp.F32
-    shapes = [(T, 3 * a, h), (T, h, a), (T, f, h), (T, h, f)]
-    bufs = []
-    for (M, N, K) in shapes:
-        A = torch.randn((M, K), device="cuda").to(td)
-        Bm = (torch.randn((K, N), device="cuda") * 0.02).to(td)
-        Cm = torch.empty((M, N), device="cuda", dtype=td)
-        bufs.append((stp.GemmArgs(dtype=code, M=M, N=N, K=K, A=A.data_ptr(), lda=K, B=Bm.data_ptr(), ldb=N,
-                                  C=Cm.data_ptr(), ldc=N, bias_scale=1.0, resid_scale=1.0), A, Bm, Cm))
-    reps = max(10, args.steps)
-    for g, *_ in bufs:
-        ctx.gemm(g)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        for g, *_ in bufs:
-            ctx.gemm(g)
-    e1.record()
-    torch.cuda.synchronize()
-    gemm_avg_ms = e0.elapsed_time(e1) / (reps * len(bufs))
-    gemm_flops_per_launch = sum(2 * M * N * K for (M, N, K) in shapes) / len(shapes)
+    gemm_avg_ms, gemm_flops_per_launch = gemm_leg(ctx, wl, max(10, args.steps), torch, stp)
     achieved = gemm_flops_per_launch / (gemm_avg_ms * 1e-3) / 1e12
 
     result = {

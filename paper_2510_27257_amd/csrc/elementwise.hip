@@ -148,15 +148,30 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, 
   }
 }
 
-// out[c] += scale * sum_{p < nparts} partial[p*stride + c]   (fixed order)
+// out[c] += scale * sum_{p < nparts} partial[p*stride + c], in a fixed order: a 256-thread group owns
+// 64 columns; thread (c, g) adds up rows g, g+4, g+8, ... (8 independent loads in flight), then the
+// four row-group sums are combined 0+1+2+3 through LDS.
 __global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__restrict__ partial, int nparts,
                                                             size_t stride, int n, float scale,
                                                             float *__restrict__ out) {
-  int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= n) return;
+  __shared__ float red[4][64];
+  const int cl = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
   float s = 0.f;
-  for (int p = 0; p < nparts; p++) s += partial[(size_t)p * stride + c];
-  out[c] += scale * s;
+  if (c < n) {
+    int p = g;
+    for (; p + 28 < nparts; p += 32) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) v[u] = partial[(size_t)(p + 4 * u) * stride + c];
+#pragma unroll
+      for (int u = 0; u < 8; u++) s += v[u];
+    }
+    for (; p < nparts; p += 4) s += partial[(size_t)p * stride + c];
+  }
+  red[g][cl] = s;
+  __syncthreads();
+  if (g == 0 && c < n) out[c] += scale * (((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl]);
 }
 
 // ======================================================================
@@ -393,11 +408,11 @@ extern "C" int stp_norm_backward(stp_ctx *ctx, int dtype, int norm, int32_t T, i
                              : norm_bwd_dispatch<float>(ctx, norm, T, h, x, gamma, stats, dy, d_resid, dx, partial, groups, s);
   if (rc != STP_OK) return rc;
   if (dgamma) {
-    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 255) / 256), dim3(256), 0, s, partial, groups, (size_t)2 * h, h, 1.0f, dgamma);
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 63) / 64), dim3(256), 0, s, partial, groups, (size_t)2 * h, h, 1.0f, dgamma);
     STP_LAUNCH_CHECK(ctx);
   }
   if (dbeta && norm == STP_NORM_LN) {
-    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 255) / 256), dim3(256), 0, s, partial + h, groups, (size_t)2 * h, h, 1.0f, dbeta);
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 63) / 64), dim3(256), 0, s, partial + h, groups, (size_t)2 * h, h, 1.0f, dbeta);
     STP_LAUNCH_CHECK(ctx);
   }
   return STP_OK;
@@ -423,7 +438,7 @@ extern "C" int stp_colsum(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const v
   if (dtype == STP_BF16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)x, T, N, partial);
   else hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float *)x, T, N, partial);
   STP_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(partial_reduce_kernel, dim3((N + 255) / 256), dim3(256), 0, s, partial, slabs, (size_t)N, N, scale, out);
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3((N + 63) / 64), dim3(256), 0, s, partial, slabs, (size_t)N, N, scale, out);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }
