@@ -5,8 +5,9 @@
 // transposed-weight forms in B; the token-contracting forms in W).
 //
 // Design (gfx950):
-//   * one workgroup = 4 waves (2 x 2), block tile BM x BN x 64, each wave owns a
-//     (BM/2) x (BN/2) sub-tile as a grid of 32x32 accumulators fed by
+//   * one workgroup = WAVES_M x WAVES_N waves (2 x 4 for the 256 x 256 tile: two waves per SIMD, so one
+//     wave's LDS waits and barrier stalls are covered by the other's MFMAs), block tile BM x BN x 64,
+//     each wave owns a (BM/WAVES_M) x (BN/WAVES_N) sub-tile as a grid of 32x32 accumulators fed by
 //     v_mfma_f32_32x32x16_bf16;
 //   * global -> registers -> LDS with two LDS stages: the loads of K-tile kt+1 are in
 //     flight while the MFMAs of K-tile kt run, one barrier per K-tile;
@@ -34,7 +35,6 @@ template <int ROWS, bool KC> struct TileGeom {
   static constexpr int pitch = KC ? (BK + KPAD) : (ROWS + XPAD);
   static constexpr int elems = KC ? ROWS * pitch : BK * pitch;
   static constexpr int chunks = ROWS * BK / 8;          // 16-byte chunks per tile
-  static constexpr int per_thread = chunks / 256;
 };
 
 // Loads this thread's share of a ROWS x 64 operand tile from global memory into registers.
@@ -42,14 +42,14 @@ template <int ROWS, bool KC> struct TileGeom {
 // read from the (always valid) first element; bit i of the returned mask says chunk i is real.
 // The zero-fill happens when the registers are written to LDS, after the MFMAs of the current
 // tile, so that all loads stay in flight together (no wait between them).
-template <int ROWS, bool KC, int NREG>
+template <int ROWS, bool KC, int NTH, int NREG>
 __device__ __forceinline__ unsigned tile_load(uint4 (&reg)[NREG], const bf16_t *__restrict__ base,
                                               int ld, int row0, int row_lim, int k0, int k_lim, int tid) {
-  static_assert(NREG == TileGeom<ROWS, KC>::per_thread, "register tile size");
+  static_assert(NREG * NTH == TileGeom<ROWS, KC>::chunks, "register tile size");
   unsigned mask = 0;
 #pragma unroll
   for (int i = 0; i < NREG; i++) {
-    int q = tid + 256 * i;
+    int q = tid + NTH * i;
     int r, k;
     if (KC) { r = q >> 3; k = (q & 7) * 8; }
     else { k = q / (ROWS / 8); r = (q % (ROWS / 8)) * 8; }
@@ -62,12 +62,12 @@ __device__ __forceinline__ unsigned tile_load(uint4 (&reg)[NREG], const bf16_t *
   return mask;
 }
 
-template <int ROWS, bool KC, int NREG>
+template <int ROWS, bool KC, int NTH, int NREG>
 __device__ __forceinline__ void tile_store(const uint4 (&reg)[NREG], unsigned mask, bf16_t *lds, int tid) {
   constexpr int P = TileGeom<ROWS, KC>::pitch;
 #pragma unroll
   for (int i = 0; i < NREG; i++) {
-    int q = tid + 256 * i;
+    int q = tid + NTH * i;
     int r, k;
     if (KC) { r = q >> 3; k = (q & 7) * 8; }
     else { k = q / (ROWS / 8); r = (q % (ROWS / 8)) * 8; }
@@ -108,22 +108,10 @@ struct Epi {
 
 enum { EPI_STORE = 0, EPI_GELU_DUAL = 1, EPI_GELU_BWD = 2, EPI_F32_ACCUM = 3 };
 
-template <int BM, int BN, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
-                                                        int ldb, int M, int N, int K, int tiles_m, int tiles_n, Epi ep) {
-  constexpr int WM = BM / 2, WN = BN / 2, MI = WM / 32, NI = WN / 32;
-  using GA = TileGeom<BM, A_KC>;
-  using GB = TileGeom<BN, B_KC>;
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  // stage s of A at s*STAGE, of B at s*STAGE + GA::elems (plain offsets from the LDS base keep the
-  // accesses in the LDS address space; pointer tables would decay to flat addressing)
-  constexpr int STAGE = GA::elems + GB::elems;
-  bf16_t *const sbase = reinterpret_cast<bf16_t *>(smem_raw);
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-
-  // ---- XCD-aware tile map: XCD x (= blockIdx % 8) walks the contiguous band [x*per, (x+1)*per)
+// XCD-aware tile map: workgroups are dealt round-robin to the 8 XCDs, so XCD x (= blockIdx % 8) is given
+// the contiguous band [x*total/8, (x+1)*total/8) of a tile order that walks groups of 4 tile-rows
+// column by column: tiles resident on one XCD share their A / B panels in that XCD's L2.
+__device__ __forceinline__ void map_tile(int tiles_m, int tiles_n, int &tm, int &tn) {
   const int total = tiles_m * tiles_n;
   int pid = blockIdx.x;
   {
@@ -135,60 +123,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
   int group = pid / (GROUP_M * tiles_n);
   int first_m = group * GROUP_M;
   int gsize = min(tiles_m - first_m, GROUP_M);
-  int tm = first_m + (pid % (GROUP_M * tiles_n)) % gsize;
-  int tn = (pid % (GROUP_M * tiles_n)) / gsize;
-  const int m0 = tm * BM, n0 = tn * BN;
+  tm = first_m + (pid % (GROUP_M * tiles_n)) % gsize;
+  tn = (pid % (GROUP_M * tiles_n)) / gsize;
+}
 
-  f32x16_t acc[MI][NI];
-#pragma unroll
-  for (int i = 0; i < MI; i++)
-#pragma unroll
-    for (int j = 0; j < NI; j++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
-
-  uint4 ra[GA::per_thread], rb[GB::per_thread];
-  const int KT = (K + BK - 1) / BK;
-  unsigned ma = tile_load<BM, A_KC>(ra, A, lda, m0, M, 0, K, tid);
-  unsigned mb = tile_load<BN, B_KC>(rb, B, ldb, n0, N, 0, K, tid);
-  tile_store<BM, A_KC>(ra, ma, sbase, tid);
-  tile_store<BN, B_KC>(rb, mb, sbase + GA::elems, tid);
-  __syncthreads();
-
-  for (int kt = 0; kt < KT; kt++) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) {
-      ma = tile_load<BM, A_KC>(ra, A, lda, m0, M, (kt + 1) * BK, K, tid);
-      mb = tile_load<BN, B_KC>(rb, B, ldb, n0, N, (kt + 1) * BK, K, tid);
-    }
-    const bf16_t *a_s = sbase + cur * STAGE, *b_s = sbase + cur * STAGE + GA::elems;
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8_t fa[MI], fb[NI];
-#pragma unroll
-      for (int i = 0; i < MI; i++) fa[i] = frag_load<BM, A_KC>(a_s, wm * WM + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < NI; j++) fb[j] = frag_load<BN, B_KC>(b_s, wn * WN + j * 32, kk, lane);
-#pragma unroll
-      for (int i = 0; i < MI; i++)
-#pragma unroll
-        for (int j = 0; j < NI; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) {
-      tile_store<BM, A_KC>(ra, ma, sbase + (cur ^ 1) * STAGE, tid);
-      tile_store<BN, B_KC>(rb, mb, sbase + (cur ^ 1) * STAGE + GA::elems, tid);
-    }
-    __syncthreads();
-  }
-
-  // ---- epilogue.  Accumulator v of lane l is C[32*i + 8*(v/4) + 4*(l/32) + v%4][32*j + l%32].
-  // Each wave stages one 32 x WN strip at a time in its own LDS area (fp32, pitch WN + 8 keeps the two
-  // lane halves on different banks) and reads it back row-wise, 8 consecutive columns per lane, so
-  // that every global access of the epilogue (C, C2, residual, aux, bias) is a 16- or 32-byte vector.
+// Epilogue.  Accumulator v of lane l is C[32*i + 8*(v/4) + 4*(l/32) + v%4][32*j + l%32].
+// Each wave stages one 32 x WN strip at a time in its own LDS area (fp32, pitch WN + 8 keeps the two
+// lane halves on different banks) and reads it back row-wise, 8 consecutive columns per lane, so
+// that every global access of the epilogue (C, C2, residual, aux, bias) is a 16- or 32-byte vector.
+// The caller guarantees that the operand stages in LDS are dead (barrier after the last K-tile).
+template <int MI, int NI, int WN, int EPI>
+__device__ __forceinline__ void store_tile(f32x16_t (&acc)[MI][NI], float *stage, int row_base, int col_base, int M, int N,
+                                           const Epi &ep, int lane) {
   constexpr int SP = WN + 8;
-  static_assert((size_t)4 * 32 * SP * sizeof(float) <= (size_t)2 * (GA::elems + GB::elems) * sizeof(bf16_t), "staging fits");
-  float *stage = reinterpret_cast<float *>(smem_raw) + wave * (32 * SP);
   const int lr = lane & 31, lg = lane >> 5;
   const bool has_bias = ep.bias != nullptr, has_resid = ep.resid != nullptr;
   constexpr int LPR = WN / 8;             // lanes per staged row
@@ -204,7 +151,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     for (int p = 0; p < PASSES; p++) {
       const int idx = p * 64 + lane;
       const int r = idx / LPR, c = (idx % LPR) * 8;
-      const int row = m0 + wm * WM + i * 32 + r, col = n0 + wn * WN + c;
+      const int row = row_base + i * 32 + r, col = col_base + c;
       if (row < M && col < N) {
         float val[8];
         Vec8<float>::load(stage + r * SP + c, val);
@@ -251,20 +198,262 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
   }
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
+                                                        int ldb, int M, int N, int K, int tiles_m, int tiles_n, Epi ep) {
+  constexpr int NTH = 64 * WAVES_M * WAVES_N;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, MI = WM / 32, NI = WN / 32;
+  using GA = TileGeom<BM, A_KC>;
+  using GB = TileGeom<BN, B_KC>;
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  // stage s of A at s*STAGE, of B at s*STAGE + GA::elems (plain offsets from the LDS base keep the
+  // accesses in the LDS address space; pointer tables would decay to flat addressing)
+  constexpr int STAGE = GA::elems + GB::elems;
+  bf16_t *const sbase = reinterpret_cast<bf16_t *>(smem_raw);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+  int tm, tn;
+  map_tile(tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  f32x16_t acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; i++)
+#pragma unroll
+    for (int j = 0; j < NI; j++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
+
+  uint4 ra[GA::chunks / NTH], rb[GB::chunks / NTH];
+  const int KT = (K + BK - 1) / BK;
+  unsigned ma = tile_load<BM, A_KC, NTH>(ra, A, lda, m0, M, 0, K, tid);
+  unsigned mb = tile_load<BN, B_KC, NTH>(rb, B, ldb, n0, N, 0, K, tid);
+  tile_store<BM, A_KC, NTH>(ra, ma, sbase, tid);
+  tile_store<BN, B_KC, NTH>(rb, mb, sbase + GA::elems, tid);
+  __syncthreads();
+
+  for (int kt = 0; kt < KT; kt++) {
+    const int cur = kt & 1;
+    if (kt + 1 < KT) {
+      ma = tile_load<BM, A_KC, NTH>(ra, A, lda, m0, M, (kt + 1) * BK, K, tid);
+      mb = tile_load<BN, B_KC, NTH>(rb, B, ldb, n0, N, (kt + 1) * BK, K, tid);
+    }
+    const bf16_t *a_s = sbase + cur * STAGE, *b_s = sbase + cur * STAGE + GA::elems;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8_t fa[MI], fb[NI];
+#pragma unroll
+      for (int i = 0; i < MI; i++) fa[i] = frag_load<BM, A_KC>(a_s, wm * WM + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < NI; j++) fb[j] = frag_load<BN, B_KC>(b_s, wn * WN + j * 32, kk, lane);
+#pragma unroll
+      for (int i = 0; i < MI; i++)
+#pragma unroll
+        for (int j = 0; j < NI; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < KT) {
+      tile_store<BM, A_KC, NTH>(ra, ma, sbase + (cur ^ 1) * STAGE, tid);
+      tile_store<BN, B_KC, NTH>(rb, mb, sbase + (cur ^ 1) * STAGE + GA::elems, tid);
+    }
+    __syncthreads();
+  }
+
+  store_tile<MI, NI, WN, EPI>(acc, reinterpret_cast<float *>(smem_raw) + wave * (32 * (WN + 8)), m0 + wm * WM, n0 + wn * WN, M, N,
+                              ep, lane);
+}
+
+
+// =====================================================================================================
+// 256 x 256 kernel with direct-to-LDS loads and a 4-stage pipeline (the path every large GEMM takes).
+//
+// global_load_lds_dwordx4 moves 16 bytes per lane from global memory straight into LDS (lane i of a
+// wave instruction lands at M0 + 16*i): no staging registers, no ds_write, and the loads of three
+// K-tiles (32 deep each) stay in flight behind the MFMAs of the current one, which is what it takes
+// to cover HBM / L2 latency with two waves per SIMD.  A wave instruction fills 1 KB of LDS
+// contiguously, so padding is impossible; bank conflicts are avoided by permuting WHICH global chunk
+// each lane fetches (an XOR swizzle applied on the global side and undone in the fragment address):
+//   k-contiguous operand : tile [rows][32], 4 chunks per row; chunk c of row r sits in slot c ^ ((r>>2)&3)
+//   row-contiguous operand: tile [32][rows], rows/8 chunks per k-row; chunk c of k-row k sits in slot
+//                           c ^ (4*(k&3))   (read back with ds_read_b64_tr_b16)
+// Synchronisation is explicit: the compiler does not track these loads, so each K-tile starts with
+// s_waitcnt vmcnt(2 tiles' worth) + s_barrier (tile kt has landed for every wave, and every wave is done
+// reading the stage that is refilled next).  Rows past M / N are fetched from a clamped (valid)
+// address and never stored; K must be a multiple of 32.
+// =====================================================================================================
+constexpr int DK = 32;         // K-tile depth of the DMA kernel
+constexpr int DSTAGES = 4;
+
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+typedef const void __attribute__((address_space(1))) * gptr_t;
+typedef void __attribute__((address_space(3))) * lptr_t;
+
+template <int ROWS, bool KC, int NWAVES>
+struct DmaOp {
+  static constexpr int NINST = ROWS * 4 / 64 / NWAVES;   // wave instructions per wave per K-tile
+  static constexpr int bytes = ROWS * DK * 2;
+  // element offset (from the operand base, K-tile 0) of the chunk that lane `lane` of this wave's j-th
+  // instruction must fetch
+  static __device__ __forceinline__ size_t chunk_offset(int j, int wave, int lane, int ld, int row0, int row_lim) {
+    const int p = (wave * NINST + j) * 64 + lane;
+    if (KC) {
+      const int r = p >> 2, c = (p & 3) ^ ((r >> 2) & 3);
+      const int row = min(row0 + r, row_lim - 1);
+      return (size_t)row * ld + c * 8;
+    } else {
+      constexpr int CPR = ROWS / 8;
+      const int k = p / CPR, c = (p % CPR) ^ (4 * (k & 3));
+      int col = row0 + c * 8;
+      col = col < row_lim ? col : 0;
+      return (size_t)k * ld + col;
+    }
+  }
+  static __device__ __forceinline__ void issue(const bf16_t *base, const size_t (&off)[NINST], size_t kstep, char *lds_tile, int wave) {
+#pragma unroll
+    for (int j = 0; j < NINST; j++)
+      __builtin_amdgcn_global_load_lds((gptr_t)(base + off[j] + kstep), (lptr_t)(lds_tile + (wave * NINST + j) * 1024), 16, 0, 0);
+  }
+  // fragment for rows row..row+31, k = kk..kk+15 (kk = 0 or 16)
+  static __device__ __forceinline__ bf16x8_t frag(const char *lds_tile, int row, int kk, int lane) {
+    if (KC) {
+      const int r = row + (lane & 31);
+      const int c = (kk >> 3) + (lane >> 5);
+      return *reinterpret_cast<const bf16x8_t *>(lds_tile + (r * 4 + (c ^ ((r >> 2) & 3))) * 16);
+    } else {
+      constexpr int CPR = ROWS / 8;
+      const int k = kk + 8 * (lane >> 5) + ((lane & 15) >> 2);
+      const int col = row + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      const char *p = lds_tile + (k * CPR + ((col >> 3) ^ (4 * (k & 3)))) * 16 + (col & 7) * 2;
+      // Issued as inline assembly: through the builtin the compiler would order every transposing read
+      // behind ALL outstanding direct-to-LDS loads (vmcnt(0)), which would serialise the pipeline.
+      // The result is only valid after frag_wait().
+      const unsigned addr = (unsigned)(size_t)(const __attribute__((address_space(3))) char *)p;
+      u32x2_t lo, hi;
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(4 * CPR * 16));
+      u32x4_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+      return __builtin_bit_cast(bf16x8_t, v);
+    }
+  }
+};
+
+// Makes the LDS reads issued by DmaOp::frag's inline assembly visible: waits for all outstanding LDS
+// operations of the wave and ties the fragments to the wait so that no MFMA can be scheduled above it.
+template <int N>
+__device__ __forceinline__ void frag_wait(bf16x8_t (&f)[N]) {
+  static_assert(N == 2 || N == 4, "fragment count");
+  if (N == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]));
+  else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[N - 2]), "+v"(f[N - 1]));
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
+                                                            int ldb, int M, int N, int K, int tiles_m, int tiles_n, Epi ep) {
+  constexpr int BM = 256, BN = 256, WAVES_M = 2, WAVES_N = 4, NWAVES = 8;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, MI = WM / 32, NI = WN / 32;
+  using OA = DmaOp<BM, A_KC, NWAVES>;
+  using OB = DmaOp<BN, B_KC, NWAVES>;
+  constexpr int STAGE_BYTES = OA::bytes + OB::bytes;
+  constexpr int LOADS_PER_TILE = OA::NINST + OB::NINST;
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  int tm, tn;
+  map_tile(tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  size_t offa[OA::NINST], offb[OB::NINST];
+#pragma unroll
+  for (int j = 0; j < OA::NINST; j++) offa[j] = OA::chunk_offset(j, wave, lane, lda, m0, M);
+#pragma unroll
+  for (int j = 0; j < OB::NINST; j++) offb[j] = OB::chunk_offset(j, wave, lane, ldb, n0, N);
+  const size_t stepa = A_KC ? (size_t)DK : (size_t)DK * lda;
+  const size_t stepb = B_KC ? (size_t)DK : (size_t)DK * ldb;
+
+  f32x16_t acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; i++)
+#pragma unroll
+    for (int j = 0; j < NI; j++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
+
+  const int KT = K / DK;
+  // prologue: K-tiles 0 .. DSTAGES-2 (clamped to the last tile so that the in-flight count is uniform)
+#pragma unroll
+  for (int t = 0; t < DSTAGES - 1; t++) {
+    const int kt = min(t, KT - 1);
+    OA::issue(A, offa, kt * stepa, smem_raw + t * STAGE_BYTES, wave);
+    OB::issue(B, offb, kt * stepb, smem_raw + t * STAGE_BYTES + OA::bytes, wave);
+  }
+  for (int kt = 0; kt < KT; kt++) {
+    // this wave's loads of tile kt have landed once at most (DSTAGES-2) tiles' worth remain in flight
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((DSTAGES - 2) * LOADS_PER_TILE) : "memory");
+    {
+      const int ktl = min(kt + DSTAGES - 1, KT - 1);
+      char *st = smem_raw + ((kt + DSTAGES - 1) % DSTAGES) * STAGE_BYTES;
+      OA::issue(A, offa, ktl * stepa, st, wave);
+      OB::issue(B, offb, ktl * stepb, st + OA::bytes, wave);
+    }
+    const char *a_s = smem_raw + (kt % DSTAGES) * STAGE_BYTES;
+    const char *b_s = a_s + OA::bytes;
+#pragma unroll
+    for (int kk = 0; kk < DK; kk += 16) {
+      bf16x8_t fa[MI], fb[NI];
+#pragma unroll
+      for (int i = 0; i < MI; i++) fa[i] = OA::frag(a_s, wm * WM + i * 32, kk, lane);
+#pragma unroll
+      for (int j = 0; j < NI; j++) fb[j] = OB::frag(b_s, wn * WN + j * 32, kk, lane);
+      if (!A_KC) frag_wait(fa);
+      if (!B_KC) frag_wait(fb);
+#pragma unroll
+      for (int i = 0; i < MI; i++)
+#pragma unroll
+        for (int j = 0; j < NI; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  // drain the (redundant) tail loads before the stages are reused as epilogue staging
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  store_tile<MI, NI, WN, EPI>(acc, reinterpret_cast<float *>(smem_raw) + wave * (32 * (WN + 8)), m0 + wm * WM, n0 + wn * WN, M, N,
+                              ep, lane);
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+int launch_dma(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t s) {
+  constexpr size_t smem = (size_t)DSTAGES * (256 * DK * 2 + 256 * DK * 2);
+  static_assert(smem <= 160 * 1024 && smem >= (size_t)8 * 32 * (64 + 8) * sizeof(float), "LDS budget");
+  auto kern = gemm_bf16_dma_kernel<A_KC, B_KC, EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    STP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_set = true;
+  }
+  int tiles_m = (a->M + 255) / 256, tiles_n = (a->N + 255) / 256;
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(512), smem, s, (const bf16_t *)a->A, a->lda, (const bf16_t *)a->B,
+                     a->ldb, a->M, a->N, a->K, tiles_m, tiles_n, ep);
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, int EPI>
 int launch_cfg(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t s) {
   using GA = TileGeom<BM, A_KC>;
   using GB = TileGeom<BN, B_KC>;
   constexpr size_t smem = (size_t)2 * (GA::elems + GB::elems) * sizeof(bf16_t);
   static_assert(smem <= 160 * 1024, "LDS budget");
-  auto kern = gemm_bf16_kernel<BM, BN, A_KC, B_KC, EPI>;
+  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, EPI>;
   static bool attr_set = false;   // the attribute is per function; setting it twice is harmless
   if (!attr_set) {
     STP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
   int tiles_m = (a->M + BM - 1) / BM, tiles_n = (a->N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, s, (const bf16_t *)a->A, a->lda, (const bf16_t *)a->B,
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(64 * WAVES_M * WAVES_N), smem, s, (const bf16_t *)a->A, a->lda, (const bf16_t *)a->B,
                      a->ldb, a->M, a->N, a->K, tiles_m, tiles_n, ep);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
@@ -273,8 +462,8 @@ int launch_cfg(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t 
 template <bool A_KC, bool B_KC, int EPI>
 int launch_tile(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t s) {
   long t256 = (long)((a->M + 255) / 256) * ((a->N + 255) / 256);
-  if (t256 >= 96) return launch_cfg<256, 256, A_KC, B_KC, EPI>(ctx, a, ep, s);
-  return launch_cfg<128, 128, A_KC, B_KC, EPI>(ctx, a, ep, s);
+  if (t256 >= 96 && a->K % DK == 0) return launch_dma<A_KC, B_KC, EPI>(ctx, a, ep, s);
+  return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI>(ctx, a, ep, s);
 }
 
 template <bool A_KC, bool B_KC>
