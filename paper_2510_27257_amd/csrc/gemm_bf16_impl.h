@@ -390,33 +390,74 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t *__rest
     OA::issue(A, offa, kt * stepa, smem_raw + t * STAGE_BYTES, wave);
     OB::issue(B, offb, kt * stepb, smem_raw + t * STAGE_BYTES + OA::bytes, wave);
   }
+
+  // ---- ping-pong schedule.  The two waves that share a SIMD (wave w and w + 4) run half a step apart:
+  // in every phase one of them issues the LDS fragment reads of its next 16-deep step while the other
+  // executes the 8 MFMAs of its current step, so the matrix pipe of every SIMD is fed in every phase
+  // and LDS latency never sits between MFMAs.  Phases are separated by s_barrier (phase lock only);
+  // data safety comes from the vmcnt wait + barrier at the head of each K-tile.
+  //   phase 4kt  : [tile kt landed] A reads (kt,0)      B runs (kt-1,1)
+  //   phase 4kt+1:                  A runs  (kt,0)      B reads (kt,0)
+  //   phase 4kt+2:                  A reads (kt,1)      B runs  (kt,0)
+  //   phase 4kt+3:                  A runs  (kt,1)      B reads (kt,1)
+  const bool grp_b = wave >= NWAVES / 2;
+  bf16x8_t fa[MI], fb[NI];
+#define STP_PHASE_BARRIER()                        \
+  do {                                             \
+    __builtin_amdgcn_sched_barrier(0);             \
+    asm volatile("s_barrier" ::: "memory");        \
+    __builtin_amdgcn_sched_barrier(0);             \
+  } while (0)
+#define STP_READ_FRAGS(a_s, b_s, kk)                                                          \
+  do {                                                                                        \
+    _Pragma("unroll") for (int i = 0; i < MI; i++) fa[i] = OA::frag(a_s, wm * WM + i * 32, kk, lane); \
+    _Pragma("unroll") for (int j = 0; j < NI; j++) fb[j] = OB::frag(b_s, wn * WN + j * 32, kk, lane); \
+  } while (0)
+#define STP_RUN_MFMAS()                                                                       \
+  do {                                                                                        \
+    if (!A_KC) frag_wait(fa);                                                                 \
+    if (!B_KC) frag_wait(fb);                                                                 \
+    _Pragma("unroll") for (int i = 0; i < MI; i++)                                            \
+      _Pragma("unroll") for (int j = 0; j < NI; j++)                                          \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0); \
+  } while (0)
+
   for (int kt = 0; kt < KT; kt++) {
-    // this wave's loads of tile kt have landed once at most (DSTAGES-2) tiles' worth remain in flight
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((DSTAGES - 2) * LOADS_PER_TILE) : "memory");
+    const char *a_s = smem_raw + (kt % DSTAGES) * STAGE_BYTES;
+    const char *b_s = a_s + OA::bytes;
+    // head of K-tile kt: this wave's loads of tile kt have landed once at most (DSTAGES-2) tiles' worth
+    // remain in flight; its own LDS reads of the stage about to be refilled have returned (lgkmcnt)
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((DSTAGES - 2) * LOADS_PER_TILE) : "memory");
+    __builtin_amdgcn_sched_barrier(0);
     {
       const int ktl = min(kt + DSTAGES - 1, KT - 1);
       char *st = smem_raw + ((kt + DSTAGES - 1) % DSTAGES) * STAGE_BYTES;
       OA::issue(A, offa, ktl * stepa, st, wave);
       OB::issue(B, offb, ktl * stepb, st + OA::bytes, wave);
     }
-    const char *a_s = smem_raw + (kt % DSTAGES) * STAGE_BYTES;
-    const char *b_s = a_s + OA::bytes;
-#pragma unroll
-    for (int kk = 0; kk < DK; kk += 16) {
-      bf16x8_t fa[MI], fb[NI];
-#pragma unroll
-      for (int i = 0; i < MI; i++) fa[i] = OA::frag(a_s, wm * WM + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < NI; j++) fb[j] = OB::frag(b_s, wn * WN + j * 32, kk, lane);
-      if (!A_KC) frag_wait(fa);
-      if (!B_KC) frag_wait(fb);
-#pragma unroll
-      for (int i = 0; i < MI; i++)
-#pragma unroll
-        for (int j = 0; j < NI; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    if (!grp_b) {
+      STP_READ_FRAGS(a_s, b_s, 0);
+      STP_PHASE_BARRIER();
+      STP_RUN_MFMAS();
+      STP_PHASE_BARRIER();
+      STP_READ_FRAGS(a_s, b_s, 16);
+      STP_PHASE_BARRIER();
+      STP_RUN_MFMAS();
+    } else {
+      if (kt > 0) STP_RUN_MFMAS();
+      STP_PHASE_BARRIER();
+      STP_READ_FRAGS(a_s, b_s, 0);
+      STP_PHASE_BARRIER();
+      STP_RUN_MFMAS();
+      STP_PHASE_BARRIER();
+      STP_READ_FRAGS(a_s, b_s, 16);
     }
   }
+  if (grp_b) STP_RUN_MFMAS();
+#undef STP_PHASE_BARRIER
+#undef STP_READ_FRAGS
+#undef STP_RUN_MFMAS
   // drain the (redundant) tail loads before the stages are reused as epilogue staging
   asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
   store_tile<MI, NI, WN, EPI>(acc, reinterpret_cast<float *>(smem_raw) + wave * (32 * (WN + 8)), m0 + wm * WM, n0 + wn * WN, M, N,
