@@ -168,7 +168,7 @@ const char *stp_status_str(int status);
 int stp_check_desc(const stp_layer_desc *desc);
 int stp_stash_bytes(const stp_layer_desc *desc, size_t *bytes);
 int stp_stash_field(const stp_layer_desc *desc, int field, size_t *offset, size_t *bytes);
-/* Workspace (split-free reductions, column-sum partials) for three concurrent
+/* Workspace (norm-gradient and column-sum partials, attention chunk partials) for three concurrent
  * streams; the maximum over the layers of a stage must be supplied. */
 int stp_workspace_bytes(const stp_layer_desc *desc, size_t *bytes);
 int stp_set_workspace(stp_ctx *ctx, void *device_ptr, size_t bytes);
@@ -253,12 +253,14 @@ int stp_norm_backward(stp_ctx *ctx, int dtype, int norm, int32_t T, int32_t h, c
                       const void *gamma, const float *stats, const void *dy, const void *d_resid,
                       void *dx, float *dgamma, float *dbeta, int lane, void *hip_stream);
 
-/* Attention core of one rank: qkv is [T, 3a] (Q|K|V), ctx [T,a], lse fp32 [mbsz,n,seq]. */
+/* Attention core of one rank: qkv is [T, 3a] (Q|K|V), ctx [T,a], lse fp32 [mbsz,n,seq].  The bf16 kernels
+ * cut the key range into chunks whose fp32 partials live in workspace lane `lane` (0..2). */
 int stp_attention_forward(stp_ctx *ctx, const stp_layer_desc *desc, const void *qkv, void *ctx_out,
-                          float *lse, void *hip_stream);
+                          float *lse, int lane, void *hip_stream);
 /* dqkv [T,3a] from dctx [T,a]; delta is fp32 scratch [mbsz,n,seq]. */
 int stp_attention_backward(stp_ctx *ctx, const stp_layer_desc *desc, const void *qkv, const void *ctx_in,
-                           const float *lse, const void *dctx, float *delta, void *dqkv, void *hip_stream);
+                           const float *lse, const void *dctx, float *delta, void *dqkv, int lane,
+                           void *hip_stream);
 
 /* Elementwise pieces (HBM-bound).  n = number of elements. */
 int stp_gelu_forward(stp_ctx *ctx, int dtype, size_t n, const void *x, void *y, void *hip_stream);

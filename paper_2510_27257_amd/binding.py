@@ -125,8 +125,8 @@ def lib() -> C.CDLL:
     L.stp_gemm.argtypes = [vp, P(GemmArgs), vp]
     L.stp_norm_forward.argtypes = [vp, C.c_int, C.c_int, i32, i32, f32, vp, vp, vp, vp, vp, vp]
     L.stp_norm_backward.argtypes = [vp, C.c_int, C.c_int, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp]
-    L.stp_attention_forward.argtypes = [vp, P(LayerDesc), vp, vp, vp, vp]
-    L.stp_attention_backward.argtypes = [vp, P(LayerDesc), vp, vp, vp, vp, vp, vp, vp]
+    L.stp_attention_forward.argtypes = [vp, P(LayerDesc), vp, vp, vp, C.c_int, vp]
+    L.stp_attention_backward.argtypes = [vp, P(LayerDesc), vp, vp, vp, vp, vp, vp, C.c_int, vp]
     L.stp_gelu_forward.argtypes = [vp, C.c_int, sz, vp, vp, vp]
     L.stp_gelu_backward.argtypes = [vp, C.c_int, sz, vp, vp, vp, vp]
     L.stp_swiglu_forward.argtypes = [vp, C.c_int, sz, vp, vp, vp, vp]
@@ -274,13 +274,13 @@ class Context:
                                                _ptr(dy), _ptr(d_resid), _ptr(dx), _ptr(dgamma), _ptr(dbeta), lane,
                                                _stream(stream)), "stp_norm_backward")
 
-    def attention_forward(self, desc, qkv, out, lse, stream=None):
-        self.check(self._lib.stp_attention_forward(self._h, C.byref(desc), _ptr(qkv), _ptr(out), _ptr(lse),
+    def attention_forward(self, desc, qkv, out, lse, lane=0, stream=None):
+        self.check(self._lib.stp_attention_forward(self._h, C.byref(desc), _ptr(qkv), _ptr(out), _ptr(lse), lane,
                                                    _stream(stream)), "stp_attention_forward")
 
-    def attention_backward(self, desc, qkv, out, lse, dout, delta, dqkv, stream=None):
+    def attention_backward(self, desc, qkv, out, lse, dout, delta, dqkv, lane=0, stream=None):
         self.check(self._lib.stp_attention_backward(self._h, C.byref(desc), _ptr(qkv), _ptr(out), _ptr(lse),
-                                                    _ptr(dout), _ptr(delta), _ptr(dqkv), _stream(stream)),
+                                                    _ptr(dout), _ptr(delta), _ptr(dqkv), lane, _stream(stream)),
                    "stp_attention_backward")
 
     def gelu_forward(self, dtype, n, x, y, stream=None):

@@ -109,9 +109,12 @@ __device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + __ex
 // ---- kernel launchers implemented in the .hip files ---------------------------------
 int stp_launch_gemm_bf16(stp_ctx *ctx, const stp_gemm_args *a, hipStream_t s);
 int stp_launch_gemm_f32(stp_ctx *ctx, const stp_gemm_args *a, hipStream_t s);
-int stp_launch_attn_fwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out, float *lse, hipStream_t s);
+int stp_launch_attn_fwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out, float *lse, float *ws,
+                             size_t ws_bytes, hipStream_t s);
 int stp_launch_attn_bwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const void *out, const float *lse,
-                             const void *dout, float *delta, void *dqkv, hipStream_t s);
+                             const void *dout, float *delta, void *dqkv, float *ws, size_t ws_bytes, hipStream_t s);
+size_t stp_attn_fwd_ws_bytes(const stp_layer_desc *d);   // workspace the bf16 attention kernels need (chunk partials)
+size_t stp_attn_bwd_ws_bytes(const stp_layer_desc *d);
 int stp_launch_attn_fwd_generic(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out, float *lse, hipStream_t s);
 int stp_launch_attn_bwd_generic(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const void *out, const float *lse,
                                 const void *dout, float *delta, void *dqkv, hipStream_t s);

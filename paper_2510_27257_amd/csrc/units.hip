@@ -113,7 +113,13 @@ static size_t ws_lane_bytes(const stp_layer_desc *d) {
   size_t widest = h > a3 ? h : a3;
   if (ff > widest) widest = ff;
   size_t cs = ((T + 63) / 64) * widest * sizeof(float);
-  return stp_align_up(norm > cs ? norm : cs, 256);
+  size_t need = norm > cs ? norm : cs;
+  if (d->dtype == STP_BF16) {
+    size_t af = stp_attn_fwd_ws_bytes(d), ab = stp_attn_bwd_ws_bytes(d);
+    if (af > need) need = af;
+    if (ab > need) need = ab;
+  }
+  return stp_align_up(need, 256);
 }
 
 extern "C" int stp_workspace_bytes(const stp_layer_desc *d, size_t *bytes) {
@@ -162,19 +168,25 @@ static int attn_args_ok(stp_ctx *ctx, const stp_layer_desc *d, const char *who) 
 }
 
 extern "C" int stp_attention_forward(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out, float *lse,
-                                     void *hip_stream) {
+                                     int lane, void *hip_stream) {
   if (!ctx) return STP_EINVAL;
   if (!d || !qkv || !out || !lse) return stp_fail(ctx, STP_EINVAL, "stp_attention_forward: null pointer%s");
   int rc = attn_args_ok(ctx, d, "stp_attention_forward");
   if (rc != STP_OK) return rc;
   if (!stp_aligned16(qkv) || !stp_aligned16(out)) return stp_fail(ctx, STP_EALIGN, "stp_attention_forward: alignment%s");
+  if (lane < 0 || lane > 2) return stp_fail(ctx, STP_EINVAL, "stp_attention_forward: lane must be 0..2%s");
   hipStream_t s = (hipStream_t)hip_stream;
-  if (d->dtype == STP_BF16) return stp_launch_attn_fwd_bf16(ctx, d, qkv, out, lse, s);
+  if (d->dtype == STP_BF16) {
+    size_t lane_bytes;
+    char *ws = stp_ws_lane(ctx, lane, &lane_bytes);
+    return stp_launch_attn_fwd_bf16(ctx, d, qkv, out, lse, (float *)ws, lane_bytes, s);
+  }
   return stp_launch_attn_fwd_generic(ctx, d, qkv, out, lse, s);
 }
 
 extern "C" int stp_attention_backward(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const void *out,
-                                      const float *lse, const void *dout, float *delta, void *dqkv, void *hip_stream) {
+                                      const float *lse, const void *dout, float *delta, void *dqkv, int lane,
+                                      void *hip_stream) {
   if (!ctx) return STP_EINVAL;
   if (!d || !qkv || !out || !lse || !dout || !delta || !dqkv)
     return stp_fail(ctx, STP_EINVAL, "stp_attention_backward: null pointer%s");
@@ -182,8 +194,13 @@ extern "C" int stp_attention_backward(stp_ctx *ctx, const stp_layer_desc *d, con
   if (rc != STP_OK) return rc;
   if (!stp_aligned16(qkv) || !stp_aligned16(out) || !stp_aligned16(dout) || !stp_aligned16(dqkv))
     return stp_fail(ctx, STP_EALIGN, "stp_attention_backward: alignment%s");
+  if (lane < 0 || lane > 2) return stp_fail(ctx, STP_EINVAL, "stp_attention_backward: lane must be 0..2%s");
   hipStream_t s = (hipStream_t)hip_stream;
-  if (d->dtype == STP_BF16) return stp_launch_attn_bwd_bf16(ctx, d, qkv, out, lse, dout, delta, dqkv, s);
+  if (d->dtype == STP_BF16) {
+    size_t lane_bytes;
+    char *ws = stp_ws_lane(ctx, lane, &lane_bytes);
+    return stp_launch_attn_bwd_bf16(ctx, d, qkv, out, lse, dout, delta, dqkv, (float *)ws, lane_bytes, s);
+  }
   return stp_launch_attn_bwd_generic(ctx, d, qkv, out, lse, dout, delta, dqkv, s);
 }
 
@@ -267,7 +284,7 @@ extern "C" int stp_forward_unit(stp_ctx *ctx, const stp_layer_desc *d, int unit,
       g.bias = bias ? w->b_qkv : nullptr;
       RET_IF(stp_gemm(ctx, &g, hip_stream));
       if (d->rope) RET_IF(stp_rope(ctx, d, f.p[STP_ST_QKV], 0, hip_stream));
-      RET_IF(stp_attention_forward(ctx, d, f.p[STP_ST_QKV], f.p[STP_ST_CTX], (float *)f.p[STP_ST_LSE], hip_stream));
+      RET_IF(stp_attention_forward(ctx, d, f.p[STP_ST_QKV], f.p[STP_ST_CTX], (float *)f.p[STP_ST_LSE], lane, hip_stream));
       g = gemm_base(d, T, h, a);
       g.A = f.p[STP_ST_CTX]; g.lda = a;
       g.B = w->w_o; g.ldb = h;
@@ -373,7 +390,7 @@ extern "C" int stp_backward_input_unit(stp_ctx *ctx, const stp_layer_desc *d, in
       g.C = f.p[STP_ST_DCTX]; g.ldc = a;
       RET_IF(stp_gemm(ctx, &g, hip_stream));
       RET_IF(stp_attention_backward(ctx, d, f.p[STP_ST_QKV], f.p[STP_ST_CTX], (const float *)f.p[STP_ST_LSE],
-                                    f.p[STP_ST_DCTX], (float *)f.p[STP_ST_DELTA], f.p[STP_ST_DQKV], hip_stream));
+                                    f.p[STP_ST_DCTX], (float *)f.p[STP_ST_DELTA], f.p[STP_ST_DQKV], lane, hip_stream));
       if (d->rope) RET_IF(stp_rope(ctx, d, f.p[STP_ST_DQKV], 1, hip_stream));
       g = gemm_base(d, T, h, 3 * a);
       g.A = f.p[STP_ST_DQKV]; g.lda = 3 * a;

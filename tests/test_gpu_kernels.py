@@ -208,7 +208,9 @@ def test_colsum(ctx, dtype, T, N):
 # ------------------------------------------------------------------ attention core
 ATTN_CASES = [("f32", 128, 1, 4, 64, True), ("f32", 52, 2, 2, 32, False), ("f32", 72, 1, 1, 128, True),
               ("bf16", 128, 1, 2, 128, True), ("bf16", 200, 1, 3, 128, True), ("bf16", 456, 2, 2, 64, True),
-              ("bf16", 328, 1, 2, 64, False), ("bf16", 1000, 1, 1, 128, False), ("bf16", 8, 1, 1, 128, True)]
+              ("bf16", 328, 1, 2, 64, False), ("bf16", 1000, 1, 1, 128, False), ("bf16", 8, 1, 1, 128, True),
+              # longer than one 1024-key / 1024-query chunk: the chunk partials and combine kernels
+              ("bf16", 2568, 1, 1, 128, True), ("bf16", 1288, 2, 2, 64, False), ("bf16", 2104, 1, 1, 64, True)]
 
 
 @pytest.mark.parametrize("dtype,seq,mbsz,n,d,causal", ATTN_CASES)
