@@ -132,6 +132,19 @@ def main():
     # ---- the timed region: K braided steps ------------------------------------------
     ms_braided = time_steps(lambda: ctx.braid_step(stg.stage, arr, sF, sB, sW), args.steps, args.warmup, torch)
 
+    # ---- sustained shader clock while braided steps run (probe wave on a side stream) -------------
+    probe_out = torch.zeros(2, dtype=torch.int64, device="cuda")
+    s_probe = torch.cuda.Stream()
+    n_probe = max(10, int(12.0 / ms_braided) + 4)
+    for i in range(n_probe):
+        ctx.braid_step(stg.stage, arr, sF, sB, sW)
+        if i == 2:
+            ctx.clock_probe(probe_out, 8.0, stream=s_probe)
+    torch.cuda.synchronize()
+    cyc, ticks = (int(v) for v in probe_out.tolist())
+    wall_khz = torch.cuda.get_device_properties(0).clock_rate if False else 100000   # wall clock: 100 MHz on gfx950
+    sustained_mhz = cyc / (ticks / wall_khz) / 1e3 if ticks else None
+
     # ---- the same op list on one stream, and the isolated units ----------------------
     ms_serial = time_steps(lambda: ctx.braid_step(stg.stage, arr, s0, s0, s0), args.steps, args.warmup, torch)
     f_ops = (stp.Op * 4)(*forward_ops(1, 1))
@@ -157,6 +170,9 @@ def main():
                                f"seq {T}, microbatch 1, tp {wl.tp}; step = F(mb1) braided with B+W(mb0), 1 layer",
                    "flops_per_step": total_flops},
         "mfma_util_frac_of_bf16_peak": total_flops / (ms_braided * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
+        "sustained_shader_clock_mhz": sustained_mhz,
+        "mfma_util_frac_at_sustained_clock": (total_flops / (ms_braided * 1e-3) / 1e12 /
+                                              (256 * 4096 * sustained_mhz * 1e6 / 1e12)) if sustained_mhz else None,
         "units": {
             "F": {"ms": ms_F, "tflops": fl["F"] / (ms_F * 1e-3) / 1e12},
             "B": {"ms": ms_B, "tflops": fl["B"] / (ms_B * 1e-3) / 1e12},

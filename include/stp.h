@@ -274,6 +274,13 @@ int stp_rope(stp_ctx *ctx, const stp_layer_desc *desc, void *qkv, int inverse, v
 int stp_colsum(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const void *x, float scale, float *out,
                int lane, void *hip_stream);
 
+
+/* Measurement aid: enqueues a one-wave kernel that spins for `milliseconds` of wall-clock time and
+ * writes {shader-clock cycles elapsed, wall-clock ticks elapsed} to device_out2[0..1] (int64; the wall
+ * clock ticks at hipDeviceAttributeWallClockRate kHz).  Run on a side stream while the units execute, it
+ * yields the sustained shader clock the MFMA roofline should be read against. */
+int stp_clock_probe(stp_ctx *ctx, long long *device_out2, double milliseconds, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

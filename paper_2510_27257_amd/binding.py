@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = [
     "stp_backward_input_unit", "stp_backward_weight_unit", "stp_braid_step", "stp_validate_ops",
     "stp_braid_reset", "stp_gemm", "stp_norm_forward", "stp_norm_backward", "stp_attention_forward",
     "stp_attention_backward", "stp_gelu_forward", "stp_gelu_backward", "stp_swiglu_forward",
-    "stp_swiglu_backward", "stp_rope", "stp_colsum",
+    "stp_swiglu_backward", "stp_rope", "stp_colsum", "stp_clock_probe",
 ]
 
 
@@ -133,6 +133,7 @@ def lib() -> C.CDLL:
     L.stp_swiglu_backward.argtypes = [vp, C.c_int, sz, vp, vp, vp, vp, vp, vp]
     L.stp_rope.argtypes = [vp, P(LayerDesc), vp, C.c_int, vp]
     L.stp_colsum.argtypes = [vp, C.c_int, i32, i32, vp, f32, vp, C.c_int, vp]
+    L.stp_clock_probe.argtypes = [vp, vp, C.c_double, vp]
     for name in EXPORTED_SYMBOLS:
         fn = getattr(L, name)
         if fn.restype is C.c_int or fn.restype is None or fn.restype == C.c_int:
@@ -301,6 +302,11 @@ class Context:
 
     def rope(self, desc, qkv, inverse=False, stream=None):
         self.check(self._lib.stp_rope(self._h, C.byref(desc), _ptr(qkv), int(inverse), _stream(stream)), "stp_rope")
+
+    def clock_probe(self, out2, milliseconds, stream=None):
+        """out2: int64 device tensor with 2 elements -> (shader cycles, wall ticks at 100 MHz-class rate)."""
+        self.check(self._lib.stp_clock_probe(self._h, _ptr(out2), float(milliseconds), _stream(stream)),
+                   "stp_clock_probe")
 
     def colsum(self, dtype, T, N, x, scale, out, lane=0, stream=None):
         self.check(self._lib.stp_colsum(self._h, dtype, T, N, _ptr(x), scale, _ptr(out), lane, _stream(stream)),

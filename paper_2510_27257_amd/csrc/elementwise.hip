@@ -524,3 +524,29 @@ int stp_launch_rowdot(stp_ctx *ctx, const stp_layer_desc *d, const void *a, cons
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }
+
+// ======================================================================
+// Clock probe for the measurements: one wave spins for `wall_ticks` ticks of the constant-rate
+// wall clock and reports how many shader-clock cycles passed meanwhile.  Launched on a side
+// stream while the units run, it gives the sustained shader clock the rooflines should be read
+// against (the chip lowers its clock under matrix-core load).
+// ======================================================================
+__global__ void clock_probe_kernel(long long *out, long long wall_ticks) {
+  const long long w0 = wall_clock64(), c0 = clock64();
+  long long w = w0;
+  while (w - w0 < wall_ticks) w = wall_clock64();   // bounded: the wall clock always advances
+  out[0] = clock64() - c0;
+  out[1] = w - w0;
+}
+
+extern "C" int stp_clock_probe(stp_ctx *ctx, long long *device_out2, double milliseconds, void *hip_stream) {
+  if (!ctx) return STP_EINVAL;
+  if (!device_out2) return stp_fail(ctx, STP_EINVAL, "stp_clock_probe: null pointer%s");
+  if (!(milliseconds > 0.0) || milliseconds > 1000.0) return stp_fail(ctx, STP_EINVAL, "stp_clock_probe: window must be in (0, 1000] ms%s");
+  int rate_khz = 0;
+  STP_HIP(ctx, hipDeviceGetAttribute(&rate_khz, hipDeviceAttributeWallClockRate, ctx->device));
+  hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, device_out2,
+                     (long long)(milliseconds * rate_khz));
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
