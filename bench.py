@@ -79,6 +79,56 @@ def gemm_leg(ctx, wl, reps, torch, stp):
     return avg_ms, sum(2 * M * N * K for (M, N, K) in shapes) / len(shapes)
 
 
+def stage_bench(ctx, args, torch, stp, synth):
+    """Makespan of one stage's braided unit sequence (warm-up F, F&B with W separated, F&W, steady F&BW,
+    degraded BW / B, cool-down W) against the same sequence on one stream and the sum of isolated units."""
+    from paper_2510_27257_amd.binding import OP_B
+    from paper_2510_27257_amd.stage import StageOnDevice, backward_ops, forward_ops, stage_sequence, weight_ops
+    lm = synth.WORKLOADS["gpt7b_tp8_s4096"]
+    if args.stage == "pp4":
+        layers, cb = [lm] * 4, None
+    else:
+        layers, cb = [synth.WORKLOADS["vit"]] * 2 + [lm] * 2, [0, 0, 1, 0, 0]
+    n_mb = 8
+    stg = StageOnDevice(ctx, layers, n_mb, seed=0, chain_break=cb)
+    stg.load_inputs()
+    L = len(layers)
+    steps = [(stp.Op * len(st))(*st) for st in stage_sequence(L, n_mb)]
+    sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    s0 = torch.cuda.current_stream()
+
+    def run(streams):
+        ctx.braid_reset()
+        for arr in steps:
+            ctx.braid_step(stg.stage, arr, *streams)
+
+    reps = max(3, args.steps // 6)
+    ms_braided = time_steps(lambda: run((sF, sB, sW)), reps, 1, torch)
+    ms_serial = time_steps(lambda: run((s0, s0, s0)), reps, 1, torch)
+    # isolated units, per layer kind: F, B, W of one layer-microbatch alone on one stream
+    ctx.braid_reset()
+    ctx.braid_step(stg.stage, (stp.Op * (4 * L))(*forward_ops(L, 0)), s0, s0, s0)
+    ctx.braid_step(stg.stage, (stp.Op * (4 * L))(*backward_ops(L, 0, OP_B)), s0, s0, s0)
+    torch.cuda.synchronize()
+    sum_iso, flops = 0.0, 0
+    for l in range(L):
+        f_ops = (stp.Op * 4)(*[o for o in forward_ops(L, 0) if o.layer == l])
+        b_ops = (stp.Op * 4)(*[o for o in backward_ops(L, 0, OP_B) if o.layer == l])
+        w_ops = (stp.Op * 2)(*[o for o in weight_ops(L, 0) if o.layer == l])
+        for ops in (f_ops, b_ops, w_ops):
+            sum_iso += n_mb * time_steps(lambda: ctx.braid_step(stg.stage, ops, s0, s0, s0), 10, 2, torch)
+        fl = unit_flops(layers[l])
+        flops += n_mb * (fl["F"] + fl["B"] + fl["W"])
+    print(json.dumps({
+        "metric": "braided stage sequence TFLOP/s", "value": flops / (ms_braided * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": ms_braided, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"stage {args.stage}: {L} layers x {n_mb} microbatches, sequence of {len(steps)} braided blocks",
+                   "flops_per_step": flops},
+        "braid": {"makespan_ms": ms_braided, "serialized_ms": ms_serial, "sum_isolated_ms": sum_iso,
+                  "makespan_over_sum_isolated": ms_braided / sum_iso}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -86,6 +136,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="gpt7b_tp8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stage", choices=["pp4", "mllm"], default=None,
+                    help="time one pipeline stage's whole braided sequence instead of the single block: "
+                         "pp4 = 4 GPT-7B TP=8 layers at seq 4096, 8 microbatches; mllm = 2 ViT layers + 2 such "
+                         "LM layers, 8 microbatches")
     ap.add_argument("--only-gemm", action="store_true",
                     help="run only the dominant-kernel leg plus a 1 GiB device copy (counter calibration runs)")
     args = ap.parse_args()
@@ -115,6 +169,10 @@ def main():
         for _ in range(5):
             dst.copy_(src)          # plain copy of known size: 1 GiB read + 1 GiB written per launch
         torch.cuda.synchronize()
+        ctx.close()
+        return
+    if args.stage:
+        stage_bench(ctx, args, torch, stp, synth)
         ctx.close()
         return
     stg = StageOnDevice(ctx, [wl], n_mb=2, seed=0)

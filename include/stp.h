@@ -148,7 +148,13 @@ typedef struct {
                                  next layer's input shape unless chain_break[l+1] is set. */
   void **grad;                /* same indexing: gradient w.r.t. act[...] */
   const int32_t *chain_break; /* NULL, or [n_layers+1]: chain_break[l] = 1 means layer l starts a new
-                                 chain (its act/grad slot is an independent input/output) */
+                                 chain: act[l*M+mb] is that chain's own input (grad[l*M+mb] receives its
+                                 input gradient), and layer l-1, which ends the previous chain, writes its
+                                 output to tail_act[(l-1)*M+mb] and reads its upstream gradient from
+                                 tail_grad[(l-1)*M+mb] instead */
+  void **tail_act;            /* [n_layers * n_microbatches]; only entries of chain-ending interior layers
+                                 are used; may be NULL when chain_break has no interior 1 */
+  void **tail_grad;           /* same indexing */
 } stp_stage;
 
 /* Called on the issuing stream's behalf at every TP boundary inside

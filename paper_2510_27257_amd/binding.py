@@ -69,7 +69,8 @@ class Stage(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("n_microbatches", C.c_int32), ("desc", C.POINTER(LayerDesc)),
                 ("w", C.POINTER(Weights)), ("g", C.POINTER(WGrads)), ("stash", C.POINTER(Stash)),
                 ("act", C.POINTER(C.c_void_p)), ("grad", C.POINTER(C.c_void_p)),
-                ("chain_break", C.POINTER(C.c_int32))]
+                ("chain_break", C.POINTER(C.c_int32)),
+                ("tail_act", C.POINTER(C.c_void_p)), ("tail_grad", C.POINTER(C.c_void_p))]
 
 
 class GemmArgs(C.Structure):

@@ -178,9 +178,12 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
     for (int f = 0; f < STP_ST_NFIELDS; f++) stp_stash_field(d, f, &off[f], &nbytes);
     char *sb = (char *)stash->base;
     void *x = st->act[(size_t)o.layer * MB + o.microbatch];
-    void *x_out = st->act[(size_t)(o.layer + 1) * MB + o.microbatch];
+    // a layer that ends a chain in the middle of the stage has its own output / upstream-gradient slots
+    const bool tail = o.layer + 1 < L && st->chain_break && st->chain_break[o.layer + 1];
+    if (tail && (!st->tail_act || !st->tail_grad)) { rc = stp_fail(ctx, STP_EINVAL, "stp_braid_step: chain break without tail slots%s"); break; }
+    void *x_out = tail ? st->tail_act[(size_t)o.layer * MB + o.microbatch] : st->act[(size_t)(o.layer + 1) * MB + o.microbatch];
     void *dx = st->grad[(size_t)o.layer * MB + o.microbatch];
-    void *dx_out = st->grad[(size_t)(o.layer + 1) * MB + o.microbatch];
+    void *dx_out = tail ? st->tail_grad[(size_t)o.layer * MB + o.microbatch] : st->grad[(size_t)(o.layer + 1) * MB + o.microbatch];
     void *x_attn = sb + off[STP_ST_X_ATTN], *dx_attn = sb + off[STP_ST_DX_ATTN];
     void *dz = sb + off[STP_ST_DZ], *dx_ln = sb + off[STP_ST_DX_LN];
     const size_t act_bytes = (size_t)d->seq * d->mbsz * d->hidden * stp_elem_size(d->dtype);

@@ -46,27 +46,37 @@ class StageOnDevice:
                 stash_arr[l * n_mb + mb] = B.Stash(base=m.data_ptr(), bytes=nbytes)
         self.stash_arr = stash_arr
         self.chain_break = list(chain_break) if chain_break is not None else [0] * (L + 1)
-        # slot l holds the input of layer l; at a chain break the slot of layer l is an independent input
-        # and the previous chain's output goes to a separate tensor kept in out_of_chain
-        self.act, self.grad = [], []
+        # slot l (l < L) holds the input of layer l, slot L the output of the last layer; a layer that ends a
+        # chain in the middle of the stage gets its own output / upstream-gradient ("tail") slots
+        self.act, self.grad, self.tail_act, self.tail_grad = [], [], {}, {}
         act_arr, grad_arr = (C.c_void_p * ((L + 1) * n_mb))(), (C.c_void_p * ((L + 1) * n_mb))()
+        tail_act_arr, tail_grad_arr = (C.c_void_p * (L * n_mb))(), (C.c_void_p * (L * n_mb))()
+
+        def new_pair(wl):
+            td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+            a = torch.zeros((wl.seq, wl.hidden), dtype=td, device="cuda")
+            return a, torch.zeros_like(a)
+
         for l in range(L + 1):
-            wl = self.layers[min(l, L - 1)]
-            if l == L or (l > 0 and not self.chain_break[l]):
-                wl_shape = self.layers[l - 1] if l > 0 else wl
-            else:
-                wl_shape = wl
-            td = torch.bfloat16 if wl_shape.dtype == "bf16" else torch.float32
+            wl_shape = self.layers[l] if l < L else self.layers[L - 1]
             for mb in range(n_mb):
-                a = torch.zeros((wl_shape.seq, wl_shape.hidden), dtype=td, device="cuda")
-                g = torch.zeros_like(a)
+                a, g = new_pair(wl_shape)
                 self.act.append(a); self.grad.append(g)
                 act_arr[l * n_mb + mb] = a.data_ptr()
                 grad_arr[l * n_mb + mb] = g.data_ptr()
+        for l in range(L - 1):
+            if self.chain_break[l + 1]:
+                for mb in range(n_mb):
+                    a, g = new_pair(self.layers[l])
+                    self.tail_act[(l, mb)], self.tail_grad[(l, mb)] = a, g
+                    tail_act_arr[l * n_mb + mb] = a.data_ptr()
+                    tail_grad_arr[l * n_mb + mb] = g.data_ptr()
         self.act_arr, self.grad_arr = act_arr, grad_arr
+        self.tail_act_arr, self.tail_grad_arr = tail_act_arr, tail_grad_arr
         self.cb_arr = (C.c_int32 * (L + 1))(*self.chain_break)
         self.stage = B.Stage(n_layers=L, n_microbatches=n_mb, desc=self.descs, w=w_arr, g=g_arr, stash=stash_arr,
-                             act=act_arr, grad=grad_arr, chain_break=self.cb_arr)
+                             act=act_arr, grad=grad_arr, chain_break=self.cb_arr, tail_act=tail_act_arr,
+                             tail_grad=tail_grad_arr)
         ctx.ensure_workspace(list(self.descs))
 
     # ---- slots ----------------------------------------------------------------
@@ -76,6 +86,13 @@ class StageOnDevice:
     def grad_slot(self, l: int, mb: int) -> torch.Tensor:
         return self.grad[l * self.n_mb + mb]
 
+    def chain_out(self, l: int, mb: int) -> torch.Tensor:
+        """Output of layer l when it ends a chain in the middle of the stage."""
+        return self.tail_act[(l, mb)]
+
+    def chain_out_grad(self, l: int, mb: int) -> torch.Tensor:
+        return self.tail_grad[(l, mb)]
+
     def field(self, l: int, mb: int, name: str) -> torch.Tensor:
         off, n = self.ctx.stash_field(self.descs[l], name)
         raw = self.stash_mem[l * self.n_mb + mb][off:off + n]
@@ -83,14 +100,29 @@ class StageOnDevice:
             return raw.view(torch.float32)
         return raw.view(torch.bfloat16 if self.layers[l].dtype == "bf16" else torch.float32)
 
-    def load_inputs(self):
-        """Seeded N(0,1) stage inputs (slot 0) and upstream gradients (slot L) for every microbatch."""
+    def chains(self):
+        """[(first_layer, last_layer)] of the independent chains of the stage."""
         L = len(self.layers)
-        for mb in range(self.n_mb):
-            x = synth.make_activation(self.layers[0], self.seed, f"x.mb{mb}")
-            dy = synth.make_activation(self.layers[-1], self.seed, f"dy.mb{mb}")
-            self.act_slot(0, mb).copy_(_to_dev(x, self.layers[0].dtype))
-            self.grad_slot(L, mb).copy_(_to_dev(dy, self.layers[-1].dtype))
+        starts = [l for l in range(L) if l == 0 or self.chain_break[l]]
+        return [(a, (starts[i + 1] if i + 1 < len(starts) else L) - 1) for i, a in enumerate(starts)]
+
+    def chain_output(self, last_layer: int, mb: int) -> torch.Tensor:
+        L = len(self.layers)
+        return self.act_slot(L, mb) if last_layer == L - 1 else self.tail_act[(last_layer, mb)]
+
+    def chain_output_grad(self, last_layer: int, mb: int) -> torch.Tensor:
+        L = len(self.layers)
+        return self.grad_slot(L, mb) if last_layer == L - 1 else self.tail_grad[(last_layer, mb)]
+
+    def load_inputs(self):
+        """Seeded N(0,1) inputs of every chain and upstream gradients of every chain end, per microbatch."""
+        for ci, (first, last) in enumerate(self.chains()):
+            tag = "" if ci == 0 and len(self.chains()) == 1 else f"c{ci}."
+            for mb in range(self.n_mb):
+                x = synth.make_activation(self.layers[first], self.seed, f"{tag}x.mb{mb}")
+                dy = synth.make_activation(self.layers[last], self.seed, f"{tag}dy.mb{mb}")
+                self.act_slot(first, mb).copy_(_to_dev(x, self.layers[first].dtype))
+                self.chain_output_grad(last, mb).copy_(_to_dev(dy, self.layers[last].dtype))
 
     def zero_grads(self):
         for gd in self.g_dev:

@@ -28,6 +28,7 @@ def test_struct_sizes_match_header():
     assert C.sizeof(stp.LayerDesc) == 15 * 4
     assert C.sizeof(stp.Weights) == 13 * 8 and C.sizeof(stp.WGrads) == 13 * 8
     assert C.sizeof(stp.Op) == 16 and C.sizeof(stp.Stash) == 16
+    assert C.sizeof(stp.Stage) == 8 + 9 * 8
 
 
 def test_desc_checks_and_sizes_need_no_gpu():

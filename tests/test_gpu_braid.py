@@ -14,7 +14,11 @@ from paper_2510_27257_amd.binding import Op, OP_F, OP_B, OP_W, OP_BW, PRE_ATTN, 
 from paper_2510_27257_amd.stage import StageOnDevice, stage_sequence, braid, forward_ops, backward_ops
 from paper_2510_27257_amd.synth import Workload
 from oracle import stp_oracle as O
-from harness import TOL, oracle_cfg, oracle_layer_pass, rel_err, to_host
+from harness import TOL, oracle_cfg, oracle_layer_pass, rel_err, to_host, to_dev
+
+
+def to_dev_like(x, wl):
+    return to_dev(x, wl.dtype)
 
 
 @pytest.fixture(scope="module")
@@ -34,7 +38,7 @@ def run_sequence(ctx, stg, streams):
 
 
 def snapshot(stg):
-    out = [t.clone() for t in stg.act] + [t.clone() for t in stg.grad]
+    out = [t.clone() for t in stg.act] + [t.clone() for t in stg.grad] + [t.clone() for t in stg.tail_act.values()]
     for gd in stg.g_dev:
         out += [gd[k].clone() for k in sorted(gd)]
     return out
@@ -129,3 +133,54 @@ def test_weight_unit_before_its_backward_is_rejected(ctx):
     with pytest.raises(stp.StpError):
         ctx.braid_step(stg.stage, [Op(OP_W, MLP, 0, 0)], s, s, s)
     torch.cuda.synchronize()
+
+
+def test_heterogeneous_stage_with_chain_break(ctx):
+    """A stage holding two independent chains (ViT-style bidirectional layers, then LM layers of another
+    width): slot 2 is the LM chain's own input, the ViT chain's output goes to layer 1's tail slot."""
+    vit = Workload("v", 128, 2, 64, 264, 72, 1, causal=False)
+    lm = Workload("m", 256, 2, 128, 520, 136, 8)
+    layers = [vit, vit, lm, lm]
+    n_mb = 3
+    stg = StageOnDevice(ctx, layers, n_mb, seed=5, chain_break=[0, 0, 1, 0, 0])
+    # chain inputs / upstream gradients: ViT chain slot 0 (in), tail of layer 1 (out); LM chain slots 2 (in), 4 (out)
+    for mb in range(n_mb):
+        stg.act_slot(0, mb).copy_(to_dev_like(synth.make_activation(vit, 5, f"vx.mb{mb}"), vit))
+        stg.act_slot(2, mb).copy_(to_dev_like(synth.make_activation(lm, 5, f"lx.mb{mb}"), lm))
+        stg.grad_slot(4, mb).copy_(to_dev_like(synth.make_activation(lm, 5, f"ldy.mb{mb}"), lm))
+    s0 = torch.cuda.current_stream()
+    sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    # LM chain only (layers 2..3): F(mb) then braided with BW of the previous microbatch
+    def lm_f(mb):
+        return [Op(OP_F, u, l, mb) for l in (2, 3) for u in (PRE_ATTN, ATTN, PRE_MLP, MLP)]
+    def lm_b(mb):
+        return [Op(OP_BW, u, l, mb) for l in (3, 2) for u in (MLP, PRE_MLP, ATTN, PRE_ATTN)]
+    def vit_f(mb):
+        return [Op(OP_F, u, l, mb) for l in (0, 1) for u in (PRE_ATTN, ATTN, PRE_MLP, MLP)]
+    results = []
+    for streams in ((s0, s0, s0), (sF, sB, sW)):
+        ctx.braid_reset()
+        stg.zero_grads()
+        ctx.braid_step(stg.stage, vit_f(0) + lm_f(0), *streams)          # two chains in one forward list
+        ctx.braid_step(stg.stage, braid(vit_f(1) + lm_f(1), lm_b(0)), *streams)
+        ctx.braid_step(stg.stage, braid(vit_f(2) + lm_f(2), lm_b(1)), *streams)
+        ctx.braid_step(stg.stage, lm_b(2), *streams)
+        torch.cuda.synchronize()
+        results.append(snapshot(stg))
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
+    # oracle for the LM chain of microbatch 1 and the ViT chain of microbatch 2
+    tol = TOL["bf16"]
+    def chain(ls, idx, x):
+        for l in idx:
+            cfg, W = oracle_cfg(ls[l]), {k: v.astype(np.float64) for k, v in stg.w_host[l].items()}
+            st = {}
+            O.forward_unit(cfg, O.PRE_ATTN, W, st, x_in=x)
+            xa = O.forward_unit(cfg, O.ATTN, W, st, x_resid=x)
+            O.forward_unit(cfg, O.PRE_MLP, W, st, x_in=xa)
+            x = O.forward_unit(cfg, O.MLP, W, st, x_resid=xa)
+        return x
+    ref_lm = chain(layers, (2, 3), synth.make_activation(lm, 5, "lx.mb1").astype(np.float64))
+    assert rel_err(to_host(stg.act_slot(4, 1)), ref_lm) < tol
+    ref_vit = chain(layers, (0, 1), synth.make_activation(vit, 5, "vx.mb2").astype(np.float64))
+    assert rel_err(to_host(stg.chain_out(1, 2)), ref_vit) < tol

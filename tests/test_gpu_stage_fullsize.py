@@ -1,0 +1,56 @@
+"""One pipeline stage at full size (4 GPT-7B TP=8 layers at seq 4096, 8 microbatches) through the whole
+braided sequence on three streams; the first and last microbatch are followed through all four layers
+by the fp64 oracle (stage output and input gradient, element by element)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2510_27257_amd as stp
+from paper_2510_27257_amd import synth
+from paper_2510_27257_amd.stage import StageOnDevice, stage_sequence
+from oracle import stp_oracle as O
+from harness import TOL, oracle_cfg, rel_err, to_host
+
+
+def test_four_layer_stage_sequence_matches_oracle():
+    wl = synth.WORKLOADS["gpt7b_tp8_s4096"]
+    L, n_mb = 4, 8
+    ctx = stp.Context(0)
+    stg = StageOnDevice(ctx, [wl] * L, n_mb, seed=0)
+    stg.load_inputs()
+    sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    ctx.braid_reset()
+    for step in stage_sequence(L, n_mb):
+        ctx.braid_step(stg.stage, step, sF, sB, sW)
+    torch.cuda.synchronize()
+    print("GPU sequence done; running the oracle for microbatches 0 and 7", flush=True)
+    cfg = oracle_cfg(wl)
+    errs = {}
+    for mb in (0, n_mb - 1):
+        x = synth.make_activation(wl, 0, f"x.mb{mb}").astype(np.float64)
+        stashes = []
+        for l in range(L):
+            W = {k: v.astype(np.float64) for k, v in stg.w_host[l].items()}
+            st = {}
+            O.forward_unit(cfg, O.PRE_ATTN, W, st, x_in=x)
+            xa = O.forward_unit(cfg, O.ATTN, W, st, x_resid=x)
+            O.forward_unit(cfg, O.PRE_MLP, W, st, x_in=xa)
+            x = O.forward_unit(cfg, O.MLP, W, st, x_resid=xa)
+            stashes.append(st)
+        errs[f"out.mb{mb}"] = rel_err(to_host(stg.act_slot(L, mb)), x)
+        dy = synth.make_activation(wl, 0, f"dy.mb{mb}").astype(np.float64)
+        for l in reversed(range(L)):
+            W = {k: v.astype(np.float64) for k, v in stg.w_host[l].items()}
+            st = stashes[l]
+            dz = O.backward_input_unit(cfg, O.MLP, W, st, dy)
+            dxa = O.backward_input_unit(cfg, O.PRE_MLP, W, st, dz, d_resid=dy)
+            dxl = O.backward_input_unit(cfg, O.ATTN, W, st, dxa)
+            dy = O.backward_input_unit(cfg, O.PRE_ATTN, W, st, dxl, d_resid=dxa)
+            stashes[l] = None
+        errs[f"dx.mb{mb}"] = rel_err(to_host(stg.grad_slot(0, mb)), dy)
+        print(errs, flush=True)
+    ctx.close()
+    bad = {k: v for k, v in errs.items() if not v < TOL["bf16"]}
+    assert not bad, bad
