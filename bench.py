@@ -79,6 +79,50 @@ def gemm_leg(ctx, wl, reps, torch, stp):
     return avg_ms, sum(2 * M * N * K for (M, N, K) in shapes) / len(shapes)
 
 
+HBM_PEAK_GBS = 8000.0
+
+
+def hbm_leg(ctx, wl, torch, stp):
+    """The HBM-bound kernels of the units at the workload's sizes, alone on the current stream: achieved
+    GB/s = algorithmic bytes (each tensor read or written once) / HIP-event time.  At these sizes (25-200 MB)
+    part of the traffic is served by the 256 MB last-level cache, so a figure can exceed what HBM alone gives."""
+    T, h, f, a = wl.seq, wl.hidden, wl.ffn_local, wl.attn_local
+    td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    es = 2 if wl.dtype == "bf16" else 4
+    code = stp.BF16 if wl.dtype == "bf16" else stp.F32
+    norm = stp.NORM_LN if wl.norm == "ln" else stp.NORM_RMS
+    mk = lambda *shape: torch.randn(*shape, device="cuda").to(td)
+    x, dy, dr, y = mk(T, h), mk(T, h), mk(T, h), torch.empty((T, h), device="cuda", dtype=td)
+    g, b = torch.ones(h, device="cuda").to(td), torch.zeros(h, device="cuda").to(td)
+    stats = torch.empty((T, 2), device="cuda")
+    dg, db, outb = torch.zeros(h, device="cuda"), torch.zeros(h, device="cuda"), torch.zeros(h, device="cuda")
+    hh, hd, hy = mk(T, f), mk(T, f), torch.empty((T, f), device="cuda", dtype=td)
+    legs = [
+        ("norm_fwd", 2 * T * h * es, lambda: ctx.norm_forward(code, norm, T, h, wl.eps, x, g, b, y, stats)),
+        ("norm_bwd_resid_dgamma", 4 * T * h * es,
+         lambda: ctx.norm_backward(code, norm, T, h, x, g, stats, dy, dr, y, dg, db)),
+        ("gelu_fwd", 2 * T * f * es, lambda: ctx.gelu_forward(code, T * f, hh, hy)),
+        ("gelu_bwd", 3 * T * f * es, lambda: ctx.gelu_backward(code, T * f, hh, hd, hy)),
+        ("swiglu_fwd", 3 * T * f * es, lambda: ctx.swiglu_forward(code, T * f, hh, hd, hy)),
+        ("colsum_T_h", T * h * es, lambda: ctx.colsum(code, T, h, x, 1.0, outb)),
+    ]
+    out = {}
+    for name, nbytes, fn in legs:
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(30):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 30
+        gbs = nbytes / ms / 1e6
+        out[name] = {"us": ms * 1e3, "GB/s": gbs, "frac_of_8TBs": gbs / HBM_PEAK_GBS, "bytes": nbytes}
+    return out
+
+
 def stage_bench(ctx, args, torch, stp, synth):
     """Makespan of one stage's braided unit sequence (warm-up F, F&B with W separated, F&W, steady F&BW,
     degraded BW / B, cool-down W) against the same sequence on one stream and the sum of isolated units."""
@@ -140,6 +184,7 @@ def main():
                     help="time one pipeline stage's whole braided sequence instead of the single block: "
                          "pp4 = 4 GPT-7B TP=8 layers at seq 4096, 8 microbatches; mllm = 2 ViT layers + 2 such "
                          "LM layers, 8 microbatches")
+    ap.add_argument("--print-gemm", action="store_true", help="with --only-gemm: print the leg's result as JSON")
     ap.add_argument("--only-gemm", action="store_true",
                     help="run only the dominant-kernel leg plus a 1 GiB device copy (counter calibration runs)")
     args = ap.parse_args()
@@ -163,7 +208,9 @@ def main():
 
     ctx = stp.Context(0)
     if args.only_gemm:
-        gemm_leg(ctx, wl, max(10, args.steps), torch, stp)
+        ms, fl = gemm_leg(ctx, wl, max(10, args.steps), torch, stp)
+        if args.print_gemm:
+            print(json.dumps({"avg_launch_ms": ms, "flops_per_launch": fl, "tflops": fl / (ms * 1e-3) / 1e12}))
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         for _ in range(5):
@@ -216,6 +263,8 @@ def main():
     gemm_avg_ms, gemm_flops_per_launch = gemm_leg(ctx, wl, max(10, args.steps), torch, stp)
     achieved = gemm_flops_per_launch / (gemm_avg_ms * 1e-3) / 1e12
 
+    hbm = hbm_leg(ctx, wl, torch, stp)
+
     result = {
         "metric": "braided F/B/W TFLOP/s, 7B layer TP=8 shard, seq 6144, 1 GPU",
         "value": total_flops / (ms_braided * 1e-3) / 1e12,
@@ -242,6 +291,7 @@ def main():
                      "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "avg_launch_ms": gemm_avg_ms,
                      "flops_per_launch": gemm_flops_per_launch, "traffic": None},
+        "hbm_kernels": hbm,
     }
 
     if not args.no_cpu_baseline:

@@ -175,22 +175,49 @@ __global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__rest
 }
 
 // ======================================================================
-// Column sums (bias gradients): stage 1 sums slabs of 64 rows, 8 columns per thread.
+// Column sums (bias gradients), stage 1: a 256-thread group owns a 64-row x 256-column patch as
+// 8 row-lanes x 32 column chunks; every thread adds 8 rows (8 independent 16-byte loads in flight),
+// the 8 row-lanes are combined through LDS in a fixed order, and the patch sum goes to the
+// workspace; partial_reduce_kernel adds the patches of a column.
 // ======================================================================
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ x, int rows, int n,
                                                      float *__restrict__ partial) {
-  int col = (blockIdx.x * 256 + threadIdx.x) * 8;
-  if (col >= n) return;
-  int r0 = blockIdx.y * 64, r1 = min(rows, r0 + 64);
+  __shared__ float red[8][32][9];
+  const int cc = threadIdx.x & 31, rl = threadIdx.x >> 5;
+  const int col = (blockIdx.x * 32 + cc) * 8;
+  const int r0 = blockIdx.y * 64;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int r = r0; r < r1; r++) {
-    float v[8];
-    Vec8<T>::load(x + (size_t)r * n + col, v);
+  if (col < n) {
+    float v[8][8];
 #pragma unroll
-    for (int i = 0; i < 8; i++) acc[i] += v[i];
+    for (int u = 0; u < 8; u++) {
+      const int r = r0 + rl + 8 * u;
+      if (r < rows) Vec8<T>::load(x + (size_t)r * n + col, v[u]);
+      else {
+#pragma unroll
+        for (int i = 0; i < 8; i++) v[u][i] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; u++)
+#pragma unroll
+      for (int i = 0; i < 8; i++) acc[i] += v[u][i];
   }
-  Vec8<float>::store(partial + (size_t)blockIdx.y * n + col, acc);
+#pragma unroll
+  for (int i = 0; i < 8; i++) red[rl][cc][i] = acc[i];
+  __syncthreads();
+  if (rl == 0 && col < n) {
+    float s[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      float t = 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; k++) t += red[k][cc][i];
+      s[i] = t;
+    }
+    Vec8<float>::store(partial + (size_t)blockIdx.y * n + col, s);
+  }
 }
 
 // ======================================================================
@@ -434,7 +461,7 @@ extern "C" int stp_colsum(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const v
   size_t need = (size_t)slabs * N * sizeof(float);
   if (!ws || lane_bytes < need) return stp_fail(ctx, STP_ENOSPACE, "stp_colsum: workspace lane too small%s (need %ld bytes)", "", (long)need);
   float *partial = (float *)ws;
-  dim3 grid((N / 8 + 255) / 256, slabs), block(256);
+  dim3 grid((N / 8 + 31) / 32, slabs), block(256);
   if (dtype == STP_BF16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)x, T, N, partial);
   else hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float *)x, T, N, partial);
   STP_LAUNCH_CHECK(ctx);
