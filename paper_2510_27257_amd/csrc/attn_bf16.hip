@@ -147,30 +147,40 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
       // ---- online softmax in the log2 domain; accumulator v of lane l is key
       //      kv0 + 32*jb + 8*(v/4) + 4*(l/32) + v%4, query l%32
       const bool need_mask = (causal && kv0 + 63 > q_wave0) || (kv0 + 64 > seq);
-      auto scale_mask_max = [&](f32x16_t &sc, int jb, float mx) {
+      // raw scores are kept; the 1/sqrt(d) log2(e) factor is folded into the exponent's FMA
+      auto mask_max = [&](f32x16_t &sc, int jb, float mx) {
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-          float x = sc[v] * scale_log2;
           if (need_mask) {
             int kv = kv0 + 32 * jb + 8 * (v >> 2) + 4 * lg + (v & 3);
-            if ((causal && kv > qg) || kv >= seq) x = -INFINITY;
+            if ((causal && kv > qg) || kv >= seq) sc[v] = -INFINITY;
           }
-          sc[v] = x;
-          mx = fmaxf(mx, x);
+          mx = fmaxf(mx, sc[v]);
         }
         return mx;
       };
-      float mx = scale_mask_max(sc0, 0, -INFINITY);
-      mx = scale_mask_max(sc1, 1, mx);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m, mx);
-      // a query row that has seen no admissible key yet keeps m = -inf: use a finite reference
-      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-      const float corr = __builtin_amdgcn_exp2f(m - m_ref);
+      float mx = mask_max(sc0, 0, -INFINITY);
+      mx = mask_max(sc1, 1, mx);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;      // scale > 0: max and scaling commute
+      // Lazy rescaling: the reference m only moves when the block maximum exceeds it by more than 2^8,
+      // so exponentials stay below 256 (harmless in fp32 / bf16) and the O rescale is skipped on almost
+      // every block.  Softmax is invariant to the reference as long as l, O and P use the same one.
+      // A query row that has seen no admissible key keeps m = -inf.
+      const float m_new = (mx > m + 8.0f) ? mx : m;
+      if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {
+        const float corr = __builtin_amdgcn_exp2f(m - (m_new == -INFINITY ? 0.f : m_new));
+        l *= corr;
+#pragma unroll
+        for (int i = 0; i < D / 32; i++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) o[i][v] *= corr;
+        m = m_new;
+      }
+      const float neg_ref = m == -INFINITY ? 0.f : -m;
       auto exp_sum = [&](f32x16_t &sc, float rs) {
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-          float p = __builtin_amdgcn_exp2f(sc[v] - m_ref);
+          float p = __builtin_amdgcn_exp2f(fmaf(sc[v], scale_log2, neg_ref));
           sc[v] = p;
           rs += p;
         }
@@ -179,12 +189,7 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
       float rs = exp_sum(sc0, 0.f);
       rs = exp_sum(sc1, rs);
       rs += __shfl_xor(rs, 32, 64);
-      l = l * corr + rs;
-      m = m_new;
-#pragma unroll
-      for (int i = 0; i < D / 32; i++)
-#pragma unroll
-        for (int v = 0; v < 16; v++) o[i][v] *= corr;
+      l += rs;
 
       // ---- O^T[d, q] += V^T P^T ; k-slot i of lane-half g in step (jb, t) is key 32*jb + 16*t + 8*(i/4) + 4*g + i%4
       auto pv = [&](const f32x16_t &sc, int jb) {
