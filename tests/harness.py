@@ -44,9 +44,9 @@ TOL = {"f32": 1e-5, "bf16": 2e-2}
 class LayerOnDevice:
     """One layer's weights, fp32 gradient accumulators and per-microbatch stashes on the GPU."""
 
-    def __init__(self, ctx: stp.Context, wl: synth.Workload, seed: int, layer: int = 0, n_mb: int = 1):
-        self.ctx, self.wl = ctx, wl
-        self.desc = stp.make_desc(wl)
+    def __init__(self, ctx: stp.Context, wl: synth.Workload, seed: int, layer: int = 0, n_mb: int = 1, mbsz: int = 1):
+        self.ctx, self.wl, self.mbsz = ctx, wl, mbsz
+        self.desc = stp.make_desc(wl, mbsz=mbsz)
         self.tdtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
         self.w_host = synth.make_weights(wl, seed, layer)
         self.w_dev = {k: to_dev(v, wl.dtype) for k, v in self.w_host.items()}
@@ -67,7 +67,7 @@ class LayerOnDevice:
         return raw.view(self.tdtype)
 
     def new_act(self) -> torch.Tensor:
-        return torch.empty((self.wl.seq, self.wl.hidden), dtype=self.tdtype, device="cuda")
+        return torch.empty((self.wl.seq * self.mbsz, self.wl.hidden), dtype=self.tdtype, device="cuda")
 
     def w64(self):
         return {k: v.astype(np.float64) for k, v in self.w_host.items()}

@@ -59,6 +59,26 @@ def test_units_match_oracle(ctx, name):
     assert not bad, f"{name}: over tolerance {tol}: {bad}\nall: {errs}"
 
 
+@pytest.mark.parametrize("name", ["gpt_bf16", "gpt_fp32_tp2"])
+def test_units_with_two_sequences_per_microbatch(ctx, name):
+    """mbsz = 2: tokens = 2 * seq; attention must not mix the two sequences, everything else is row-wise."""
+    wl = CASES[name]
+    tol = TOL[wl.dtype]
+    lay = LayerOnDevice(ctx, wl, seed=4, mbsz=2)
+    Xs = [synth.make_activation(wl, 4, f"x.s{i}") for i in range(2)]
+    dOs = [synth.make_activation(wl, 4, f"dy.s{i}") for i in range(2)]
+    got = gpu_layer_pass(ctx, lay, to_dev(np.concatenate(Xs), wl.dtype), to_dev(np.concatenate(dOs), wl.dtype))
+    torch.cuda.synchronize()
+    g_ref, outs, dxs = {}, [], []
+    for X, dO in zip(Xs, dOs):   # the oracle sees the two sequences as two microbatches of one sequence
+        ref, _, _ = oracle_layer_pass(oracle_cfg(wl), lay.w64(), X.astype(np.float64), dO.astype(np.float64), grads=g_ref)
+        outs.append(ref["x_out"]); dxs.append(ref["dx"])
+    assert rel_err(to_host(got["x_out"]), np.concatenate(outs)) < tol
+    assert rel_err(to_host(got["dx"]), np.concatenate(dxs)) < tol
+    for k, r in g_ref.items():
+        assert rel_err(to_host(lay.g_dev[k]), r) < tol, k
+
+
 def test_weight_grads_accumulate_across_microbatches(ctx):
     wl = CASES["gpt_fp32_tp2"]
     lay = LayerOnDevice(ctx, wl, seed=3, n_mb=2)
