@@ -50,6 +50,9 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
     if r.returncode != 0:
         print(r.stdout, file=sys.stderr)
         raise RuntimeError("link failed")
+    # a kernel whose host stub was dropped shows up only as an unresolved symbol at load time
+    import ctypes
+    ctypes.CDLL(LIB)
     if verbose:
         print(f"[build] wrote {LIB}")
     return LIB

@@ -24,6 +24,7 @@
 //     in that XCD's L2.
 #pragma once
 #include "common.h"
+#include <utility>
 
 namespace {
 
@@ -267,97 +268,140 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
 
 
 // =====================================================================================================
-// 256 x 256 kernel with direct-to-LDS loads and a 4-stage pipeline (the path every large GEMM takes).
+// Kernel with direct-to-LDS loads and a 4-stage pipeline (the path every large GEMM takes).
 //
-// global_load_lds_dwordx4 moves 16 bytes per lane from global memory straight into LDS (lane i of a
+// buffer_load_dwordx4 ... lds moves 16 bytes per lane from global memory straight into LDS (lane i of a
 // wave instruction lands at M0 + 16*i): no staging registers, no ds_write, and the loads of three
-// K-tiles (32 deep each) stay in flight behind the MFMAs of the current one, which is what it takes
-// to cover HBM / L2 latency with two waves per SIMD.  A wave instruction fills 1 KB of LDS
-// contiguously, so padding is impossible; bank conflicts are avoided by permuting WHICH global chunk
-// each lane fetches (an XOR swizzle applied on the global side and undone in the fragment address):
+// K-tiles (32 deep each) stay in flight behind the MFMAs of the current one.  The buffer form (resource
+// descriptor in SGPRs, one 32-bit byte offset per lane, the K position in a scalar offset) is used
+// because the issue of a load with 64-bit per-lane addresses holds the SIMD's vector register ports
+// long enough to stall the MFMAs of the other wave on that SIMD (measured: about 15 % of a K-tile).
+// A wave instruction fills 1 KB of LDS contiguously, so padding is impossible; bank conflicts are
+// avoided by permuting WHICH global chunk each lane fetches (an XOR swizzle applied on the global
+// side and undone in the fragment address):
 //   k-contiguous operand : tile [rows][32], 4 chunks per row; chunk c of row r sits in slot c ^ ((r>>2)&3)
 //   row-contiguous operand: tile [32][rows], rows/8 chunks per k-row; chunk c of k-row k sits in slot
 //                           c ^ (4*(k&3))   (read back with ds_read_b64_tr_b16)
-// Synchronisation is explicit: the compiler does not track these loads, so each K-tile starts with
-// s_waitcnt vmcnt(2 tiles' worth) + s_barrier (tile kt has landed for every wave, and every wave is done
-// reading the stage that is refilled next).  Rows past M / N are fetched from a clamped (valid)
-// address and never stored; K must be a multiple of 32.
+//
+// Schedule.  Two waves per SIMD run freely (no phase lock); each wave software-pipelines its fragments:
+// the LDS reads of the next 16-deep step are issued before the 8..16 MFMAs of the current one, so LDS
+// latency hides behind the wave's own MFMAs and the other wave on the SIMD fills what is left.  All
+// fragment reads are inline assembly with explicit lgkmcnt waits: the compiler neither tracks the
+// direct-to-LDS loads nor may it order LDS reads behind them (through builtins it would wait for
+// vmcnt(0) before every transposing read).  One s_barrier per K-tile, between its two steps:
+//     s_waitcnt vmcnt(2 tiles' worth) lgkmcnt(0) ; s_barrier
+// after it tile kt+1 has landed for every wave, and no wave has a read of stage kt outstanding (both
+// fragment sets of tile kt are in registers), so stage kt is refilled with tile kt+4 right there.
+// Rows past M / N are fetched from a clamped (valid) address and never stored; K must be a multiple
+// of 32 and each operand must span less than 2 GiB.
 // =====================================================================================================
 constexpr int DK = 32;         // K-tile depth of the DMA kernel
 constexpr int DSTAGES = 4;
 
 typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-typedef const void __attribute__((address_space(1))) * gptr_t;
 typedef void __attribute__((address_space(3))) * lptr_t;
+
+// The result of these reads is valid only after lds_wait<N>() + lds_tie() on the destination.
+template <int OFF>
+__device__ __forceinline__ u32x4_t lds_read_b128(unsigned addr) {
+  u32x4_t v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+template <int OFF, int HI>
+__device__ __forceinline__ u32x4_t lds_read_tr16(unsigned addr) {
+  u32x2_t lo, hi;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(OFF));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(OFF + HI));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+}
+// Waits until at most N LDS operations of this wave are outstanding (they complete in order).
+template <int N>
+__device__ __forceinline__ void lds_wait() {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
+}
+// Pins the fragments behind the preceding lds_wait: no use of them can be scheduled above it.
+template <int NF>
+__device__ __forceinline__ void lds_tie(u32x4_t (&f)[NF]) {
+#pragma unroll
+  for (int i = 0; i < NF; i++) asm volatile("" : "+v"(f[i]));
+}
+
+// One wave instruction: lane i copies 16 bytes from base + voff(lane) + soff to lds + 16*i (lds is wave-uniform).
+// (Kept in a device function: the builtin is not callable where the host pass parses a kernel body.)
+__device__ __forceinline__ void dma_load16(__amdgpu_buffer_rsrc_t rsrc, char *lds, unsigned voff, unsigned soff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lptr_t)lds, 16, voff, soff, 0, 0);
+}
 
 template <int ROWS, bool KC, int NWAVES>
 struct DmaOp {
-  static constexpr int NINST = ROWS * 4 / 64 / NWAVES;   // wave instructions per wave per K-tile
+  static_assert(ROWS % (16 * NWAVES) == 0, "each wave issues a whole number of 1 KB loads per K-tile");
+  static constexpr int NINST = ROWS / 16 / NWAVES;       // wave instructions per wave per K-tile
   static constexpr int bytes = ROWS * DK * 2;
-  // element offset (from the operand base, K-tile 0) of the chunk that lane `lane` of this wave's j-th
+  static constexpr int CPR = ROWS / 8;                   // 16-byte chunks per k-row (row-contiguous operand)
+  static constexpr int LDS_OPS_PER_FRAG = KC ? 1 : 2;
+  // byte offset (from the operand base, K-tile 0) of the chunk that lane `lane` of this wave's j-th
   // instruction must fetch
-  static __device__ __forceinline__ size_t chunk_offset(int j, int wave, int lane, int ld, int row0, int row_lim) {
+  static __device__ __forceinline__ unsigned chunk_offset(int j, int wave, int lane, int ld, int row0, int row_lim) {
     const int p = (wave * NINST + j) * 64 + lane;
     if (KC) {
       const int r = p >> 2, c = (p & 3) ^ ((r >> 2) & 3);
       const int row = min(row0 + r, row_lim - 1);
-      return (size_t)row * ld + c * 8;
+      return ((unsigned)row * (unsigned)ld + c * 8) * 2u;
     } else {
-      constexpr int CPR = ROWS / 8;
       const int k = p / CPR, c = (p % CPR) ^ (4 * (k & 3));
       int col = row0 + c * 8;
       col = col < row_lim ? col : 0;
-      return (size_t)k * ld + col;
+      return ((unsigned)k * (unsigned)ld + col) * 2u;
     }
   }
-  static __device__ __forceinline__ void issue(const bf16_t *base, const size_t (&off)[NINST], size_t kstep, char *lds_tile, int wave) {
-#pragma unroll
-    for (int j = 0; j < NINST; j++)
-      __builtin_amdgcn_global_load_lds((gptr_t)(base + off[j] + kstep), (lptr_t)(lds_tile + (wave * NINST + j) * 1024), 16, 0, 0);
-  }
-  // fragment for rows row..row+31, k = kk..kk+15 (kk = 0 or 16)
-  static __device__ __forceinline__ bf16x8_t frag(const char *lds_tile, int row, int kk, int lane) {
+  // LDS byte offsets (within a tile) from which the fragments of rows row .. row + 32*NF - 1 are read:
+  // k-contiguous: one address per 16-deep half (fragment i adds 32 rows = 2048 bytes as an immediate);
+  // row-contiguous: one address per fragment (the half adds 16 k-rows as an immediate).
+  template <int NF>
+  static __device__ __forceinline__ void frag_bases(unsigned (&ad)[KC ? 2 : NF], int row, int lane) {
     if (KC) {
       const int r = row + (lane & 31);
-      const int c = (kk >> 3) + (lane >> 5);
-      return *reinterpret_cast<const bf16x8_t *>(lds_tile + (r * 4 + (c ^ ((r >> 2) & 3))) * 16);
+#pragma unroll
+      for (int h = 0; h < 2; h++) {
+        const int c = 2 * h + (lane >> 5);
+        ad[h] = (r * 4 + (c ^ ((r >> 2) & 3))) * 16;
+      }
     } else {
-      constexpr int CPR = ROWS / 8;
-      const int k = kk + 8 * (lane >> 5) + ((lane & 15) >> 2);
-      const int col = row + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-      const char *p = lds_tile + (k * CPR + ((col >> 3) ^ (4 * (k & 3)))) * 16 + (col & 7) * 2;
-      // Issued as inline assembly: through the builtin the compiler would order every transposing read
-      // behind ALL outstanding direct-to-LDS loads (vmcnt(0)), which would serialise the pipeline.
-      // The result is only valid after frag_wait().
-      const unsigned addr = (unsigned)(size_t)(const __attribute__((address_space(3))) char *)p;
-      u32x2_t lo, hi;
-      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
-      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(4 * CPR * 16));
-      u32x4_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
-      return __builtin_bit_cast(bf16x8_t, v);
+      const int k = 8 * (lane >> 5) + ((lane & 15) >> 2);
+#pragma unroll
+      for (int i = 0; i < NF; i++) {
+        const int col = row + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        ad[i] = (k * CPR + ((col >> 3) ^ (4 * (k & 3)))) * 16 + (col & 7) * 2;
+      }
+    }
+  }
+  // issues the reads of the NF fragments of half H (k = 16*H .. 16*H+15) of the tile at LDS address `tile`
+  template <int H, int NF, int... I>
+  static __device__ __forceinline__ void frag_issue(u32x4_t (&f)[NF], const unsigned (&ad)[KC ? 2 : NF], unsigned tile,
+                                                    std::integer_sequence<int, I...>) {
+    if constexpr (KC) {
+      const unsigned a = ad[H] + tile;
+      ((f[I] = lds_read_b128<I * 2048>(a)), ...);
+    } else {
+      ((f[I] = lds_read_tr16<H * 16 * CPR * 16, 4 * CPR * 16>(ad[I] + tile)), ...);
     }
   }
 };
 
-// Makes the LDS reads issued by DmaOp::frag's inline assembly visible: waits for all outstanding LDS
-// operations of the wave and ties the fragments to the wait so that no MFMA can be scheduled above it.
-template <int N>
-__device__ __forceinline__ void frag_wait(bf16x8_t (&f)[N]) {
-  static_assert(N == 2 || N == 4, "fragment count");
-  if (N == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]));
-  else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[N - 2]), "+v"(f[N - 1]));
-}
-
-template <bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
-                                                            int ldb, int M, int N, int K, int tiles_m, int tiles_n, Epi ep) {
-  constexpr int BM = 256, BN = 256, WAVES_M = 2, WAVES_N = 4, NWAVES = 8;
+template <int BM, int BN, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t *__restrict__ A, int lda, int a_bytes,
+                                                            const bf16_t *__restrict__ B, int ldb, int b_bytes, int M, int N, int K,
+                                                            int tiles_m, int tiles_n, Epi ep) {
+  constexpr int WAVES_M = 2, WAVES_N = 4, NWAVES = 8;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, MI = WM / 32, NI = WN / 32;
   using OA = DmaOp<BM, A_KC, NWAVES>;
   using OB = DmaOp<BN, B_KC, NWAVES>;
   constexpr int STAGE_BYTES = OA::bytes + OB::bytes;
   constexpr int LOADS_PER_TILE = OA::NINST + OB::NINST;
+  constexpr int READS_PER_STEP = MI * OA::LDS_OPS_PER_FRAG + NI * OB::LDS_OPS_PER_FRAG;
+  static_assert(READS_PER_STEP <= 15, "lgkmcnt is a 4-bit counter");
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -366,13 +410,20 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t *__rest
   map_tile(tiles_m, tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
 
-  size_t offa[OA::NINST], offb[OB::NINST];
+  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(A), 0, a_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(B), 0, b_bytes, 0x00020000);
+  unsigned offa[OA::NINST], offb[OB::NINST];
 #pragma unroll
   for (int j = 0; j < OA::NINST; j++) offa[j] = OA::chunk_offset(j, wave, lane, lda, m0, M);
 #pragma unroll
   for (int j = 0; j < OB::NINST; j++) offb[j] = OB::chunk_offset(j, wave, lane, ldb, n0, N);
-  const size_t stepa = A_KC ? (size_t)DK : (size_t)DK * lda;
-  const size_t stepb = B_KC ? (size_t)DK : (size_t)DK * ldb;
+  const unsigned stepa = (A_KC ? (unsigned)DK : (unsigned)DK * lda) * 2u;
+  const unsigned stepb = (B_KC ? (unsigned)DK : (unsigned)DK * ldb) * 2u;
+
+  unsigned ada[A_KC ? 2 : MI], adb[B_KC ? 2 : NI];
+  OA::template frag_bases<MI>(ada, wm * WM, lane);
+  OB::template frag_bases<NI>(adb, wn * WN, lane);
+  const unsigned lds0 = (unsigned)(size_t)(const __attribute__((address_space(3))) char *)smem_raw;
 
   f32x16_t acc[MI][NI];
 #pragma unroll
@@ -383,100 +434,105 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t *__rest
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
   const int KT = K / DK;
-  // prologue: K-tiles 0 .. DSTAGES-2 (clamped to the last tile so that the in-flight count is uniform)
+  // The direct-to-LDS loads form one stream, tile after tile, each tile as A's instructions then B's.
+  // Issuing a load holds the wave until the address unit takes it, so the loads are placed one at a time
+  // between MFMAs (whose execution covers the hold) instead of in a burst behind the barrier, where the
+  // eight waves would queue on the address FIFO with the matrix pipes idle.  Per K-tile kt the first
+  // LF loads of tile kt+4 go into the MFMA block that follows the barrier (stage kt is free from there on)
+  // and the remaining LS loads into the MFMA block before the next barrier.
+  constexpr int LF = (LOADS_PER_TILE + 1) / 2, LS = LOADS_PER_TILE - LF;
+#define STP_ISSUE(q, ktile, stage)                                                                               \
+  do {                                                                                                           \
+    const int kt_ = min((ktile), KT - 1);                                                                        \
+    char *st_ = smem_raw + (stage) * STAGE_BYTES;                                                                \
+    if ((q) < OA::NINST)                                                                                         \
+      dma_load16(ra, st_ + (wave * OA::NINST + (q)) * 1024, offa[(q) < OA::NINST ? (q) : 0], kt_ * stepa);       \
+    else                                                                                                         \
+      dma_load16(rb, st_ + OA::bytes + (wave * OB::NINST + (q) - OA::NINST) * 1024,                              \
+                 offb[(q) >= OA::NINST ? (q) - OA::NINST : 0], kt_ * stepb);                                     \
+  } while (0)
+  // prologue: tiles 0 .. DSTAGES-2 and the first LF loads of tile DSTAGES-1
 #pragma unroll
-  for (int t = 0; t < DSTAGES - 1; t++) {
-    const int kt = min(t, KT - 1);
-    OA::issue(A, offa, kt * stepa, smem_raw + t * STAGE_BYTES, wave);
-    OB::issue(B, offb, kt * stepb, smem_raw + t * STAGE_BYTES + OA::bytes, wave);
-  }
+  for (int t = 0; t < DSTAGES; t++)
+#pragma unroll
+    for (int q = 0; q < (t < DSTAGES - 1 ? LOADS_PER_TILE : LF); q++) STP_ISSUE(q, t, t);
 
-  // ---- ping-pong schedule.  The two waves that share a SIMD (wave w and w + 4) run half a step apart:
-  // in every phase one of them issues the LDS fragment reads of its next 16-deep step while the other
-  // executes the 8 MFMAs of its current step, so the matrix pipe of every SIMD is fed in every phase
-  // and LDS latency never sits between MFMAs.  Phases are separated by s_barrier (phase lock only);
-  // data safety comes from the vmcnt wait + barrier at the head of each K-tile.
-  //   phase 4kt  : [tile kt landed] A reads (kt,0)      B runs (kt-1,1)
-  //   phase 4kt+1:                  A runs  (kt,0)      B reads (kt,0)
-  //   phase 4kt+2:                  A reads (kt,1)      B runs  (kt,0)
-  //   phase 4kt+3:                  A runs  (kt,1)      B reads (kt,1)
-  const bool grp_b = wave >= NWAVES / 2;
-  bf16x8_t fa[MI], fb[NI];
-#define STP_PHASE_BARRIER()                        \
-  do {                                             \
-    __builtin_amdgcn_sched_barrier(0);             \
-    asm volatile("s_barrier" ::: "memory");        \
-    __builtin_amdgcn_sched_barrier(0);             \
+  u32x4_t fa0[MI], fb0[NI], fa1[MI], fb1[NI];
+  using SeqM = std::make_integer_sequence<int, MI>;
+  using SeqN = std::make_integer_sequence<int, NI>;
+#define STP_READ(H, FA, FB, stage)                                                   \
+  do {                                                                               \
+    const unsigned t_ = lds0 + (unsigned)(stage) * STAGE_BYTES;                      \
+    OA::template frag_issue<H>(FA, ada, t_, SeqM{});                                 \
+    OB::template frag_issue<H>(FB, adb, t_ + OA::bytes, SeqN{});                     \
+    __builtin_amdgcn_sched_barrier(0);                                               \
   } while (0)
-#define STP_READ_FRAGS(a_s, b_s, kk)                                                          \
-  do {                                                                                        \
-    _Pragma("unroll") for (int i = 0; i < MI; i++) fa[i] = OA::frag(a_s, wm * WM + i * 32, kk, lane); \
-    _Pragma("unroll") for (int j = 0; j < NI; j++) fb[j] = OB::frag(b_s, wn * WN + j * 32, kk, lane); \
+  // MI*NI MFMAs with loads Q0 .. Q0+NQ-1 of tile `ktile` spread evenly between them
+#define STP_MFMAS(FA, FB, Q0, NQ, ktile, stage)                                      \
+  do {                                                                               \
+    lds_tie(FA);                                                                     \
+    lds_tie(FB);                                                                     \
+    _Pragma("unroll") for (int i = 0; i < MI; i++)                                   \
+      _Pragma("unroll") for (int j = 0; j < NI; j++) {                               \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, FA[i]), __builtin_bit_cast(bf16x8_t, FB[j]), \
+                                                            acc[i][j], 0, 0, 0);     \
+        _Pragma("unroll") for (int r = 0; r < (NQ); r++)                             \
+          if (i * NI + j == max(0, ((r + 1) * MI * NI) / ((NQ) + 1) - 1)) {          \
+            __builtin_amdgcn_sched_barrier(0);                                       \
+            STP_ISSUE((Q0) + r, ktile, stage);                                       \
+            __builtin_amdgcn_sched_barrier(0);                                       \
+          }                                                                          \
+      }                                                                              \
+    __builtin_amdgcn_sched_barrier(0);                                               \
   } while (0)
-#define STP_RUN_MFMAS()                                                                       \
-  do {                                                                                        \
-    if (!A_KC) frag_wait(fa);                                                                 \
-    if (!B_KC) frag_wait(fb);                                                                 \
-    _Pragma("unroll") for (int i = 0; i < MI; i++)                                            \
-      _Pragma("unroll") for (int j = 0; j < NI; j++)                                          \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0); \
-  } while (0)
+
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((DSTAGES - 2) * LOADS_PER_TILE + LF) : "memory");
+  STP_READ(0, fa0, fb0, 0);
 
   for (int kt = 0; kt < KT; kt++) {
-    const char *a_s = smem_raw + (kt % DSTAGES) * STAGE_BYTES;
-    const char *b_s = a_s + OA::bytes;
-    // head of K-tile kt: this wave's loads of tile kt have landed once at most (DSTAGES-2) tiles' worth
-    // remain in flight; its own LDS reads of the stage about to be refilled have returned (lgkmcnt)
-    __builtin_amdgcn_sched_barrier(0);
+    const int st = kt % DSTAGES;
+    STP_READ(1, fa1, fb1, st);
+    lds_wait<READS_PER_STEP>();          // the reads of half 0 (issued one step ago) have returned
+    STP_MFMAS(fa0, fb0, LF, LS, kt + DSTAGES - 1, (kt + DSTAGES - 1) % DSTAGES);
+    // tile kt+1 has landed once at most (DSTAGES-2) tiles' worth of this wave's loads remain in flight;
+    // lgkmcnt(0): this wave's reads of stage st are complete, so after the barrier the stage is free
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((DSTAGES - 2) * LOADS_PER_TILE) : "memory");
     __builtin_amdgcn_sched_barrier(0);
-    {
-      const int ktl = min(kt + DSTAGES - 1, KT - 1);
-      char *st = smem_raw + ((kt + DSTAGES - 1) % DSTAGES) * STAGE_BYTES;
-      OA::issue(A, offa, ktl * stepa, st, wave);
-      OB::issue(B, offb, ktl * stepb, st + OA::bytes, wave);
-    }
-    if (!grp_b) {
-      STP_READ_FRAGS(a_s, b_s, 0);
-      STP_PHASE_BARRIER();
-      STP_RUN_MFMAS();
-      STP_PHASE_BARRIER();
-      STP_READ_FRAGS(a_s, b_s, 16);
-      STP_PHASE_BARRIER();
-      STP_RUN_MFMAS();
-    } else {
-      if (kt > 0) STP_RUN_MFMAS();
-      STP_PHASE_BARRIER();
-      STP_READ_FRAGS(a_s, b_s, 0);
-      STP_PHASE_BARRIER();
-      STP_RUN_MFMAS();
-      STP_PHASE_BARRIER();
-      STP_READ_FRAGS(a_s, b_s, 16);
-    }
+    STP_READ(0, fa0, fb0, (kt + 1) % DSTAGES);   // past the last tile this reads a stale stage; never used
+    lds_wait<READS_PER_STEP>();
+    STP_MFMAS(fa1, fb1, 0, LF, kt + DSTAGES, st);
   }
-  if (grp_b) STP_RUN_MFMAS();
-#undef STP_PHASE_BARRIER
-#undef STP_READ_FRAGS
-#undef STP_RUN_MFMAS
-  // drain the (redundant) tail loads before the stages are reused as epilogue staging
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+#undef STP_READ
+#undef STP_MFMAS
+#undef STP_ISSUE
+  // drain the (redundant) tail loads and reads before the stages are reused as epilogue staging
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  lds_tie(fa0);
+  lds_tie(fb0);
   store_tile<MI, NI, WN, EPI>(acc, reinterpret_cast<float *>(smem_raw) + wave * (32 * (WN + 8)), m0 + wm * WM, n0 + wn * WN, M, N,
                               ep, lane);
 }
 
-template <bool A_KC, bool B_KC, int EPI>
+// extent in bytes of a K x rows operand as the kernel addresses it; 0 if it does not fit a 31-bit offset
+inline long operand_bytes(bool kc, long rows, long K, long ld) {
+  long el = kc ? (rows - 1) * ld + K : (K - 1) * ld + rows;
+  return el * 2 < 0x7fffffffL ? el * 2 : 0;
+}
+
+template <int BM, int BN, bool A_KC, bool B_KC, int EPI>
 int launch_dma(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t s) {
-  constexpr size_t smem = (size_t)DSTAGES * (256 * DK * 2 + 256 * DK * 2);
-  static_assert(smem <= 160 * 1024 && smem >= (size_t)8 * 32 * (64 + 8) * sizeof(float), "LDS budget");
-  auto kern = gemm_bf16_dma_kernel<A_KC, B_KC, EPI>;
+  constexpr size_t smem = (size_t)DSTAGES * (BM + BN) * DK * 2;
+  static_assert(smem <= 160 * 1024 && smem >= (size_t)8 * 32 * (BN / 4 + 8) * sizeof(float), "LDS budget");
+  auto kern = gemm_bf16_dma_kernel<BM, BN, A_KC, B_KC, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
     STP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
-  int tiles_m = (a->M + 255) / 256, tiles_n = (a->N + 255) / 256;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(512), smem, s, (const bf16_t *)a->A, a->lda, (const bf16_t *)a->B,
-                     a->ldb, a->M, a->N, a->K, tiles_m, tiles_n, ep);
+  const int tiles_m = (a->M + BM - 1) / BM, tiles_n = (a->N + BN - 1) / BN;
+  const long ab = operand_bytes(A_KC, a->M, a->K, a->lda), bb = operand_bytes(B_KC, a->N, a->K, a->ldb);
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(512), smem, s, (const bf16_t *)a->A, a->lda, (int)ab, (const bf16_t *)a->B,
+                     a->ldb, (int)bb, a->M, a->N, a->K, tiles_m, tiles_n, ep);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }
@@ -503,7 +559,8 @@ int launch_cfg(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t 
 template <bool A_KC, bool B_KC, int EPI>
 int launch_tile(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t s) {
   long t256 = (long)((a->M + 255) / 256) * ((a->N + 255) / 256);
-  if (t256 >= 96 && a->K % DK == 0) return launch_dma<A_KC, B_KC, EPI>(ctx, a, ep, s);
+  const bool dma_ok = a->K % DK == 0 && operand_bytes(A_KC, a->M, a->K, a->lda) > 0 && operand_bytes(B_KC, a->N, a->K, a->ldb) > 0;
+  if (t256 >= 96 && dma_ok) return launch_dma<256, 256, A_KC, B_KC, EPI>(ctx, a, ep, s);
   return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI>(ctx, a, ep, s);
 }
 
