@@ -80,7 +80,8 @@ class GemmArgs(C.Structure):
                 ("C", C.c_void_p), ("ldc", C.c_int32), ("c_f32_accum", C.c_int32),
                 ("bias", C.c_void_p), ("bias_scale", C.c_float),
                 ("resid", C.c_void_p), ("ldr", C.c_int32), ("resid_scale", C.c_float),
-                ("epilogue", C.c_int32), ("C2", C.c_void_p), ("aux", C.c_void_p), ("ld2", C.c_int32)]
+                ("epilogue", C.c_int32), ("C2", C.c_void_p), ("aux", C.c_void_p), ("ld2", C.c_int32),
+                ("tile_m", C.c_int32), ("tile_n", C.c_int32)]
 
 
 BOUNDARY_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p)

@@ -51,9 +51,29 @@ def test_gemm_layouts(ctx, dtype, a_trans, b_trans, M, N, K):
     assert rel_err(to_host(Cd), ref) < (4e-3 if dtype == "bf16" else 2e-6)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_gemm_epilogues(ctx, dtype):
-    M, N, K = 392, 456, 136
+@pytest.mark.parametrize("tile", [(256, 256), (256, 128), (128, 256), (128, 128)])
+@pytest.mark.parametrize("a_trans,b_trans", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("M,N,K", [(520, 776, 160), (264, 136, 32), (1288, 520, 352)])
+def test_gemm_forced_tiles(ctx, tile, a_trans, b_trans, M, N, K):
+    """Every workgroup tile of the direct-to-LDS kernel, on shapes with ragged edge tiles, fewer K-tiles than
+    pipeline stages (K = 32) and more (K = 352)."""
+    rng = np.random.default_rng(M + N + K)
+    A = q(rng.standard_normal((M, K), dtype=np.float32), "bf16")
+    B = q(rng.standard_normal((K, N), dtype=np.float32) * 0.05, "bf16")
+    Ad = to_dev(np.ascontiguousarray(A.T) if a_trans else A, "bf16")
+    Bd = to_dev(np.ascontiguousarray(B.T) if b_trans else B, "bf16")
+    Cd = torch.zeros((M, N), dtype=Ad.dtype, device="cuda")
+    ctx.gemm(stp.GemmArgs(dtype=stp.BF16, M=M, N=N, K=K, A=Ad.data_ptr(), lda=M if a_trans else K, a_trans=a_trans,
+                          B=Bd.data_ptr(), ldb=K if b_trans else N, b_trans=b_trans, C=Cd.data_ptr(), ldc=N,
+                          bias_scale=1.0, resid_scale=1.0, tile_m=tile[0], tile_n=tile[1]))
+    torch.cuda.synchronize()
+    assert rel_err(to_host(Cd), A.astype(np.float64) @ B.astype(np.float64)) < 4e-3
+
+
+@pytest.mark.parametrize("dtype,tile", [("bf16", (0, 0)), ("f32", (0, 0)), ("bf16", (256, 256)), ("bf16", (128, 128)),
+                                        ("bf16", (256, 128)), ("bf16", (128, 256))])
+def test_gemm_epilogues(ctx, dtype, tile):
+    M, N, K = (392, 456, 136) if tile == (0, 0) else (392, 456, 160)
     rng = np.random.default_rng(5)
     tol = 6e-3 if dtype == "bf16" else 3e-6
     A = q(rng.standard_normal((M, K), dtype=np.float32), dtype)
@@ -62,7 +82,8 @@ def test_gemm_epilogues(ctx, dtype):
     R = q(rng.standard_normal((M, N), dtype=np.float32), dtype)
     Ad, Bd, bd, Rd = (to_dev(x, dtype) for x in (A, B, bias, R))
     code = stp.BF16 if dtype == "bf16" else stp.F32
-    base = dict(dtype=code, M=M, N=N, K=K, A=Ad.data_ptr(), lda=K, B=Bd.data_ptr(), ldb=N, ldc=N)
+    base = dict(dtype=code, M=M, N=N, K=K, A=Ad.data_ptr(), lda=K, B=Bd.data_ptr(), ldb=N, ldc=N, tile_m=tile[0],
+                tile_n=tile[1])
     AB = A.astype(np.float64) @ B.astype(np.float64)
     # bias*scale + resid*scale
     Cd = torch.zeros((M, N), dtype=Ad.dtype, device="cuda")
@@ -93,7 +114,9 @@ def test_gemm_rejects_bad_arguments(ctx):
     x = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
     ok = dict(dtype=stp.BF16, M=64, N=64, K=64, A=x.data_ptr(), lda=64, B=x.data_ptr(), ldb=64, C=x.data_ptr(), ldc=64)
     for bad, status in [(dict(M=63), 2), (dict(A=None), 1), (dict(A=x.data_ptr() + 2), 3), (dict(lda=32), 2),
-                        (dict(dtype=7), 1), (dict(epilogue=1), 1)]:
+                        (dict(dtype=7), 1), (dict(epilogue=1), 1), (dict(tile_m=64, tile_n=128), 1),
+                        (dict(tile_m=128, tile_n=0), 1), (dict(K=40, lda=64, tile_m=128, tile_n=128), 1),
+                        (dict(dtype=stp.F32, tile_m=128, tile_n=128), 1)]:
         with pytest.raises(stp.StpError) as e:
             ctx.gemm(stp.GemmArgs(**(ok | bad)))
         assert e.value.status == status
