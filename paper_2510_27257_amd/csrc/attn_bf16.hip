@@ -2,12 +2,12 @@
 // the attention core of one TP rank, no communication).
 //
 // Work decomposition.  A workgroup owns 128 query rows of one (sequence, head) and ONE CHUNK of up
-// to 1024 keys; chunks of the same query block are merged afterwards by a small combine kernel
+// to CH2 * 128 keys; chunks of the same query block are merged afterwards by a small combine kernel
 // (fixed order, deterministic).  Cutting the key range into chunks turns the causal triangle into
-// ~3 pieces of similar size per compute unit instead of 192 workgroups whose length varies 1..96.
+// pieces of similar size instead of workgroups whose length varies 1..seq/128.
 // Inside a workgroup 8 waves run as 4 query sub-tiles (32 rows) x 2 key halves: per 128-key step
-// waves 0-3 take keys 0..63 and waves 4-7 keys 64..127, so every SIMD holds two waves and one
-// wave's softmax arithmetic overlaps the other's MFMAs.  The two halves are merged through LDS.
+// waves 0-3 (group A) take keys 0..63 and waves 4-7 (group B) keys 64..127; a SIMD holds one wave of
+// each group.  The two halves are merged through LDS at the end.
 //
 // Per wave the kernel works on the TRANSPOSED score tile, S^T = K Q^T: with the 32x32x16 MFMA the
 // accumulator of lane l then holds column q = l % 32, i.e. every softmax statistic (running max,
@@ -15,54 +15,40 @@
 // cross-half shuffle.  The probabilities are already in the register layout the next MFMA wants for
 // its B operand (O^T += V^T P^T), so P never touches LDS.  V^T fragments come from the V tile as it
 // lies in memory ([kv][d]) through the transposing LDS read.
-//   K tile  : LDS [128][D + 8]   16-byte fragment reads
-//   V tile  : LDS [128][D + 32]  ds_read_b64_tr_b16 fragment reads
-// Both are double-buffered through registers (next step's loads in flight during the MFMAs of the
-// current one).
+//
+// Schedule.  A step of a wave is a matrix phase M(k) = { S(k+1) = K(k+1) Q^T ; O += V(k)^T P(k) } and
+// a vector phase V(k) = { P(k) = online softmax of S(k) }, of about equal length.  In iteration k group
+// A runs M(k) then V(k+1) and group B V(k) then M(k), so on every SIMD one wave feeds the matrix pipe
+// while the other does the exponentials; there is one s_barrier per iteration, none between the phases.
+// K and V tiles (128 keys x D) go global -> LDS directly (buffer_load ... lds), K and V each in a ring
+// of two tiles.  Tile K(k+2) replaces K(k) and V(k+1) replaces V(k-1); both are issued at the top of
+// iteration k, when every wave is done with the tiles they overwrite, and waited for (vmcnt(0) + the
+// barrier) at the top of iteration k+1, where they are first used.  A direct-to-LDS wave instruction fills
+// 1 KB contiguously, so rows cannot be padded; bank conflicts are avoided by an XOR permutation of
+// the 16-byte chunks of a row, applied on the global side and undone in the fragment addresses:
+//   K tile [key][D]: chunk c of row r in slot c ^ ((r / RPB) & (CPR-1))        (16-byte fragment reads)
+//   V tile [key][D]: chunk c of row r in slot c ^ (4 * ((r & 3) / RPB))        (ds_read_b64_tr_b16 reads)
+// with CPR = D/8 chunks per row and RPB = 128/D rows per 256 bytes.  Fragment reads are inline assembly
+// with explicit waits, software-pipelined one group of MFMAs ahead.
 #include "common.h"
+#include "lds_dma.h"
 
 namespace {
 
 constexpr int QB = 128;    // query rows per workgroup
 constexpr int KSTEP = 128; // keys per step (64 per wave half)
-constexpr int CH2 = 8;     // steps per chunk (1024 keys)
+constexpr int CH2 = 16;     // steps per chunk (2048 keys)
 constexpr float LN2 = 0.69314718055994531f;
 
-typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
-
 template <int D> struct AttnGeom {
-  static constexpr int kp = D + 8;    // K tile pitch (elements)
-  static constexpr int vp = D + 32;   // V tile pitch
-  static constexpr int k_elems = KSTEP * kp;
-  static constexpr int v_elems = KSTEP * vp;
-  static constexpr int nld = KSTEP * D / 8 / 512;  // 16-byte chunks per thread per tile
+  static constexpr int RB = D * 2;               // bytes per tile row
+  static constexpr int CPR = D / 8;              // 16-byte chunks per row
+  static constexpr int RPB = 256 / RB;           // rows per 256 bytes (one pass over the 64 banks)
+  static constexpr int RPI = 64 / CPR;           // tile rows covered by one direct-to-LDS wave instruction
+  static constexpr int NLD = KSTEP / RPI / 8;    // such instructions per wave per tile
+  static constexpr int TILE = KSTEP * RB;        // bytes of a K or V tile
   static constexpr int piece_floats = QB * D + 2 * QB;   // partial O, then m, then l
 };
-
-// 128 x D tile, 512 threads: registers <- global (rows clamped to seq-1; keys past the end are masked later)
-template <int D, int NLD>
-__device__ __forceinline__ void tile_load(uint4 (&r)[NLD], const bf16_t *__restrict__ base, size_t ld, int row0, int seq, int tid) {
-  static_assert(NLD == KSTEP * D / 8 / 512, "register count");
-#pragma unroll
-  for (int i = 0; i < NLD; i++) {
-    int q = tid + 512 * i;
-    int rr = q / (D / 8), c = (q % (D / 8)) * 8;
-    int row = min(row0 + rr, seq - 1);
-    const uint4 v = *reinterpret_cast<const uint4 *>(base + (size_t)row * ld + c);
-    r[i].x = v.x; r[i].y = v.y; r[i].z = v.z; r[i].w = v.w;
-  }
-}
-template <int D, int P, int NLD>
-__device__ __forceinline__ void tile_store(const uint4 (&r)[NLD], bf16_t *tile, int tid) {
-#pragma unroll
-  for (int i = 0; i < NLD; i++) {
-    int q = tid + 512 * i;
-    int rr = q / (D / 8), c = (q % (D / 8)) * 8;
-    uint4 v;   // component-wise copy: a whole-struct copy keeps the register array in scratch memory
-    v.x = r[i].x; v.y = r[i].y; v.z = r[i].z; v.w = r[i].w;
-    *reinterpret_cast<uint4 *>(tile + rr * P + c) = v;
-  }
-}
 
 // number of 128-key steps a query block needs
 __host__ __device__ inline int attn_steps(int qb, int seq, int causal) {
@@ -70,13 +56,48 @@ __host__ __device__ inline int attn_steps(int qb, int seq, int causal) {
   return (kv_end + KSTEP - 1) / KSTEP;
 }
 
+// ---- fragment reads (results valid after lds_wait + lds_tie) ----
+// K fragments of sub-block JB (32 keys), d-steps 4*SG .. 4*SG+3: A operand, lane supplies key row lr, d = 16 s + 8 lg ..
+template <int D, int JB, int SG>
+__device__ __forceinline__ void read_k(u32x4_t (&buf)[4], const unsigned (&kaddr)[D / 16], unsigned tile) {
+  constexpr int OFF = JB * 32 * AttnGeom<D>::RB;
+  buf[0] = lds_read_b128<OFF>(kaddr[4 * SG + 0] + tile);
+  buf[1] = lds_read_b128<OFF>(kaddr[4 * SG + 1] + tile);
+  buf[2] = lds_read_b128<OFF>(kaddr[4 * SG + 2] + tile);
+  buf[3] = lds_read_b128<OFF>(kaddr[4 * SG + 3] + tile);
+}
+// V^T fragments of keys 32 JB + 16 T .. +15 for the D/32 blocks of 32 output columns
+template <int D, int JB, int T>
+__device__ __forceinline__ void read_v(u32x4_t (&buf)[4], const unsigned (&vaddr)[D / 32], unsigned tile) {
+  constexpr int RB = AttnGeom<D>::RB, OFF = (32 * JB + 16 * T) * RB;
+  buf[0] = lds_read_tr16<OFF, 8 * RB>(vaddr[0] + tile);
+  buf[1] = lds_read_tr16<OFF, 8 * RB>(vaddr[1] + tile);
+  if constexpr (D == 128) {
+    buf[2] = lds_read_tr16<OFF, 8 * RB>(vaddr[2] + tile);
+    buf[3] = lds_read_tr16<OFF, 8 * RB>(vaddr[3] + tile);
+  }
+}
+template <int D, int SG>
+__device__ __forceinline__ void mfma_qk(f32x16_t &sc, const u32x4_t (&buf)[4], const bf16x8_t (&qf)[D / 16]) {
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+    sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, buf[i]), qf[4 * SG + i], sc, 0, 0, 0);
+}
+template <int D>
+__device__ __forceinline__ void mfma_pv(f32x16_t (&o)[D / 32], const u32x4_t (&buf)[4], bf16x8_t pf) {
+#pragma unroll
+  for (int db = 0; db < D / 32; db++)
+    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, buf[db]), pf, o[db], 0, 0, 0);
+}
+
 template <int D>
 __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__restrict__ qkv, float *__restrict__ part, int seq,
                                                             int n, int causal, int max_chunks, float scale_log2) {
   using G = AttnGeom<D>;
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  constexpr int STAGE = G::k_elems + G::v_elems;
-  bf16_t *const sbase = reinterpret_cast<bf16_t *>(smem_raw);
+  static_assert(D == 64 || D == 128, "head dimension");
+  constexpr int RB = G::RB, CPR = G::CPR, RPB = G::RPB, RPI = G::RPI, NLD = G::NLD, TILE = G::TILE;
+  constexpr int KREADS = 4, VREADS = 2 * (D / 32);   // LDS operations of one fragment group
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];   // K ring [2][TILE], V ring [2][TILE]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lg = lane >> 5;
@@ -88,10 +109,11 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
   const int nsteps = attn_steps(qb, seq, causal);
   const int s_begin = chunk * CH2, s_end = min(nsteps, s_begin + CH2);
   if (s_begin >= nsteps) return;
+  const int ns = s_end - s_begin;
 
   const int a = n * D;
-  const size_t ld = 3 * (size_t)a;
-  const bf16_t *base = qkv + (size_t)b * seq * ld + head * D;  // Q of this head; K at +a, V at +2a
+  const int ld = 3 * a;
+  const bf16_t *bbase = qkv + (size_t)b * seq * ld;           // this sequence's [seq][3a] block
   const int q_wave0 = qb * QB + qsub * 32;
   const int qg = q_wave0 + lr;                  // this lane's query row
   const int q_ld = min(qg, seq - 1);            // clamp so that tail lanes read valid memory
@@ -100,7 +122,44 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
   bf16x8_t qf[D / 16];
 #pragma unroll
   for (int s = 0; s < D / 16; s++)
-    qf[s] = *reinterpret_cast<const bf16x8_t *>(base + (size_t)q_ld * ld + 16 * s + 8 * lg);
+    qf[s] = *reinterpret_cast<const bf16x8_t *>(bbase + (size_t)q_ld * ld + head * D + 16 * s + 8 * lg);
+
+  // ---- direct-to-LDS loads of this wave: instruction I = wave * NLD + j covers tile rows I*RPI .. +RPI-1
+  const __amdgpu_buffer_rsrc_t rs =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(bbase), 0, (int)min((size_t)seq * ld * 2, (size_t)0x7fffffff), 0x00020000);
+  int ld_row[NLD];
+  unsigned ld_kcol[NLD], ld_vcol[NLD];          // byte offset within a [3a] row of the chunk this lane fetches
+#pragma unroll
+  for (int j = 0; j < NLD; j++) {
+    const int row = (wave * NLD + j) * RPI + lane / CPR, slot = lane % CPR;
+    ld_row[j] = row;
+    ld_kcol[j] = (unsigned)(head * D + a + (slot ^ ((row / RPB) & (CPR - 1))) * 8) * 2u;
+    ld_vcol[j] = (unsigned)(head * D + 2 * a + (slot ^ (4 * ((row & 3) / RPB))) * 8) * 2u;
+  }
+  auto issue_tile = [&](int k, bool is_v) {   // tile of local step k into ring slot k & 1
+    char *dst = smem_raw + (is_v ? 2 * TILE : 0) + (k & 1) * TILE + wave * NLD * 1024;
+#pragma unroll
+    for (int j = 0; j < NLD; j++) {
+      const int grow = min((s_begin + k) * KSTEP + ld_row[j], seq - 1);
+      dma_load16(rs, dst + j * 1024, (unsigned)grow * (unsigned)(ld * 2) + (is_v ? ld_vcol[j] : ld_kcol[j]), 0);
+    }
+  };
+
+  // ---- fragment addresses within a tile (this wave's 64-key half)
+  const unsigned lds0 = (unsigned)(size_t)(const __attribute__((address_space(3))) char *)smem_raw;
+  unsigned kaddr[D / 16], vaddr[D / 32];
+  {
+    const int row = half * 64 + lr;
+#pragma unroll
+    for (int s = 0; s < D / 16; s++) kaddr[s] = lds0 + row * RB + (((2 * s + lg) ^ ((row / RPB) & (CPR - 1))) * 16);
+    // lane reads 4 consecutive d of key kbase + 4 lg + (lane&15)/4 (and of that key + 8): the k-slot order of P^T
+    const int key = half * 64 + 4 * lg + ((lane & 15) >> 2);
+#pragma unroll
+    for (int db = 0; db < D / 32; db++) {
+      const int col = 32 * db + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      vaddr[db] = lds0 + 2 * TILE + key * RB + (((col >> 3) ^ (4 * ((key & 3) / RPB))) * 16) + (col & 7) * 2;
+    }
+  }
 
   f32x16_t o[D / 32];
 #pragma unroll
@@ -108,116 +167,158 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
 #pragma unroll
     for (int v = 0; v < 16; v++) o[i][v] = 0.f;
   float m = -INFINITY, l = 0.f;
-  const bf16_t *kbase = base + a;
+  f32x16_t sc0, sc1;                 // S^T of the step in flight: keys 0..31 and 32..63 of this wave's half
+  bf16x8_t pf00, pf01, pf10, pf11;   // P^T of the step whose PV is pending: [sub-block][16-key half]
+#pragma unroll
+  for (int i = 0; i < 8; i++) { pf00[i] = (bf16_t)0.f; pf01[i] = (bf16_t)0.f; pf10[i] = (bf16_t)0.f; pf11[i] = (bf16_t)0.f; }
 
-  uint4 rk[G::nld], rv[G::nld];
-  tile_load<D>(rk, kbase, ld, s_begin * KSTEP, seq, tid);
-  tile_load<D>(rv, kbase + a, ld, s_begin * KSTEP, seq, tid);
-  tile_store<D, G::kp>(rk, sbase, tid);
-  tile_store<D, G::vp>(rv, sbase + G::k_elems, tid);
-  __syncthreads();
+  // wave-uniform: does local step k hold a key this wave's queries may attend to?
+  auto active = [&](int k) {
+    const int kv0 = (s_begin + k) * KSTEP + half * 64;
+    return kv0 < seq && (!causal || kv0 <= q_wave0 + 31);
+  };
 
-  for (int st = s_begin; st < s_end; st++) {
-    const int cur = (st - s_begin) & 1;
-    const bf16_t *ks_cur = sbase + cur * STAGE + half * 64 * G::kp;
-    const bf16_t *vs_cur = sbase + cur * STAGE + G::k_elems + half * 64 * G::vp;
-    const int kv0 = st * KSTEP + half * 64;       // first key of this wave's 64-key block
-    if (st + 1 < s_end) {
-      tile_load<D>(rk, kbase, ld, (st + 1) * KSTEP, seq, tid);
-      tile_load<D>(rv, kbase + a, ld, (st + 1) * KSTEP, seq, tid);
+#define STP_SB() __builtin_amdgcn_sched_barrier(0)
+  // S(kn) = K(kn) Q^T
+  auto qk_only = [&](int kn) {
+    const unsigned kt = (kn & 1) * TILE;
+    u32x4_t fa[4], fb[4];
+#pragma unroll
+    for (int v = 0; v < 16; v++) { sc0[v] = 0.f; sc1[v] = 0.f; }
+    read_k<D, 0, 0>(fa, kaddr, kt);
+    if constexpr (D == 128) {
+      read_k<D, 0, 1>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc0, fa, qf); STP_SB();
+      read_k<D, 1, 0>(fa, kaddr, kt); lds_wait<KREADS>(); lds_tie(fb); mfma_qk<D, 1>(sc0, fb, qf); STP_SB();
+      read_k<D, 1, 1>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc1, fa, qf); STP_SB();
+      lds_wait<0>(); lds_tie(fb); mfma_qk<D, 1>(sc1, fb, qf); STP_SB();
+    } else {
+      read_k<D, 1, 0>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc0, fa, qf); STP_SB();
+      lds_wait<0>(); lds_tie(fb); mfma_qk<D, 0>(sc1, fb, qf); STP_SB();
     }
+  };
+  // O^T += V(k)^T P^T
+  auto pv_only = [&](int k) {
+    const unsigned vt = (k & 1) * TILE;
+    u32x4_t fa[4], fb[4];
+    read_v<D, 0, 0>(fa, vaddr, vt);
+    read_v<D, 0, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf00); STP_SB();
+    read_v<D, 1, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_pv<D>(o, fb, pf01); STP_SB();
+    read_v<D, 1, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf10); STP_SB();
+    lds_wait<0>(); lds_tie(fb); mfma_pv<D>(o, fb, pf11); STP_SB();
+  };
+  // both, as one software pipeline (the common case)
+  auto qk_pv = [&](int kn, int k) {
+    const unsigned kt = (kn & 1) * TILE, vt = (k & 1) * TILE;
+    u32x4_t fa[4], fb[4];
+#pragma unroll
+    for (int v = 0; v < 16; v++) { sc0[v] = 0.f; sc1[v] = 0.f; }
+    read_k<D, 0, 0>(fa, kaddr, kt);
+    if constexpr (D == 128) {
+      read_k<D, 0, 1>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc0, fa, qf); STP_SB();
+      read_k<D, 1, 0>(fa, kaddr, kt); lds_wait<KREADS>(); lds_tie(fb); mfma_qk<D, 1>(sc0, fb, qf); STP_SB();
+      read_k<D, 1, 1>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc1, fa, qf); STP_SB();
+      read_v<D, 0, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_qk<D, 1>(sc1, fb, qf); STP_SB();
+    } else {
+      read_k<D, 1, 0>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc0, fa, qf); STP_SB();
+      read_v<D, 0, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_qk<D, 0>(sc1, fb, qf); STP_SB();
+    }
+    read_v<D, 0, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf00); STP_SB();
+    read_v<D, 1, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_pv<D>(o, fb, pf01); STP_SB();
+    read_v<D, 1, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf10); STP_SB();
+    lds_wait<0>(); lds_tie(fb); mfma_pv<D>(o, fb, pf11); STP_SB();
+  };
 
-    // wave-uniform skip: all of this wave's queries precede the key block, or the block is past the end
-    const bool active = kv0 < seq && (!causal || kv0 <= q_wave0 + 31);
-    if (active) {
-      // ---- S^T[kv, q] = K Q^T for the two 32-key sub-blocks (named accumulators: an array of vectors
-      //      would be demoted to scratch memory)
-      auto scores = [&](int jb) {
-        f32x16_t acc;
+  // P(k) = online softmax of S(k) in the log2 domain; accumulator v of lane l is key
+  // kv0 + 32*jb + 8*(v/4) + 4*(l/32) + v%4, query l%32
+  auto softmax = [&](int k) {
+    const int kv0 = (s_begin + k) * KSTEP + half * 64;
+    const bool need_mask = (causal && kv0 + 63 > q_wave0) || (kv0 + 64 > seq);
+    // raw scores are kept; the 1/sqrt(d) log2(e) factor is folded into the exponent's FMA
+    auto mask_max = [&](f32x16_t &sc, int jb, float mx) {
 #pragma unroll
-        for (int v = 0; v < 16; v++) acc[v] = 0.f;
-#pragma unroll
-        for (int s = 0; s < D / 16; s++) {
-          bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(ks_cur + (32 * jb + lr) * G::kp + 16 * s + 8 * lg);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc, 0, 0, 0);
+      for (int v = 0; v < 16; v++) {
+        if (need_mask) {
+          int kv = kv0 + 32 * jb + 8 * (v >> 2) + 4 * lg + (v & 3);
+          if ((causal && kv > qg) || kv >= seq) sc[v] = -INFINITY;
         }
-        return acc;
-      };
-      f32x16_t sc0 = scores(0), sc1 = scores(1);
-      // ---- online softmax in the log2 domain; accumulator v of lane l is key
-      //      kv0 + 32*jb + 8*(v/4) + 4*(l/32) + v%4, query l%32
-      const bool need_mask = (causal && kv0 + 63 > q_wave0) || (kv0 + 64 > seq);
-      // raw scores are kept; the 1/sqrt(d) log2(e) factor is folded into the exponent's FMA
-      auto mask_max = [&](f32x16_t &sc, int jb, float mx) {
-#pragma unroll
-        for (int v = 0; v < 16; v++) {
-          if (need_mask) {
-            int kv = kv0 + 32 * jb + 8 * (v >> 2) + 4 * lg + (v & 3);
-            if ((causal && kv > qg) || kv >= seq) sc[v] = -INFINITY;
-          }
-          mx = fmaxf(mx, sc[v]);
-        }
-        return mx;
-      };
-      float mx = mask_max(sc0, 0, -INFINITY);
-      mx = mask_max(sc1, 1, mx);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;      // scale > 0: max and scaling commute
-      // Lazy rescaling: the reference m only moves when the block maximum exceeds it by more than 2^8,
-      // so exponentials stay below 256 (harmless in fp32 / bf16) and the O rescale is skipped on almost
-      // every block.  Softmax is invariant to the reference as long as l, O and P use the same one.
-      // A query row that has seen no admissible key keeps m = -inf.
-      const float m_new = (mx > m + 8.0f) ? mx : m;
-      if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {
-        const float corr = __builtin_amdgcn_exp2f(m - (m_new == -INFINITY ? 0.f : m_new));
-        l *= corr;
-#pragma unroll
-        for (int i = 0; i < D / 32; i++)
-#pragma unroll
-          for (int v = 0; v < 16; v++) o[i][v] *= corr;
-        m = m_new;
+        mx = fmaxf(mx, sc[v]);
       }
-      const float neg_ref = m == -INFINITY ? 0.f : -m;
-      auto exp_sum = [&](f32x16_t &sc, float rs) {
+      return mx;
+    };
+    float mx = mask_max(sc0, 0, -INFINITY);
+    mx = mask_max(sc1, 1, mx);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;      // scale > 0: max and scaling commute
+    // Lazy rescaling: the reference m only moves when the block maximum exceeds it by more than 2^8,
+    // so exponentials stay below 256 (harmless in fp32 / bf16) and the O rescale is skipped on almost
+    // every block.  Softmax is invariant to the reference as long as l, O and P use the same one.
+    // A query row that has seen no admissible key keeps m = -inf.
+    const float m_new = (mx > m + 8.0f) ? mx : m;
+    if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {
+      const float corr = __builtin_amdgcn_exp2f(m - (m_new == -INFINITY ? 0.f : m_new));
+      l *= corr;
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          float p = __builtin_amdgcn_exp2f(fmaf(sc[v], scale_log2, neg_ref));
-          sc[v] = p;
-          rs += p;
-        }
-        return rs;
-      };
-      float rs = exp_sum(sc0, 0.f);
-      rs = exp_sum(sc1, rs);
-      rs += __shfl_xor(rs, 32, 64);
-      l += rs;
+      for (int i = 0; i < D / 32; i++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) o[i][v] *= corr;
+      m = m_new;
+    }
+    const float neg_ref = m == -INFINITY ? 0.f : -m;
+    float rs = 0.f;
+    // k-slot i of lane-half g in the PV step (jb, t) is key 32*jb + 16*t + 8*(i/4) + 4*g + i%4
+    auto exp_pack = [&](const f32x16_t &sc, bf16x8_t &p0, bf16x8_t &p1) {
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sc[v], scale_log2, neg_ref));
+        rs += p;
+        if (v < 8) p0[v] = (bf16_t)p; else p1[v - 8] = (bf16_t)p;
+      }
+    };
+    exp_pack(sc0, pf00, pf01);
+    exp_pack(sc1, pf10, pf11);
+    rs += __shfl_xor(rs, 32, 64);
+    l += rs;
+  };
 
-      // ---- O^T[d, q] += V^T P^T ; k-slot i of lane-half g in step (jb, t) is key 32*jb + 16*t + 8*(i/4) + 4*g + i%4
-      auto pv = [&](const f32x16_t &sc, int jb) {
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-          bf16x8_t pf;
-#pragma unroll
-          for (int i = 0; i < 8; i++) pf[i] = (bf16_t)sc[8 * t + i];
-          const int krow = 32 * jb + 16 * t + 4 * lg + ((lane & 15) >> 2);
-#pragma unroll
-          for (int db = 0; db < D / 32; db++) {
-            const bf16_t *p = vs_cur + krow * G::vp + 32 * db + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-            s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
-            s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 8 * G::vp));
-            s16x8_t vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv), pf, o[db], 0, 0, 0);
-          }
-        }
-      };
-      pv(sc0, 0);
-      pv(sc1, 1);
-    }
-    if (st + 1 < s_end) {
-      tile_store<D, G::kp>(rk, sbase + (cur ^ 1) * STAGE, tid);
-      tile_store<D, G::vp>(rv, sbase + (cur ^ 1) * STAGE + G::k_elems, tid);
-    }
-    __syncthreads();
+  // ---- main loop.  Iteration k uses tiles K(k+1) and V(k).  At its top every wave's loads have landed
+  // (vmcnt(0) + barrier) and every wave is done with K(k) and V(k-1), whose slots take K(k+2) and V(k+1).
+  // Group A runs M(k) then V(k+1), group B V(k) then M(k): the matrix work of one wave of a SIMD
+  // coincides with the vector work of the other without a barrier in between.
+  const bool last_active = active(ns - 1);      // only the last step of a chunk can be masked out for a wave
+  auto matrix_phase = [&](int k) {
+    const bool do_qk = k + 1 < ns && (k + 1 < ns - 1 || last_active), do_pv = k >= 0 && (k < ns - 1 || last_active);
+    if (do_qk && do_pv) qk_pv(k + 1, k);
+    else if (do_qk) qk_only(k + 1);
+    else if (do_pv) pv_only(k);
+  };
+  auto vector_phase = [&](int k) {
+    if (k >= 0 && k < ns && (k < ns - 1 || last_active)) softmax(k);
+  };
+  issue_tile(0, false);
+  issue_tile(0, true);
+  if (ns > 1) {
+    issue_tile(1, false);
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * NLD) : "memory");
+  } else {
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NLD) : "memory");
   }
+  for (int k = -1; k < ns; k++) {
+    if (k >= 0) {
+      STP_SB();
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      STP_SB();
+      if (k + 2 < ns) issue_tile(k + 2, false);
+      if (k + 1 < ns) issue_tile(k + 1, true);
+    }
+    if (half == 0) {
+      matrix_phase(k);
+      vector_phase(k + 1);
+    } else {
+      vector_phase(k);
+      matrix_phase(k);
+    }
+  }
+#undef STP_SB
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
   // ---- merge the two key halves (upper half -> LDS -> lower half), then write this chunk's partial:
   // O (un-normalised, relative to m), m (log2 domain), l.
@@ -302,7 +403,7 @@ template <int D>
 int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out, float *lse, float *ws, size_t ws_bytes,
                hipStream_t s) {
   using G = AttnGeom<D>;
-  constexpr size_t smem = (size_t)2 * (G::k_elems + G::v_elems) * sizeof(bf16_t);
+  constexpr size_t smem = (size_t)4 * G::TILE;   // K ring and V ring of two tiles each
   static_assert(smem >= (size_t)(4 * (D / 2) * 64 + 4 * 2 * 32) * sizeof(float), "merge area fits");
   static_assert(smem <= 160 * 1024, "LDS budget");
   auto kern = attn_fwd_bf16_kernel<D>;
@@ -311,6 +412,8 @@ int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out
     STP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
+  if ((size_t)d->seq * 3 * d->heads_local * D * sizeof(bf16_t) > (size_t)0x7fffffff)
+    return stp_fail(ctx, STP_ESHAPE, "attention forward: one sequence of QKV must span less than 2 GiB%s");
   const int nqb = (d->seq + QB - 1) / QB;
   const int max_chunks = (attn_steps(nqb - 1, d->seq, d->causal) + CH2 - 1) / CH2;
   const size_t need = (size_t)d->mbsz * d->heads_local * nqb * max_chunks * G::piece_floats * sizeof(float);
