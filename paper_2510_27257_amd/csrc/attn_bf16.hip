@@ -32,6 +32,7 @@
 // with explicit waits, software-pipelined one group of MFMAs ahead.
 #include "common.h"
 #include "lds_dma.h"
+#include <type_traits>
 
 namespace {
 
@@ -136,13 +137,15 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
     ld_kcol[j] = (unsigned)(head * D + a + (slot ^ ((row / RPB) & (CPR - 1))) * 8) * 2u;
     ld_vcol[j] = (unsigned)(head * D + 2 * a + (slot ^ (4 * ((row & 3) / RPB))) * 8) * 2u;
   }
-  auto issue_tile = [&](int k, bool is_v) {   // tile of local step k into ring slot k & 1
-    char *dst = smem_raw + (is_v ? 2 * TILE : 0) + (k & 1) * TILE + wave * NLD * 1024;
+  // load j (0 .. NLD-1) of the K or V tile of local step k, into ring slot k & 1
+  auto issue_one = [&](int k, bool is_v, int j) {
+    char *dst = smem_raw + (is_v ? 2 * TILE : 0) + (k & 1) * TILE + (wave * NLD + j) * 1024;
+    const int grow = min((s_begin + k) * KSTEP + ld_row[j], seq - 1);
+    dma_load16(rs, dst, (unsigned)grow * (unsigned)(ld * 2) + (is_v ? ld_vcol[j] : ld_kcol[j]), 0);
+  };
+  auto issue_tile = [&](int k, bool is_v) {
 #pragma unroll
-    for (int j = 0; j < NLD; j++) {
-      const int grow = min((s_begin + k) * KSTEP + ld_row[j], seq - 1);
-      dma_load16(rs, dst + j * 1024, (unsigned)grow * (unsigned)(ld * 2) + (is_v ? ld_vcol[j] : ld_kcol[j]), 0);
-    }
+    for (int j = 0; j < NLD; j++) issue_one(k, is_v, j);
   };
 
   // ---- fragment addresses within a tile (this wave's 64-key half)
@@ -206,48 +209,63 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
     read_v<D, 1, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf10); STP_SB();
     lds_wait<0>(); lds_tie(fb); mfma_pv<D>(o, fb, pf11); STP_SB();
   };
-  // both, as one software pipeline (the common case)
-  auto qk_pv = [&](int kn, int k) {
+  // both, as one software pipeline (the common case).  With `defer` the wave's direct-to-LDS loads of this
+  // iteration (K(k+2) if ld_k, V(k+1) if ld_v) are issued one at a time behind the MFMA groups, whose
+  // execution covers the time the address unit holds the wave, instead of in a burst before them.
+  auto qk_pv = [&](int kn, int k, bool ld_k, bool ld_v) {
     const unsigned kt = (kn & 1) * TILE, vt = (k & 1) * TILE;
     u32x4_t fa[4], fb[4];
 #pragma unroll
     for (int v = 0; v < 16; v++) { sc0[v] = 0.f; sc1[v] = 0.f; }
+    // the 2 * NLD loads are spread over the first 2 * NLD of the 8 (D = 128) or 6 (D = 64) groups
+#define STP_LD(g)                                                        \
+    do {                                                                 \
+      if ((g) < NLD) { if (ld_k) issue_one(k + 2, false, (g)); }         \
+      else if ((g) < 2 * NLD) { if (ld_v) issue_one(k + 1, true, (g) - NLD); } \
+      STP_SB();                                                          \
+    } while (0)
     read_k<D, 0, 0>(fa, kaddr, kt);
     if constexpr (D == 128) {
-      read_k<D, 0, 1>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc0, fa, qf); STP_SB();
-      read_k<D, 1, 0>(fa, kaddr, kt); lds_wait<KREADS>(); lds_tie(fb); mfma_qk<D, 1>(sc0, fb, qf); STP_SB();
-      read_k<D, 1, 1>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc1, fa, qf); STP_SB();
-      read_v<D, 0, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_qk<D, 1>(sc1, fb, qf); STP_SB();
+      read_k<D, 0, 1>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc0, fa, qf); STP_SB(); STP_LD(0);
+      read_k<D, 1, 0>(fa, kaddr, kt); lds_wait<KREADS>(); lds_tie(fb); mfma_qk<D, 1>(sc0, fb, qf); STP_SB(); STP_LD(1);
+      read_k<D, 1, 1>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc1, fa, qf); STP_SB(); STP_LD(2);
+      read_v<D, 0, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_qk<D, 1>(sc1, fb, qf); STP_SB(); STP_LD(3);
+      read_v<D, 0, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf00); STP_SB(); STP_LD(4);
+      read_v<D, 1, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_pv<D>(o, fb, pf01); STP_SB(); STP_LD(5);
+      read_v<D, 1, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf10); STP_SB(); STP_LD(6);
+      lds_wait<0>(); lds_tie(fb); mfma_pv<D>(o, fb, pf11); STP_SB(); STP_LD(7);
     } else {
-      read_k<D, 1, 0>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc0, fa, qf); STP_SB();
-      read_v<D, 0, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_qk<D, 0>(sc1, fb, qf); STP_SB();
+      read_k<D, 1, 0>(fb, kaddr, kt); lds_wait<KREADS>(); lds_tie(fa); mfma_qk<D, 0>(sc0, fa, qf); STP_SB(); STP_LD(0);
+      read_v<D, 0, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_qk<D, 0>(sc1, fb, qf); STP_SB(); STP_LD(1);
+      read_v<D, 0, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf00); STP_SB(); STP_LD(2);
+      read_v<D, 1, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_pv<D>(o, fb, pf01); STP_SB(); STP_LD(3);
+      read_v<D, 1, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf10); STP_SB();
+      lds_wait<0>(); lds_tie(fb); mfma_pv<D>(o, fb, pf11); STP_SB();
     }
-    read_v<D, 0, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf00); STP_SB();
-    read_v<D, 1, 0>(fa, vaddr, vt); lds_wait<VREADS>(); lds_tie(fb); mfma_pv<D>(o, fb, pf01); STP_SB();
-    read_v<D, 1, 1>(fb, vaddr, vt); lds_wait<VREADS>(); lds_tie(fa); mfma_pv<D>(o, fa, pf10); STP_SB();
-    lds_wait<0>(); lds_tie(fb); mfma_pv<D>(o, fb, pf11); STP_SB();
+#undef STP_LD
   };
 
   // P(k) = online softmax of S(k) in the log2 domain; accumulator v of lane l is key
   // kv0 + 32*jb + 8*(v/4) + 4*(l/32) + v%4, query l%32
-  auto softmax = [&](int k) {
+  auto softmax_impl = [&](int k, auto masked) {
+    constexpr bool MASK = decltype(masked)::value;
     const int kv0 = (s_begin + k) * KSTEP + half * 64;
-    const bool need_mask = (causal && kv0 + 63 > q_wave0) || (kv0 + 64 > seq);
     // raw scores are kept; the 1/sqrt(d) log2(e) factor is folded into the exponent's FMA
     auto mask_max = [&](f32x16_t &sc, int jb, float mx) {
+      if constexpr (MASK) {
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        if (need_mask) {
-          int kv = kv0 + 32 * jb + 8 * (v >> 2) + 4 * lg + (v & 3);
-          if ((causal && kv > qg) || kv >= seq) sc[v] = -INFINITY;
+        for (int v = 0; v < 16; v++) {
+          const int kv = kv0 + 32 * jb + 8 * (v >> 2) + 4 * lg + (v & 3);
+          sc[v] = ((causal && kv > qg) || kv >= seq) ? -INFINITY : sc[v];
         }
-        mx = fmaxf(mx, sc[v]);
       }
+#pragma unroll
+      for (int v = 0; v < 16; v++) mx = fmaxf(mx, sc[v]);
       return mx;
     };
     float mx = mask_max(sc0, 0, -INFINITY);
     mx = mask_max(sc1, 1, mx);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;      // scale > 0: max and scaling commute
+    mx = fmaxf(mx, other_half(mx)) * scale_log2;      // scale > 0: max and scaling commute
     // Lazy rescaling: the reference m only moves when the block maximum exceeds it by more than 2^8,
     // so exponentials stay below 256 (harmless in fp32 / bf16) and the O rescale is skipped on almost
     // every block.  Softmax is invariant to the reference as long as l, O and P use the same one.
@@ -275,8 +293,14 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
     };
     exp_pack(sc0, pf00, pf01);
     exp_pack(sc1, pf10, pf11);
-    rs += __shfl_xor(rs, 32, 64);
+    rs += other_half(rs);
     l += rs;
+  };
+  // only a step that touches the causal diagonal or the end of the sequence needs the mask
+  auto softmax = [&](int k) {
+    const int kv0 = (s_begin + k) * KSTEP + half * 64;
+    if ((causal && kv0 + 63 > q_wave0) || (kv0 + 64 > seq)) softmax_impl(k, std::true_type{});
+    else softmax_impl(k, std::false_type{});
   };
 
   // ---- main loop.  Iteration k uses tiles K(k+1) and V(k).  At its top every wave's loads have landed
@@ -284,12 +308,6 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
   // Group A runs M(k) then V(k+1), group B V(k) then M(k): the matrix work of one wave of a SIMD
   // coincides with the vector work of the other without a barrier in between.
   const bool last_active = active(ns - 1);      // only the last step of a chunk can be masked out for a wave
-  auto matrix_phase = [&](int k) {
-    const bool do_qk = k + 1 < ns && (k + 1 < ns - 1 || last_active), do_pv = k >= 0 && (k < ns - 1 || last_active);
-    if (do_qk && do_pv) qk_pv(k + 1, k);
-    else if (do_qk) qk_only(k + 1);
-    else if (do_pv) pv_only(k);
-  };
   auto vector_phase = [&](int k) {
     if (k >= 0 && k < ns && (k < ns - 1 || last_active)) softmax(k);
   };
@@ -302,20 +320,24 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NLD) : "memory");
   }
   for (int k = -1; k < ns; k++) {
+    const bool do_qk = k + 1 < ns && (k + 1 < ns - 1 || last_active), do_pv = k >= 0 && (k < ns - 1 || last_active);
+    const bool ld_k = k >= 0 && k + 2 < ns, ld_v = k >= 0 && k + 1 < ns;
+    // group A starts with the matrix phase: its loads ride behind the MFMA groups
+    const bool defer = half == 0 && do_qk && do_pv;
     if (k >= 0) {
       STP_SB();
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
       STP_SB();
-      if (k + 2 < ns) issue_tile(k + 2, false);
-      if (k + 1 < ns) issue_tile(k + 1, true);
+      if (!defer) {
+        if (ld_k) issue_tile(k + 2, false);
+        if (ld_v) issue_tile(k + 1, true);
+      }
     }
-    if (half == 0) {
-      matrix_phase(k);
-      vector_phase(k + 1);
-    } else {
-      vector_phase(k);
-      matrix_phase(k);
-    }
+    if (half == 1) vector_phase(k);
+    if (do_qk && do_pv) qk_pv(k + 1, k, defer && ld_k, defer && ld_v);
+    else if (do_qk) qk_only(k + 1);
+    else if (do_pv) pv_only(k);
+    if (half == 0) vector_phase(k + 1);
   }
 #undef STP_SB
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");

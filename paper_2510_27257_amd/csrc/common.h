@@ -86,6 +86,17 @@ template <> struct Vec8<bf16_t> {
 template <typename T> __device__ __forceinline__ float to_f32(T x) { return (float)x; }
 template <typename T> __device__ __forceinline__ T from_f32(float x) { return (T)x; }
 
+// The value lane (l ^ 32) holds, without the LDS round trip of a shuffle: v_permlane32_swap exchanges the
+// upper half of one register with the lower half of another.  (Inline assembly: the builtin form was
+// seen to return the same register for both results.  The no-ops cover the wait states between a
+// vector write and the lane permute, which the compiler cannot insert inside assembly.)
+__device__ __forceinline__ float other_half(float v) {
+  float a = v, b = v;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32_e32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  // a = [v.lo | v.lo], b = [v.hi | v.hi]: lanes below 32 want b, the others a
+  return (threadIdx.x & 32) ? a : b;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
