@@ -17,15 +17,20 @@
 // the 256 compute units; the 8-wave layout puts two waves on every SIMD so one wave's exponentials
 // overlap the other's MFMAs.  S and dP are formed twice (7 matrix products executed for the 5 the
 // method needs): the price of bit-reproducible gradients without atomics.
-// Tiles that are read both ways sit in LDS twice, once per pitch (16-byte fragment reads want a
-// +16-byte row pitch, transposing reads a +64-byte one), so both patterns are bank-conflict free.
+// Tiles go global -> LDS directly (buffer_load ... lds) and sit there once, unpadded ([row][D]); the
+// 16-byte chunks of a row are permuted by an XOR, slot = chunk ^ swz(row), applied on the global side
+// of the load and undone in the fragment addresses.  swz is chosen so that both access patterns are
+// bank-conflict free: 16-byte fragment reads (16 consecutive rows, same chunk) and transposing
+// ds_read_b64_tr_b16 reads (4 consecutive rows x 4 consecutive chunks).  Fragment reads are inline
+// assembly with explicit waits, software-pipelined one MFMA group ahead.
 #include "common.h"
+#include "lds_dma.h"
+#include <type_traits>
 
 int stp_launch_rowdot(stp_ctx *ctx, const stp_layer_desc *d, const void *a, const void *b, float *delta, hipStream_t s);
 
 namespace {
 
-typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr int KVB = 128;    // keys per dkv workgroup / per dq step
 constexpr int QSTEP = 64;   // queries per dkv step
@@ -33,50 +38,63 @@ constexpr int CHQ = 16;     // dkv: steps per chunk (1024 queries)
 constexpr int CHK = 8;      // dq: 128-key steps per chunk (1024 keys)
 
 template <int D> struct BG {
-  static constexpr int kc = D + 8;    // pitch for 16-byte fragment reads
-  static constexpr int tr = D + 32;   // pitch for transposing reads
+  static constexpr int RB = D * 2;        // bytes per tile row
+  static constexpr int CPR = D / 8;       // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;    // rows covered by one direct-to-LDS wave instruction
+  // chunk permutation of a tile row.  D = 128 (16 chunks, one row per 256 B): rows r..r+15 get 16 distinct
+  // values and rows 4m..4m+3 differ in bits 2-3.  D = 64 (8 chunks, two rows per 256 B): the same for row pairs.
+  static __device__ __forceinline__ int swz(int row) {
+    if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+    const int x = row >> 1;
+    return ((x & 1) << 2) | ((x >> 1) & 3);
+  }
 };
 
-// fragment (32 rows x 16 k) from a [row][k] tile, k contiguous: lane supplies row row0 + l%32, k0 + 8*(l/32)..+7
-template <int P>
-__device__ __forceinline__ bf16x8_t frag_kc(const bf16_t *tile, int row0, int k0, int lane) {
-  return *reinterpret_cast<const bf16x8_t *>(tile + (row0 + (lane & 31)) * P + k0 + 8 * (lane >> 5));
-}
-// A-operand fragment whose 32 rows are the tile's COLUMNS c0.. and whose k-slots are tile rows
-// r_lo + 4*(lane/32) + {0..3} and r_lo + 8 + 4*(lane/32) + {0..3}: the order in which a 32x32
-// accumulator hands its rows to the next MFMA as a B operand.
-template <int P>
-__device__ __forceinline__ bf16x8_t frag_tr(const bf16_t *tile, int c0, int r_lo, int lane) {
-  const bf16_t *p = tile + (r_lo + 4 * (lane >> 5) + ((lane & 15) >> 2)) * P + c0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
-  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 8 * P));
-  s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8_t, v);
+// Loads rows row0 .. row0+ROWS-1 (clamped to seq-1) of a [seq][ld] bf16 matrix, D columns from byte column col_bytes,
+// into the swizzled LDS tile.  Every wave issues ROWS / RPI / 8 wave instructions.
+template <int D, int ROWS>
+__device__ __forceinline__ void dma_tile(__amdgpu_buffer_rsrc_t rs, char *tile, int row0, int seq, unsigned ld_bytes, unsigned col_bytes,
+                                         int wave, int lane) {
+  using G = BG<D>;
+  constexpr int N = ROWS / G::RPI / 8;
+  static_assert(N >= 1, "tile too small for 8 waves");
+#pragma unroll
+  for (int j = 0; j < N; j++) {
+    const int row = (wave * N + j) * G::RPI + lane / G::CPR, slot = lane % G::CPR;
+    const int grow = min(row0 + row, seq - 1);
+    dma_load16(rs, tile + (wave * N + j) * 1024, (unsigned)grow * ld_bytes + col_bytes + ((slot ^ G::swz(row)) * 16), 0);
+  }
 }
 
-// ROWS x D tile, 512 threads: registers <- global (rows clamped to seq-1), LDS <- registers (rows past seq zeroed)
-template <int ROWS, int D, int NLD>
-__device__ __forceinline__ void tile_load(uint4 (&r)[NLD], const bf16_t *__restrict__ base, size_t ld, int row0, int seq, int tid) {
-  static_assert(NLD == ROWS * D / 8 / 512, "register count");
-#pragma unroll
-  for (int i = 0; i < NLD; i++) {
-    int q = tid + 512 * i;
-    int rr = q / (D / 8), c = (q % (D / 8)) * 8;
-    int row = min(row0 + rr, seq - 1);
-    r[i] = *reinterpret_cast<const uint4 *>(base + (size_t)row * ld + c);
-  }
+// two 16-byte fragments (k-steps 2*SP and 2*SP+1) of tile rows ROW0 + lane%32; base = tile + lane part (see kc_lane)
+template <int D, int ROW0, int SP>
+__device__ __forceinline__ void read_kc2(u32x4_t &f0, u32x4_t &f1, unsigned base) {
+  f0 = lds_read_b128<ROW0 * BG<D>::RB>(base ^ (32 * (2 * SP)));
+  f1 = lds_read_b128<ROW0 * BG<D>::RB>(base ^ (32 * (2 * SP + 1)));
 }
-template <int D, int P, int NLD>
-__device__ __forceinline__ void tile_store(const uint4 (&r)[NLD], bf16_t *tile, int row0, int seq, int tid) {
-#pragma unroll
-  for (int i = 0; i < NLD; i++) {
-    int q = tid + 512 * i;
-    int rr = q / (D / 8), c = (q % (D / 8)) * 8;
-    const bool ok = row0 + rr < seq;
-    uint4 v;
-    v.x = ok ? r[i].x : 0u; v.y = ok ? r[i].y : 0u; v.z = ok ? r[i].z : 0u; v.w = ok ? r[i].w : 0u;
-    *reinterpret_cast<uint4 *>(tile + rr * P + c) = v;
-  }
+// lane part of a 16-byte fragment address: row lane%32 (+ a multiple of 32), k-step 0; XOR 32*s selects k-step s
+template <int D>
+__device__ __forceinline__ unsigned kc_lane(int lane) {
+  const int lr = lane & 31, lg = lane >> 5;
+  return lr * BG<D>::RB + ((lg ^ BG<D>::swz(lr)) * 16);
+}
+// Transposed fragment: A operand whose 32 rows are tile COLUMNS 32*db .. and whose k-slots are tile rows
+// R0 + 4*(lane/32) + {0..3} and R0 + 8 + 4*(lane/32) + {0..3} (R0 a multiple of 16): the order in which a
+// 32x32 accumulator hands its rows to the next MFMA as a B operand.  lo/hi = tile + lane parts (tr_lane).
+template <int D, int R0>
+__device__ __forceinline__ u32x4_t read_tr(unsigned lo, unsigned hi, int db) {
+  u32x2_t a, b;
+  const unsigned x = 64 * db;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(a) : "v"(lo ^ x), "n"(R0 * BG<D>::RB));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(b) : "v"(hi ^ x), "n"((R0 + 8) * BG<D>::RB));
+  return __builtin_shufflevector(a, b, 0, 1, 2, 3);
+}
+template <int D>
+__device__ __forceinline__ void tr_lane(int lane, unsigned &lo, unsigned &hi) {
+  const int row = 4 * (lane >> 5) + ((lane & 15) >> 2);      // + R0 (multiple of 16: does not change swz)
+  const int col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);   // + 32 db (XOR 64*db on the address)
+  lo = row * BG<D>::RB + (((col >> 3) ^ BG<D>::swz(row)) * 16) + (col & 7) * 2;
+  hi = row * BG<D>::RB + (((col >> 3) ^ BG<D>::swz(row + 8)) * 16) + (col & 7) * 2;
 }
 
 __host__ __device__ inline int dkv_first_step(int kvb, int causal) { return causal ? (kvb * KVB) / QSTEP : 0; }
@@ -85,8 +103,12 @@ __host__ __device__ inline int dq_steps(int qb, int seq, int causal) {
   return (kv_end + KVB - 1) / KVB;
 }
 
+#define STP_SB() __builtin_amdgcn_sched_barrier(0)
+
 // ---------------------------------------------------------------------------------------------
 // dK, dV partials.  piece layout: dK [128][D] fp32, then dV [128][D] fp32
+// LDS: K [128][D], V [128][D] (resident), then a ring of two stages { Q [64][D], dO [64][D] }, then the
+// ring of { lse [64], delta [64] } (fp32).
 // ---------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
@@ -94,15 +116,10 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
                                                            float *__restrict__ part, int seq, int n, int causal,
                                                            int max_chunks, float scale) {
   using G = BG<D>;
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  bf16_t *const k_kc = reinterpret_cast<bf16_t *>(smem_raw);
-  bf16_t *const v_kc = k_kc + KVB * G::kc;
-  bf16_t *const q_kc = v_kc + KVB * G::kc;
-  bf16_t *const q_tr = q_kc + QSTEP * G::kc;
-  bf16_t *const o_kc = q_tr + QSTEP * G::tr;
-  bf16_t *const o_tr = o_kc + QSTEP * G::kc;
-  float *const s_lse = reinterpret_cast<float *>(o_tr + QSTEP * G::tr);   // [64] log2-domain L
-  float *const s_del = s_lse + QSTEP;
+  constexpr int RB = G::RB;
+  constexpr int KV_TILE = KVB * RB, Q_TILE = QSTEP * RB, STAGE = 2 * Q_TILE;
+  constexpr int OFF_K = 0, OFF_V = KV_TILE, OFF_RING = 2 * KV_TILE, OFF_STAT = OFF_RING + 2 * STAGE;
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lg = lane >> 5;
@@ -112,101 +129,142 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
   const int nq = (seq + QSTEP - 1) / QSTEP;
   const int s_begin = dkv_first_step(kvb, causal) + chunk * CHQ, s_end = min(nq, s_begin + CHQ);
   if (s_begin >= nq) return;
+  const int ns = s_end - s_begin;
 
   const int a = n * D;
-  const size_t ld = 3 * (size_t)a;
-  const bf16_t *qbase = qkv + (size_t)b * seq * ld + head * D;
-  const bf16_t *dobase = dout + (size_t)b * seq * a + head * D;
+  const unsigned ldq = 3u * a * 2u, ldo = (unsigned)a * 2u;       // row pitches in bytes
+  const bf16_t *qkv_b = qkv + (size_t)b * seq * 3 * a;
+  const bf16_t *do_b = dout + (size_t)b * seq * a;
   const float *lse_b = lse + ((size_t)b * n + head) * seq;
   const float *del_b = delta + ((size_t)b * n + head) * seq;
+  const __amdgpu_buffer_rsrc_t rs_qkv =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv_b), 0, (int)min((size_t)seq * ldq, (size_t)0x7fffffff), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_do =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(do_b), 0, (int)min((size_t)seq * ldo, (size_t)0x7fffffff), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_lse = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(lse_b), 0, seq * 4, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_del = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(del_b), 0, seq * 4, 0x00020000);
   const int kv_wave0 = kvb * KVB + ksub * 32;
   const int kvg = kv_wave0 + lr;
   const float scale_log2 = scale * LOG2E;
 
+  // tile k of the chunk (64 queries): Q, dO, lse, delta into ring stage k & 1
+  auto issue_step = [&](int k) {
+    const int q0 = (s_begin + k) * QSTEP;
+    char *st = smem_raw + OFF_RING + (k & 1) * STAGE;
+    dma_tile<D, QSTEP>(rs_qkv, st, q0, seq, ldq, (unsigned)(head * D) * 2u, wave, lane);
+    dma_tile<D, QSTEP>(rs_do, st + Q_TILE, q0, seq, ldo, (unsigned)(head * D) * 2u, wave, lane);
+    if (wave < 2) {   // one 4-byte-per-lane instruction each for the 64 lse and delta values
+      const unsigned off = (unsigned)min(q0 + lane, seq - 1) * 4u;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(wave == 0 ? rs_lse : rs_del,
+                                               (lptr_t)(smem_raw + OFF_STAT + (k & 1) * 512 + wave * 256), 4, off, 0, 0, 0);
+    }
+  };
+
   // K and V of the 128 keys: loaded once
-  {
-    uint4 rk[KVB * D / 8 / 512], rv[KVB * D / 8 / 512];
-    tile_load<KVB, D>(rk, qbase + a, ld, kvb * KVB, seq, tid);
-    tile_load<KVB, D>(rv, qbase + 2 * a, ld, kvb * KVB, seq, tid);
-    tile_store<D, G::kc>(rk, k_kc, kvb * KVB, seq, tid);
-    tile_store<D, G::kc>(rv, v_kc, kvb * KVB, seq, tid);
-  }
+  dma_tile<D, KVB>(rs_qkv, smem_raw + OFF_K, kvb * KVB, seq, ldq, (unsigned)(a + head * D) * 2u, wave, lane);
+  dma_tile<D, KVB>(rs_qkv, smem_raw + OFF_V, kvb * KVB, seq, ldq, (unsigned)(2 * a + head * D) * 2u, wave, lane);
+  issue_step(0);
+
+  const unsigned lds0 = (unsigned)(size_t)(const __attribute__((address_space(3))) char *)smem_raw;
+  const unsigned kcl = kc_lane<D>(lane);
+  unsigned trl_lo, trl_hi;
+  tr_lane<D>(lane, trl_lo, trl_hi);
+  const unsigned k_base = lds0 + OFF_K + ksub * 32 * RB + kcl, v_base = lds0 + OFF_V + ksub * 32 * RB + kcl;
+
   f32x16_t dk[D / 32], dv[D / 32];
 #pragma unroll
   for (int i = 0; i < D / 32; i++)
 #pragma unroll
     for (int v = 0; v < 16; v++) { dk[i][v] = 0.f; dv[i][v] = 0.f; }
 
-  uint4 rq[QSTEP * D / 8 / 512], ro[QSTEP * D / 8 / 512];
-  float r_l = 0.f, r_d = 0.f;
-  tile_load<QSTEP, D>(rq, qbase, ld, s_begin * QSTEP, seq, tid);
-  tile_load<QSTEP, D>(ro, dobase, a, s_begin * QSTEP, seq, tid);
-  if (tid < QSTEP) {
-    int qi = s_begin * QSTEP + tid;
-    r_l = qi < seq ? lse_b[qi] * LOG2E : INFINITY;       // +inf makes P = 0 for rows past the end
-    r_d = qi < seq ? del_b[qi] : 0.f;
-  }
-  for (int st = s_begin; st < s_end; st++) {
-    const int q0 = st * QSTEP;
-    tile_store<D, G::kc>(rq, q_kc, q0, seq, tid);
-    tile_store<D, G::tr>(rq, q_tr, q0, seq, tid);
-    tile_store<D, G::kc>(ro, o_kc, q0, seq, tid);
-    tile_store<D, G::tr>(ro, o_tr, q0, seq, tid);
-    if (tid < QSTEP) { s_lse[tid] = r_l; s_del[tid] = r_d; }
-    __syncthreads();
-    if (st + 1 < s_end) {
-      tile_load<QSTEP, D>(rq, qbase, ld, q0 + QSTEP, seq, tid);
-      tile_load<QSTEP, D>(ro, dobase, a, q0 + QSTEP, seq, tid);
-      if (tid < QSTEP) {
-        int qi = q0 + QSTEP + tid;
-        r_l = qi < seq ? lse_b[qi] * LOG2E : INFINITY;
-        r_d = qi < seq ? del_b[qi] : 0.f;
-      }
-    }
+  for (int k = 0; k < ns; k++) {
+    // every wave's loads of tile k have landed; every wave is done with tile k-1, whose stage takes tile k+1
+    STP_SB();
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    STP_SB();
+    if (k + 1 < ns) issue_step(k + 1);
+    const int q0 = (s_begin + k) * QSTEP;
     const int qs0 = q0 + 32 * qhalf;                        // this wave's 32 queries of the step
     const bool active = !causal || qs0 + 31 >= kv_wave0;    // some query sees some key of the wave
-    if (active) {
-      const bool need_mask = causal && qs0 < kv_wave0 + 31;
-      f32x16_t sacc, pacc;
+    if (!active) continue;
+    const unsigned stage = lds0 + OFF_RING + (k & 1) * STAGE;
+    const unsigned q_kc = stage + qhalf * 32 * RB + kcl, o_kc = q_kc + Q_TILE;
+    const unsigned q_lo = stage + qhalf * 32 * RB + trl_lo, q_hi = stage + qhalf * 32 * RB + trl_hi;
+    const unsigned o_lo = q_lo + Q_TILE, o_hi = q_hi + Q_TILE;
+    const float *s_lse = reinterpret_cast<const float *>(smem_raw + OFF_STAT + (k & 1) * 512) + 32 * qhalf;
+    const float *s_del = s_lse + 64;
+
+    // ---- S = Q K^T and dP = dO V^T for 32 queries x 32 keys
+    f32x16_t sacc, pacc;
 #pragma unroll
-      for (int v = 0; v < 16; v++) { sacc[v] = 0.f; pacc[v] = 0.f; }
-#pragma unroll
-      for (int s = 0; s < D / 16; s++) {
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_kc<G::kc>(q_kc, 32 * qhalf, 16 * s, lane),
-                                                       frag_kc<G::kc>(k_kc, 32 * ksub, 16 * s, lane), sacc, 0, 0, 0);
-        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_kc<G::kc>(o_kc, 32 * qhalf, 16 * s, lane),
-                                                       frag_kc<G::kc>(v_kc, 32 * ksub, 16 * s, lane), pacc, 0, 0, 0);
-      }
-      // accumulator v of lane l: query qs0 + 8*(v/4) + 4*(l/32) + v%4, key kv_wave0 + l%32
-      bf16x8_t pf[2], sf[2];
+    for (int v = 0; v < 16; v++) { sacc[v] = 0.f; pacc[v] = 0.f; }
+    u32x4_t fa[4], fb[4];
+#define STP_SP(buf, acc) do {                                                                                                   \
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, buf[0]), __builtin_bit_cast(bf16x8_t, buf[2]), acc, 0, 0, 0); \
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, buf[1]), __builtin_bit_cast(bf16x8_t, buf[3]), acc, 0, 0, 0); \
+      STP_SB(); } while (0)
+#define STP_RD_S(buf, SP) do { read_kc2<D, 0, SP>(buf[0], buf[1], q_kc); read_kc2<D, 0, SP>(buf[2], buf[3], k_base); } while (0)
+#define STP_RD_P(buf, SP) do { read_kc2<D, 0, SP>(buf[0], buf[1], o_kc); read_kc2<D, 0, SP>(buf[2], buf[3], v_base); } while (0)
+#define STP_RD_T(buf, lo, hi, T) do {                                                                        \
+      buf[0] = read_tr<D, 16 * T>(lo, hi, 0); buf[1] = read_tr<D, 16 * T>(lo, hi, 1);                        \
+      if constexpr (D == 128) { buf[2] = read_tr<D, 16 * T>(lo, hi, 2); buf[3] = read_tr<D, 16 * T>(lo, hi, 3); } } while (0)
+    constexpr int TR_READS = 2 * (D / 32);
+    STP_RD_S(fa, 0);
+    STP_RD_P(fb, 0); lds_wait<4>(); lds_tie(fa); STP_SP(fa, sacc);
+    STP_RD_S(fa, 1); lds_wait<4>(); lds_tie(fb); STP_SP(fb, pacc);
+    if constexpr (D == 128) {
+      STP_RD_P(fb, 1); lds_wait<4>(); lds_tie(fa); STP_SP(fa, sacc);
+      STP_RD_S(fa, 2); lds_wait<4>(); lds_tie(fb); STP_SP(fb, pacc);
+      STP_RD_P(fb, 2); lds_wait<4>(); lds_tie(fa); STP_SP(fa, sacc);
+      STP_RD_S(fa, 3); lds_wait<4>(); lds_tie(fb); STP_SP(fb, pacc);
+      STP_RD_P(fb, 3); lds_wait<4>(); lds_tie(fa); STP_SP(fa, sacc);
+    } else {
+      STP_RD_P(fb, 1); lds_wait<4>(); lds_tie(fa); STP_SP(fa, sacc);
+    }
+    STP_RD_T(fa, o_lo, o_hi, 0); lds_wait<TR_READS>(); lds_tie(fb); STP_SP(fb, pacc);   // first dO^T fragments ride through the vector phase
+
+    // ---- P = exp(S - L), dS = P o (dP - delta); accumulator v of lane l: query qs0 + 8*(v/4) + 4*(l/32) + v%4, key kv_wave0 + l%32
+    bf16x8_t pf[2], sf[2];
+    auto vector_phase = [&](auto masked) {
+      constexpr bool MASK = decltype(masked)::value;
 #pragma unroll
       for (int j = 0; j < 4; j++) {
-        const f32x4_t L4 = *reinterpret_cast<const f32x4_t *>(s_lse + 32 * qhalf + 8 * j + 4 * lg);
-        const f32x4_t D4 = *reinterpret_cast<const f32x4_t *>(s_del + 32 * qhalf + 8 * j + 4 * lg);
+        const f32x4_t L4 = *reinterpret_cast<const f32x4_t *>(s_lse + 8 * j + 4 * lg);
+        const f32x4_t D4 = *reinterpret_cast<const f32x4_t *>(s_del + 8 * j + 4 * lg);
 #pragma unroll
         for (int r = 0; r < 4; r++) {
           const int v = 4 * j + r;
-          float p = __builtin_amdgcn_exp2f(sacc[v] * scale_log2 - L4[r]);
-          if (need_mask) {
+          float p = __builtin_amdgcn_exp2f(fmaf(sacc[v], scale_log2, -L4[r] * LOG2E));
+          if constexpr (MASK) {
             const int qi = qs0 + 8 * j + 4 * lg + r;
-            if (qi < kvg) p = 0.f;
+            p = ((causal && qi < kvg) || qi >= seq) ? 0.f : p;
           }
           const float ds = p * (pacc[v] - D4[r]);
           pf[j >> 1][4 * (j & 1) + r] = (bf16_t)p;
           sf[j >> 1][4 * (j & 1) + r] = (bf16_t)ds;
         }
       }
-      // dV^T[d, kv] += dO^T P ; dK^T[d, kv] += Q^T dS   (k = the 32 queries, two 16-steps)
-#pragma unroll
-      for (int t = 0; t < 2; t++)
-#pragma unroll
-        for (int db = 0; db < D / 32; db++) {
-          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<G::tr>(o_tr, 32 * db, 32 * qhalf + 16 * t, lane), pf[t], dv[db], 0, 0, 0);
-          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<G::tr>(q_tr, 32 * db, 32 * qhalf + 16 * t, lane), sf[t], dk[db], 0, 0, 0);
-        }
-    }
-    __syncthreads();
+    };
+    if ((causal && qs0 < kv_wave0 + 31) || qs0 + 32 > seq) vector_phase(std::true_type{});
+    else vector_phase(std::false_type{});
+    STP_SB();
+
+    // ---- dV^T[d, kv] += dO^T P ; dK^T[d, kv] += Q^T dS   (k = the 32 queries, two 16-steps)
+#define STP_ACC(buf, acc, bop) do {                                                                                             \
+      _Pragma("unroll") for (int db = 0; db < D / 32; db++)                                                                      \
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, buf[db]), bop, acc[db], 0, 0, 0);         \
+      STP_SB(); } while (0)
+    STP_RD_T(fb, q_lo, q_hi, 0); lds_wait<TR_READS>(); lds_tie(fa); STP_ACC(fa, dv, pf[0]);
+    STP_RD_T(fa, o_lo, o_hi, 1); lds_wait<TR_READS>(); lds_tie(fb); STP_ACC(fb, dk, sf[0]);
+    STP_RD_T(fb, q_lo, q_hi, 1); lds_wait<TR_READS>(); lds_tie(fa); STP_ACC(fa, dv, pf[1]);
+    lds_wait<0>(); lds_tie(fb); STP_ACC(fb, dk, sf[1]);
+#undef STP_SP
+#undef STP_RD_S
+#undef STP_RD_P
+#undef STP_RD_T
+#undef STP_ACC
   }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   // ---- sum the two query halves through LDS (upper half -> lower half), write the chunk's partial
   float *red = reinterpret_cast<float *>(smem_raw);        // [4][D][64]: dk rows 0..D/2-1, dv rows D/2..D-1 per key sub-tile
   if (qhalf == 1) {
@@ -281,10 +339,9 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
                                                           float *__restrict__ part, int seq, int n, int causal, int max_chunks,
                                                           float scale) {
   using G = BG<D>;
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  bf16_t *const k_kc = reinterpret_cast<bf16_t *>(smem_raw);
-  bf16_t *const k_tr = k_kc + KVB * G::kc;
-  bf16_t *const v_kc = k_tr + KVB * G::tr;
+  constexpr int RB = G::RB;
+  constexpr int KV_TILE = KVB * RB, STAGE = 2 * KV_TILE;      // LDS: ring of two stages { K [128][D], V [128][D] }
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lg = lane >> 5;
@@ -296,11 +353,23 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
   const int nsteps = dq_steps(qb, seq, causal);
   const int s_begin = chunk * CHK, s_end = min(nsteps, s_begin + CHK);
   if (s_begin >= nsteps) return;
+  const int ns = s_end - s_begin;
 
   const int a = n * D;
   const size_t ld = 3 * (size_t)a;
-  const bf16_t *qbase = qkv + (size_t)b * seq * ld + head * D;
+  const unsigned ldq = 3u * a * 2u;
+  const bf16_t *qkv_b = qkv + (size_t)b * seq * ld;
+  const bf16_t *qbase = qkv_b + head * D;
   const bf16_t *dobase = dout + (size_t)b * seq * a + head * D;
+  const __amdgpu_buffer_rsrc_t rs_qkv =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv_b), 0, (int)min((size_t)seq * ldq, (size_t)0x7fffffff), 0x00020000);
+  auto issue_step = [&](int k) {
+    char *st = smem_raw + (k & 1) * STAGE;
+    dma_tile<D, KVB>(rs_qkv, st, (s_begin + k) * KVB, seq, ldq, (unsigned)(a + head * D) * 2u, wave, lane);
+    dma_tile<D, KVB>(rs_qkv, st + KV_TILE, (s_begin + k) * KVB, seq, ldq, (unsigned)(2 * a + head * D) * 2u, wave, lane);
+  };
+  issue_step(0);
+
   const int q_wave0 = qb * 128 + qsub * 32;
   const int qg = q_wave0 + lr;
   const int q_ld = min(qg, seq - 1);
@@ -320,54 +389,85 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
 #pragma unroll
     for (int v = 0; v < 16; v++) dq[i][v] = 0.f;
 
-  uint4 rk[KVB * D / 8 / 512], rv[KVB * D / 8 / 512];
-  tile_load<KVB, D>(rk, qbase + a, ld, s_begin * KVB, seq, tid);
-  tile_load<KVB, D>(rv, qbase + 2 * a, ld, s_begin * KVB, seq, tid);
-  for (int st = s_begin; st < s_end; st++) {
-    const int kvt = st * KVB;
-    tile_store<D, G::kc>(rk, k_kc, kvt, seq, tid);
-    tile_store<D, G::tr>(rk, k_tr, kvt, seq, tid);
-    tile_store<D, G::kc>(rv, v_kc, kvt, seq, tid);
-    __syncthreads();
-    if (st + 1 < s_end) {
-      tile_load<KVB, D>(rk, qbase + a, ld, kvt + KVB, seq, tid);
-      tile_load<KVB, D>(rv, qbase + 2 * a, ld, kvt + KVB, seq, tid);
-    }
-    const int kv0 = kvt + 64 * half;                         // this wave's 64 keys of the step
+  const unsigned lds0 = (unsigned)(size_t)(const __attribute__((address_space(3))) char *)smem_raw;
+  const unsigned kcl = kc_lane<D>(lane);
+  unsigned trl_lo, trl_hi;
+  tr_lane<D>(lane, trl_lo, trl_hi);
+
+  for (int k = 0; k < ns; k++) {
+    // every wave's loads of tile k have landed; every wave is done with tile k-1, whose stage takes tile k+1
+    STP_SB();
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    STP_SB();
+    if (k + 1 < ns) issue_step(k + 1);
+    const int kv0 = (s_begin + k) * KVB + 64 * half;          // this wave's 64 keys of the step
     const bool active = kv0 < seq && (!causal || kv0 <= q_wave0 + 31);
-    if (active) {
-      const bool need_mask = (causal && kv0 + 63 > q_wave0) || (kv0 + 64 > seq);
+    if (!active) continue;
+    const bool need_mask = (causal && kv0 + 63 > q_wave0) || (kv0 + 64 > seq);
+    const unsigned stage = lds0 + (k & 1) * STAGE + 64 * half * RB;
+    const unsigned k_kc = stage + kcl, v_kc = k_kc + KV_TILE;
+    const unsigned k_lo = stage + trl_lo, k_hi = stage + trl_hi;
+
+    u32x4_t fa[4], fb[4];
+    f32x16_t sacc, pacc;
+    bf16x8_t sf[2];
+    constexpr int TR_READS = 2 * (D / 32);
+    // four 16-byte fragments (k-steps 4*SG .. 4*SG+3) of the 32 tile rows from ROW0
+#define STP_RD4(buf, base, ROW0, SG) do { read_kc2<D, ROW0, 2 * (SG)>(buf[0], buf[1], base); read_kc2<D, ROW0, 2 * (SG) + 1>(buf[2], buf[3], base); } while (0)
+#define STP_MF4(buf, acc, bop, SG) do {                                                                                          \
+      _Pragma("unroll") for (int i = 0; i < 4; i++)                                                                               \
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, buf[i]), bop[4 * (SG) + i], acc, 0, 0, 0);     \
+      STP_SB(); } while (0)
+#define STP_RD_T(buf, R0) do {                                                                               \
+      buf[0] = read_tr<D, R0>(k_lo, k_hi, 0); buf[1] = read_tr<D, R0>(k_lo, k_hi, 1);                        \
+      if constexpr (D == 128) { buf[2] = read_tr<D, R0>(k_lo, k_hi, 2); buf[3] = read_tr<D, R0>(k_lo, k_hi, 3); } } while (0)
+#define STP_ACC(buf, bop) do {                                                                                                   \
+      _Pragma("unroll") for (int db = 0; db < D / 32; db++)                                                                      \
+        dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, buf[db]), bop, dq[db], 0, 0, 0);           \
+      STP_SB(); } while (0)
+    // accumulator v of lane l: key kv0 + 32*ks + 8*(v/4) + 4*(l/32) + v%4, query q_wave0 + l%32
+    auto vector_phase = [&](int ks, auto masked) {
+      constexpr bool MASK = decltype(masked)::value;
 #pragma unroll
-      for (int ks = 0; ks < 2; ks++) {                     // two 32-key sub-blocks
-        const int r0 = 64 * half + 32 * ks;                // first tile row of the sub-block
-        f32x16_t sacc, pacc;
-#pragma unroll
-        for (int v = 0; v < 16; v++) { sacc[v] = 0.f; pacc[v] = 0.f; }
-#pragma unroll
-        for (int s = 0; s < D / 16; s++) {
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_kc<G::kc>(k_kc, r0, 16 * s, lane), qf[s], sacc, 0, 0, 0);
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_kc<G::kc>(v_kc, r0, 16 * s, lane), of[s], pacc, 0, 0, 0);
+      for (int v = 0; v < 16; v++) {
+        float p = __builtin_amdgcn_exp2f(fmaf(sacc[v], scale_log2, -L2));
+        if constexpr (MASK) {
+          const int kv = kv0 + 32 * ks + 8 * (v >> 2) + 4 * lg + (v & 3);
+          p = ((causal && kv > qg) || kv >= seq) ? 0.f : p;
         }
-        // accumulator v of lane l: key kv0 + 32*ks + 8*(v/4) + 4*(l/32) + v%4, query q_wave0 + l%32
-        bf16x8_t sf[2];
-#pragma unroll
-        for (int v = 0; v < 16; v++) {
-          float p = __builtin_amdgcn_exp2f(sacc[v] * scale_log2 - L2);
-          if (need_mask) {
-            const int kv = kv0 + 32 * ks + 8 * (v >> 2) + 4 * lg + (v & 3);
-            if ((causal && kv > qg) || kv >= seq) p = 0.f;
-          }
-          sf[v >> 3][v & 7] = (bf16_t)(p * (pacc[v] - Dl));
-        }
-#pragma unroll
-        for (int t = 0; t < 2; t++)
-#pragma unroll
-          for (int db = 0; db < D / 32; db++)
-            dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<G::tr>(k_tr, 32 * db, r0 + 16 * t, lane), sf[t], dq[db], 0, 0, 0);
+        sf[v >> 3][v & 7] = (bf16_t)(p * (pacc[v] - Dl));
       }
-    }
-    __syncthreads();
+    };
+    // one 32-key sub-block: S^T = K Q^T, dP^T = V dO^T, dS^T, dQ^T += K^T dS^T.  On entry fa holds (or is receiving)
+    // the first four K fragments; NEXT names what to prefetch behind the last MFMA group.
+#define STP_SUBBLOCK(KS, NEXT)                                                                                                    \
+    do {                                                                                                                          \
+      _Pragma("unroll") for (int v = 0; v < 16; v++) { sacc[v] = 0.f; pacc[v] = 0.f; }                                            \
+      if constexpr (D == 128) {                                                                                                   \
+        STP_RD4(fb, k_kc, 32 * KS, 1); lds_wait<4>(); lds_tie(fa); STP_MF4(fa, sacc, qf, 0);                                      \
+        STP_RD4(fa, v_kc, 32 * KS, 0); lds_wait<4>(); lds_tie(fb); STP_MF4(fb, sacc, qf, 1);                                      \
+        STP_RD4(fb, v_kc, 32 * KS, 1); lds_wait<4>(); lds_tie(fa); STP_MF4(fa, pacc, of, 0);                                      \
+        STP_RD_T(fa, 32 * KS); lds_wait<TR_READS>(); lds_tie(fb); STP_MF4(fb, pacc, of, 1);                                       \
+      } else {                                                                                                                    \
+        STP_RD4(fb, v_kc, 32 * KS, 0); lds_wait<4>(); lds_tie(fa); STP_MF4(fa, sacc, qf, 0);                                      \
+        STP_RD_T(fa, 32 * KS); lds_wait<TR_READS>(); lds_tie(fb); STP_MF4(fb, pacc, of, 0);                                       \
+      }                                                                                                                           \
+      if (need_mask) vector_phase(KS, std::true_type{}); else vector_phase(KS, std::false_type{});                                \
+      STP_SB();                                                                                                                   \
+      STP_RD_T(fb, 32 * KS + 16); lds_wait<TR_READS>(); lds_tie(fa); STP_ACC(fa, sf[0]);                                          \
+      NEXT;                                                                                                                       \
+      STP_ACC(fb, sf[1]);                                                                                                         \
+    } while (0)
+    STP_RD4(fa, k_kc, 0, 0);
+    STP_SUBBLOCK(0, STP_RD4(fa, k_kc, 32, 0); lds_wait<4>(); lds_tie(fb));
+    STP_SUBBLOCK(1, lds_wait<0>(); lds_tie(fb));
+#undef STP_RD4
+#undef STP_MF4
+#undef STP_RD_T
+#undef STP_ACC
+#undef STP_SUBBLOCK
   }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   float *red = reinterpret_cast<float *>(smem_raw);        // [4][D/2][64]
   if (half == 1) {
 #pragma unroll
@@ -428,10 +528,12 @@ template <int D>
 int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const float *lse, const void *dout, const float *delta,
                void *dqkv, float *ws, size_t ws_bytes, hipStream_t s) {
   using G = BG<D>;
-  constexpr size_t smem_kv = (size_t)(2 * KVB * G::kc + 2 * QSTEP * (G::kc + G::tr)) * sizeof(bf16_t) + 2 * QSTEP * sizeof(float);
-  constexpr size_t smem_q = (size_t)KVB * (2 * G::kc + G::tr) * sizeof(bf16_t);
+  constexpr size_t smem_kv = (size_t)(2 * KVB + 4 * QSTEP) * G::RB + 2 * 512;   // K, V, ring of {Q, dO}, ring of {lse, delta}
+  constexpr size_t smem_q = (size_t)4 * KVB * G::RB;                              // ring of {K, V}
   static_assert(smem_kv <= 160 * 1024 && smem_kv >= (size_t)4 * D * 64 * sizeof(float), "dkv LDS budget");
   static_assert(smem_q <= 160 * 1024 && smem_q >= (size_t)4 * (D / 2) * 64 * sizeof(float), "dq LDS budget");
+  if ((size_t)d->seq * 3 * d->heads_local * D * sizeof(bf16_t) > (size_t)0x7fffffff)
+    return stp_fail(ctx, STP_ESHAPE, "attention backward: one sequence of QKV must span less than 2 GiB%s");
   auto kkv = attn_bwd_dkv_kernel<D>;
   auto kq = attn_bwd_dq_kernel<D>;
   static bool attr_set = false;
