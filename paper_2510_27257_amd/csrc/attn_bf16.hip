@@ -2,7 +2,7 @@
 // the attention core of one TP rank, no communication).
 //
 // Work decomposition.  A workgroup owns 128 query rows of one (sequence, head) and ONE CHUNK of up
-// to CH2 * 128 keys; chunks of the same query block are merged afterwards by a small combine kernel
+// to `chunk_steps` * 128 keys (chosen per launch); chunks of the same query block are merged afterwards by a small combine kernel
 // (fixed order, deterministic).  Cutting the key range into chunks turns the causal triangle into
 // pieces of similar size instead of workgroups whose length varies 1..seq/128.
 // Inside a workgroup 8 waves run as 4 query sub-tiles (32 rows) x 2 key halves: per 128-key step
@@ -33,12 +33,13 @@
 #include "common.h"
 #include "lds_dma.h"
 #include <type_traits>
+#include <vector>
+#include <algorithm>
 
 namespace {
 
 constexpr int QB = 128;    // query rows per workgroup
 constexpr int KSTEP = 128; // keys per step (64 per wave half)
-constexpr int CH2 = 16;     // steps per chunk (2048 keys)
 constexpr float LN2 = 0.69314718055994531f;
 
 template <int D> struct AttnGeom {
@@ -93,7 +94,7 @@ __device__ __forceinline__ void mfma_pv(f32x16_t (&o)[D / 32], const u32x4_t (&b
 
 template <int D>
 __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__restrict__ qkv, float *__restrict__ part, int seq,
-                                                            int n, int causal, int max_chunks, float scale_log2) {
+                                                            int n, int causal, int max_chunks, int chunk_steps, float scale_log2) {
   using G = AttnGeom<D>;
   static_assert(D == 64 || D == 128, "head dimension");
   constexpr int RB = G::RB, CPR = G::CPR, RPB = G::RPB, RPI = G::RPI, NLD = G::NLD, TILE = G::TILE;
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
   const int chunk = blockIdx.y;
   const int head = blockIdx.z % n, b = blockIdx.z / n;
   const int nsteps = attn_steps(qb, seq, causal);
-  const int s_begin = chunk * CH2, s_end = min(nsteps, s_begin + CH2);
+  const int s_begin = chunk * chunk_steps, s_end = min(nsteps, s_begin + chunk_steps);
   if (s_begin >= nsteps) return;
   const int ns = s_end - s_begin;
 
@@ -385,14 +386,14 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
 template <int D>
 __global__ __launch_bounds__(256) void attn_fwd_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ out,
                                                                float *__restrict__ lse, int seq, int n, int mbsz, int causal,
-                                                               int max_chunks) {
+                                                               int max_chunks, int chunk_steps) {
   using G = AttnGeom<D>;
   const int lane = threadIdx.x & 63;
   const size_t w = blockIdx.x * (size_t)4 + (threadIdx.x >> 6);
   if (w >= (size_t)mbsz * n * seq) return;
   const int q = w % seq, head = (w / seq) % n, b = w / ((size_t)seq * n);
   const int nqb = (seq + QB - 1) / QB, qb = q / QB, qloc = q % QB;
-  const int nch = (attn_steps(qb, seq, causal) + CH2 - 1) / CH2;
+  const int nch = (attn_steps(qb, seq, causal) + chunk_steps - 1) / chunk_steps;
   const float *p0 = part + ((((size_t)b * n + head) * nqb + qb) * max_chunks) * G::piece_floats;
   float M = -INFINITY;
   for (int c = 0; c < nch; c++) M = fmaxf(M, p0[(size_t)c * G::piece_floats + QB * D + qloc]);
@@ -421,6 +422,14 @@ __global__ __launch_bounds__(256) void attn_fwd_combine_kernel(const float *__re
   if (lane == 0) lse[((size_t)b * n + head) * seq + q] = (M + log2f(L)) * LN2;
 }
 
+// steps per chunk for this shape: grid x runs over the query blocks, last block first
+inline int fwd_chunk_steps(const stp_layer_desc *d) {
+  const int nqb = (d->seq + QB - 1) / QB;
+  std::vector<int> steps(nqb);
+  for (int x = 0; x < nqb; x++) steps[x] = attn_steps(nqb - 1 - x, d->seq, d->causal);
+  return stp_pick_chunk(0, nqb, steps.data());
+}
+
 template <int D>
 int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out, float *lse, float *ws, size_t ws_bytes,
                hipStream_t s) {
@@ -437,17 +446,18 @@ int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out
   if ((size_t)d->seq * 3 * d->heads_local * D * sizeof(bf16_t) > (size_t)0x7fffffff)
     return stp_fail(ctx, STP_ESHAPE, "attention forward: one sequence of QKV must span less than 2 GiB%s");
   const int nqb = (d->seq + QB - 1) / QB;
-  const int max_chunks = (attn_steps(nqb - 1, d->seq, d->causal) + CH2 - 1) / CH2;
+  const int chunk_steps = fwd_chunk_steps(d);
+  const int max_chunks = (attn_steps(nqb - 1, d->seq, d->causal) + chunk_steps - 1) / chunk_steps;
   const size_t need = (size_t)d->mbsz * d->heads_local * nqb * max_chunks * G::piece_floats * sizeof(float);
   if (!ws || ws_bytes < need)
     return stp_fail(ctx, STP_ENOSPACE, "attention forward: workspace lane too small%s (need %ld bytes)", "", (long)need);
   dim3 grid(nqb, max_chunks, d->heads_local * d->mbsz), block(512);
   float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
-  hipLaunchKernelGGL(kern, grid, block, smem, s, (const bf16_t *)qkv, ws, d->seq, d->heads_local, d->causal, max_chunks, scale_log2);
+  hipLaunchKernelGGL(kern, grid, block, smem, s, (const bf16_t *)qkv, ws, d->seq, d->heads_local, d->causal, max_chunks, chunk_steps, scale_log2);
   STP_LAUNCH_CHECK(ctx);
   size_t waves = (size_t)d->mbsz * d->heads_local * d->seq;
   hipLaunchKernelGGL(attn_fwd_combine_kernel<D>, dim3((waves + 3) / 4), dim3(256), 0, s, ws, (bf16_t *)out, lse, d->seq,
-                     d->heads_local, d->mbsz, d->causal, max_chunks);
+                     d->heads_local, d->mbsz, d->causal, max_chunks, chunk_steps);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }
@@ -456,7 +466,8 @@ int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out
 
 size_t stp_attn_fwd_ws_bytes(const stp_layer_desc *d) {
   const int nqb = (d->seq + QB - 1) / QB;
-  const int max_chunks = (attn_steps(nqb - 1, d->seq, d->causal) + CH2 - 1) / CH2;
+  const int chunk_steps = fwd_chunk_steps(d);
+  const int max_chunks = (attn_steps(nqb - 1, d->seq, d->causal) + chunk_steps - 1) / chunk_steps;
   return (size_t)d->mbsz * d->heads_local * nqb * max_chunks * (QB * d->head_dim + 2 * QB) * sizeof(float);
 }
 
@@ -465,4 +476,18 @@ int stp_launch_attn_fwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *
   if (d->head_dim == 128) return launch_fwd<128>(ctx, d, qkv, out, lse, ws, ws_bytes, s);
   if (d->head_dim == 64) return launch_fwd<64>(ctx, d, qkv, out, lse, ws, ws_bytes, s);
   return stp_fail(ctx, STP_ESHAPE, "bf16 attention needs head_dim 64 or 128%s");
+}
+
+int stp_pick_chunk(int kind, int nblocks, const int *steps) {
+  // Measured on gpt7b_tp8-like shapes (4 heads x 128, seq 4096 and 6144, causal): 16 steps of 128 keys for the
+  // forward and dq kernels and 32 steps of 64 queries for dkv beat both shorter chunks (more partial pieces,
+  // more workgroup prologues and epilogues) and longer ones (too few workgroups for 256 compute units).  A
+  // list-scheduling model of the dispatch did not reproduce that ordering, so the lengths are constants; they
+  // are only capped so that a block is never cut into more than 8 pieces (bounds the workspace).
+  static const int dflt[3] = {16, 32, 16};
+  int max_steps = 1;
+  for (int x = 0; x < nblocks; x++) max_steps = std::max(max_steps, steps[x]);
+  int c = std::min(dflt[kind], max_steps);
+  while ((max_steps + c - 1) / c > 8) c *= 2;
+  return c;
 }

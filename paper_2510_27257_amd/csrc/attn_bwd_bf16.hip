@@ -5,11 +5,11 @@
 //     P = exp(S - L),  S = Q K^T / sqrt(d)  (causal: key > query masked)
 //     dV = P^T dO,  dP = dO V^T,  dS = P o (dP - delta),  dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d)
 // Two kernels, both deterministic (no atomics):
-//   * dkv: a workgroup owns 128 keys and one CHUNK of up to 1024 queries; 8 waves = 4 key sub-tiles
+//   * dkv: a workgroup owns 128 keys and one CHUNK of up to 32 steps of 64 queries; 8 waves = 4 key sub-tiles
 //     (32 keys) x 2 halves of each 64-query step.  S and dP are formed with the keys as MFMA columns,
 //     so the accumulator layout of P / dS is already the B-operand layout of dV^T += dO^T P and
 //     dK^T += Q^T dS.  dO^T / Q^T fragments come from the [q][d] tiles through the transposing LDS read.
-//   * dq: a workgroup owns 128 queries and one chunk of up to 1024 keys; 8 waves = 4 query sub-tiles
+//   * dq: a workgroup owns 128 queries and one chunk of up to 16 steps of 128 keys; 8 waves = 4 query sub-tiles
 //     x 2 halves of each 128-key step, with the transposed tiles S^T = K Q^T, dP^T = V dO^T (queries
 //     as MFMA columns: L and delta are per-lane scalars) and dQ^T += K^T dS^T.
 // In both, the two wave halves are summed through LDS, every chunk writes an fp32 partial, and a
@@ -26,6 +26,7 @@
 #include "common.h"
 #include "lds_dma.h"
 #include <type_traits>
+#include <vector>
 
 int stp_launch_rowdot(stp_ctx *ctx, const stp_layer_desc *d, const void *a, const void *b, float *delta, hipStream_t s);
 
@@ -34,8 +35,6 @@ namespace {
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr int KVB = 128;    // keys per dkv workgroup / per dq step
 constexpr int QSTEP = 64;   // queries per dkv step
-constexpr int CHQ = 16;     // dkv: steps per chunk (1024 queries)
-constexpr int CHK = 8;      // dq: 128-key steps per chunk (1024 keys)
 
 template <int D> struct BG {
   static constexpr int RB = D * 2;        // bytes per tile row
@@ -114,7 +113,7 @@ template <int D>
 __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                                            const float *__restrict__ lse, const float *__restrict__ delta,
                                                            float *__restrict__ part, int seq, int n, int causal,
-                                                           int max_chunks, float scale) {
+                                                           int max_chunks, int chunk_steps, float scale) {
   using G = BG<D>;
   constexpr int RB = G::RB;
   constexpr int KV_TILE = KVB * RB, Q_TILE = QSTEP * RB, STAGE = 2 * Q_TILE;
@@ -127,7 +126,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
   const int kvb = blockIdx.x, chunk = blockIdx.y;      // key block 0 owns the most chunks and is scheduled first
   const int head = blockIdx.z % n, b = blockIdx.z / n;
   const int nq = (seq + QSTEP - 1) / QSTEP;
-  const int s_begin = dkv_first_step(kvb, causal) + chunk * CHQ, s_end = min(nq, s_begin + CHQ);
+  const int s_begin = dkv_first_step(kvb, causal) + chunk * chunk_steps, s_end = min(nq, s_begin + chunk_steps);
   if (s_begin >= nq) return;
   const int ns = s_end - s_begin;
 
@@ -303,7 +302,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ dqkv,
                                                                    int seq, int n, int mbsz, int causal, int max_chunks,
-                                                                   float scale) {
+                                                                   int chunk_steps, float scale) {
   const size_t idx = blockIdx.x * (size_t)256 + threadIdx.x;
   constexpr int CPR = D / 8;
   if (idx >= (size_t)mbsz * n * seq * CPR) return;
@@ -312,7 +311,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_combine_kernel(const float *
   const int kv = row % seq, head = (row / seq) % n, b = row / ((size_t)seq * n);
   const int kvb = kv / KVB, kloc = kv % KVB;
   const int nkvb = (seq + KVB - 1) / KVB, nq = (seq + QSTEP - 1) / QSTEP;
-  const int nch = (nq - dkv_first_step(kvb, causal) + CHQ - 1) / CHQ;
+  const int nch = (nq - dkv_first_step(kvb, causal) + chunk_steps - 1) / chunk_steps;
   const float *p0 = part + ((((size_t)b * n + head) * nkvb + kvb) * max_chunks) * (size_t)(2 * KVB * D) + (size_t)kloc * D + c8;
   float sk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sv[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int c = 0; c < nch; c++) {
@@ -337,7 +336,7 @@ template <int D>
 __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                                           const float *__restrict__ lse, const float *__restrict__ delta,
                                                           float *__restrict__ part, int seq, int n, int causal, int max_chunks,
-                                                          float scale) {
+                                                          int chunk_steps, float scale) {
   using G = BG<D>;
   constexpr int RB = G::RB;
   constexpr int KV_TILE = KVB * RB, STAGE = 2 * KV_TILE;      // LDS: ring of two stages { K [128][D], V [128][D] }
@@ -351,7 +350,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
   const int chunk = blockIdx.y;
   const int head = blockIdx.z % n, b = blockIdx.z / n;
   const int nsteps = dq_steps(qb, seq, causal);
-  const int s_begin = chunk * CHK, s_end = min(nsteps, s_begin + CHK);
+  const int s_begin = chunk * chunk_steps, s_end = min(nsteps, s_begin + chunk_steps);
   if (s_begin >= nsteps) return;
   const int ns = s_end - s_begin;
 
@@ -497,7 +496,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dq_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ dqkv,
                                                                   int seq, int n, int mbsz, int causal, int max_chunks,
-                                                                  float scale) {
+                                                                  int chunk_steps, float scale) {
   const size_t idx = blockIdx.x * (size_t)256 + threadIdx.x;
   constexpr int CPR = D / 8;
   if (idx >= (size_t)mbsz * n * seq * CPR) return;
@@ -506,7 +505,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_combine_kernel(const float *_
   const int q = row % seq, head = (row / seq) % n, b = row / ((size_t)seq * n);
   const int qb = q / 128, qloc = q % 128;
   const int nqblk = (seq + 127) / 128;
-  const int nch = (dq_steps(qb, seq, causal) + CHK - 1) / CHK;
+  const int nch = (dq_steps(qb, seq, causal) + chunk_steps - 1) / chunk_steps;
   const float *p0 = part + ((((size_t)b * n + head) * nqblk + qb) * max_chunks) * (size_t)(128 * D) + (size_t)qloc * D + c8;
   float sq[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int c = 0; c < nch; c++) {
@@ -521,8 +520,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_combine_kernel(const float *_
   Vec8<bf16_t>::store(dqkv + ((size_t)b * seq + q) * (3 * (size_t)a) + head * D + c8, sq);
 }
 
-inline int dkv_max_chunks(int seq) { return ((seq + QSTEP - 1) / QSTEP + CHQ - 1) / CHQ; }
-inline int dq_max_chunks(int seq, int causal) { return (dq_steps((seq + 127) / 128 - 1, seq, causal) + CHK - 1) / CHK; }
+// steps per chunk for this shape (grid x: key blocks in order for dkv; query blocks, last first, for dq)
+inline int dkv_chunk_steps(const stp_layer_desc *d) {
+  const int nkvb = (d->seq + KVB - 1) / KVB, nq = (d->seq + QSTEP - 1) / QSTEP;
+  std::vector<int> steps(nkvb);
+  for (int x = 0; x < nkvb; x++) steps[x] = nq - dkv_first_step(x, d->causal);
+  return stp_pick_chunk(1, nkvb, steps.data());
+}
+inline int dq_chunk_steps(const stp_layer_desc *d) {
+  const int nqb = (d->seq + 127) / 128;
+  std::vector<int> steps(nqb);
+  for (int x = 0; x < nqb; x++) steps[x] = dq_steps(nqb - 1 - x, d->seq, d->causal);
+  return stp_pick_chunk(2, nqb, steps.data());
+}
+inline int dkv_max_chunks(int seq, int chunk_steps) { return ((seq + QSTEP - 1) / QSTEP + chunk_steps - 1) / chunk_steps; }
+inline int dq_max_chunks(int seq, int causal, int chunk_steps) {
+  return (dq_steps((seq + 127) / 128 - 1, seq, causal) + chunk_steps - 1) / chunk_steps;
+}
 
 template <int D>
 int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const float *lse, const void *dout, const float *delta,
@@ -544,7 +558,8 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
   }
   const float scale = 1.0f / sqrtf((float)D);
   const int nkvb = (d->seq + KVB - 1) / KVB, nqb = (d->seq + 127) / 128;
-  const int mc_kv = dkv_max_chunks(d->seq), mc_q = dq_max_chunks(d->seq, d->causal);
+  const int ch_kv = dkv_chunk_steps(d), ch_q = dq_chunk_steps(d);
+  const int mc_kv = dkv_max_chunks(d->seq, ch_kv), mc_q = dq_max_chunks(d->seq, d->causal, ch_q);
   const size_t bh = (size_t)d->mbsz * d->heads_local;
   const size_t need_kv = bh * nkvb * mc_kv * 2 * KVB * D * sizeof(float), need_q = bh * nqb * mc_q * 128 * D * sizeof(float);
   const size_t need = need_kv > need_q ? need_kv : need_q;
@@ -552,16 +567,16 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
     return stp_fail(ctx, STP_ENOSPACE, "attention backward: workspace lane too small%s (need %ld bytes)", "", (long)need);
   const size_t rows8 = bh * d->seq * (D / 8);
   hipLaunchKernelGGL(kkv, dim3(nkvb, mc_kv, (unsigned)bh), dim3(512), smem_kv, s, (const bf16_t *)qkv, (const bf16_t *)dout, lse,
-                     delta, ws, d->seq, d->heads_local, d->causal, mc_kv, scale);
+                     delta, ws, d->seq, d->heads_local, d->causal, mc_kv, ch_kv, scale);
   STP_LAUNCH_CHECK(ctx);
   hipLaunchKernelGGL(attn_bwd_dkv_combine_kernel<D>, dim3((rows8 + 255) / 256), dim3(256), 0, s, ws, (bf16_t *)dqkv, d->seq,
-                     d->heads_local, d->mbsz, d->causal, mc_kv, scale);
+                     d->heads_local, d->mbsz, d->causal, mc_kv, ch_kv, scale);
   STP_LAUNCH_CHECK(ctx);
   hipLaunchKernelGGL(kq, dim3(nqb, mc_q, (unsigned)bh), dim3(512), smem_q, s, (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta,
-                     ws, d->seq, d->heads_local, d->causal, mc_q, scale);
+                     ws, d->seq, d->heads_local, d->causal, mc_q, ch_q, scale);
   STP_LAUNCH_CHECK(ctx);
   hipLaunchKernelGGL(attn_bwd_dq_combine_kernel<D>, dim3((rows8 + 255) / 256), dim3(256), 0, s, ws, (bf16_t *)dqkv, d->seq,
-                     d->heads_local, d->mbsz, d->causal, mc_q, scale);
+                     d->heads_local, d->mbsz, d->causal, mc_q, ch_q, scale);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }
@@ -571,8 +586,8 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
 size_t stp_attn_bwd_ws_bytes(const stp_layer_desc *d) {
   const int nkvb = (d->seq + KVB - 1) / KVB, nqb = (d->seq + 127) / 128;
   const size_t bh = (size_t)d->mbsz * d->heads_local;
-  const size_t need_kv = bh * nkvb * dkv_max_chunks(d->seq) * 2 * KVB * d->head_dim * sizeof(float);
-  const size_t need_q = bh * nqb * dq_max_chunks(d->seq, d->causal) * 128 * d->head_dim * sizeof(float);
+  const size_t need_kv = bh * nkvb * dkv_max_chunks(d->seq, dkv_chunk_steps(d)) * 2 * KVB * d->head_dim * sizeof(float);
+  const size_t need_q = bh * nqb * dq_max_chunks(d->seq, d->causal, dq_chunk_steps(d)) * 128 * d->head_dim * sizeof(float);
   return need_kv > need_q ? need_kv : need_q;
 }
 

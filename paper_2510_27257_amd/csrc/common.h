@@ -124,6 +124,10 @@ int stp_launch_attn_fwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *
                              size_t ws_bytes, hipStream_t s);
 int stp_launch_attn_bwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const void *out, const float *lse,
                              const void *dout, float *delta, void *dqkv, float *ws, size_t ws_bytes, hipStream_t s);
+// Steps per chunk for the attention kernels, whose workgroups own one chunk of a block's step range (grid =
+// blocks x chunks x heads).  kind: 0 forward, 1 dkv, 2 dq; steps[x] is the number of steps of block x.
+int stp_pick_chunk(int kind, int nblocks, const int *steps);
+
 size_t stp_attn_fwd_ws_bytes(const stp_layer_desc *d);   // workspace the bf16 attention kernels need (chunk partials)
 size_t stp_attn_bwd_ws_bytes(const stp_layer_desc *d);
 int stp_launch_attn_fwd_generic(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out, float *lse, hipStream_t s);

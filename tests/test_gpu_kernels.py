@@ -17,7 +17,7 @@ from harness import to_dev, to_host, rel_err, TOL
 @pytest.fixture(scope="module")
 def ctx():
     c = stp.Context(0)
-    c.set_workspace(torch.empty(64 << 20, dtype=torch.uint8, device="cuda"))
+    c.set_workspace(torch.empty(256 << 20, dtype=torch.uint8, device="cuda"))
     yield c
     torch.cuda.synchronize()
     c.close()
