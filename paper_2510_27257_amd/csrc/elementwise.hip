@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, 
   for (int row = blockIdx.x; row < rows; row += gridDim.x, it++) {
     const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
     const size_t off = (size_t)row * h;
-    float xh[NCH][8], g[NCH][8];
+    float xh[NCH][8], g[NCH][8], rs[NCH][8];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; c++) {
@@ -101,6 +101,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, 
         float xv[8], dv[8];
         Vec8<T>::load(x + off + col, xv);
         Vec8<T>::load(dy + off + col, dv);
+        if (dres) Vec8<T>::load(dres + off + col, rs[c]);   // in flight with the other two, used after the row reduction
 #pragma unroll
         for (int i = 0; i < 8; i++) {
           xh[c][i] = (xv[i] - mean) * rstd;
@@ -124,12 +125,11 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, 
     for (int c = 0; c < NCH; c++) {
       int col = (c * 256 + tid) * 8;
       if (col < h) {
-        float o[8], r[8];
-        if (dres) Vec8<T>::load(dres + off + col, r);
+        float o[8];
 #pragma unroll
         for (int i = 0; i < 8; i++) {
           o[i] = rstd * (g[c][i] - c1 - xh[c][i] * c2);
-          if (dres) o[i] += r[i];
+          if (dres) o[i] += rs[c][i];
         }
         Vec8<T>::store(dx + off + col, o);
       }
@@ -151,9 +151,12 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, 
 // out[c] += scale * sum_{p < nparts} partial[p*stride + c], in a fixed order: a 256-thread group owns
 // 64 columns; thread (c, g) adds up rows g, g+4, g+8, ... (8 independent loads in flight), then the
 // four row-group sums are combined 0+1+2+3 through LDS.
+// Columns n_first .. n-1 go to out2 (its column 0 is column n_first): the gain and bias gradients of a norm,
+// whose partials lie side by side, are reduced by one launch.
 __global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__restrict__ partial, int nparts,
                                                             size_t stride, int n, float scale,
-                                                            float *__restrict__ out) {
+                                                            float *__restrict__ out, int n_first = 0x7fffffff,
+                                                            float *__restrict__ out2 = nullptr) {
   __shared__ float red[4][64];
   const int cl = threadIdx.x & 63, g = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl;
@@ -171,7 +174,10 @@ __global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__rest
   }
   red[g][cl] = s;
   __syncthreads();
-  if (g == 0 && c < n) out[c] += scale * (((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl]);
+  if (g == 0 && c < n) {
+    float *dst = c < n_first ? out + c : out2 + (c - n_first);
+    *dst += scale * (((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl]);
+  }
 }
 
 // ======================================================================
@@ -434,12 +440,18 @@ extern "C" int stp_norm_backward(stp_ctx *ctx, int dtype, int norm, int32_t T, i
   int rc = dtype == STP_BF16 ? norm_bwd_dispatch<bf16_t>(ctx, norm, T, h, x, gamma, stats, dy, d_resid, dx, partial, groups, s)
                              : norm_bwd_dispatch<float>(ctx, norm, T, h, x, gamma, stats, dy, d_resid, dx, partial, groups, s);
   if (rc != STP_OK) return rc;
-  if (dgamma) {
-    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 63) / 64), dim3(256), 0, s, partial, groups, (size_t)2 * h, h, 1.0f, dgamma);
+  const bool want_beta = dbeta && norm == STP_NORM_LN;
+  if (dgamma && want_beta) {   // the partials of a row group lie side by side: [gain | bias]
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3((2 * h + 63) / 64), dim3(256), 0, s, partial, groups, (size_t)2 * h, 2 * h, 1.0f,
+                       dgamma, h, dbeta);
     STP_LAUNCH_CHECK(ctx);
-  }
-  if (dbeta && norm == STP_NORM_LN) {
-    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 63) / 64), dim3(256), 0, s, partial + h, groups, (size_t)2 * h, h, 1.0f, dbeta);
+  } else if (dgamma) {
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 63) / 64), dim3(256), 0, s, partial, groups, (size_t)2 * h, h, 1.0f, dgamma,
+                       0x7fffffff, nullptr);
+    STP_LAUNCH_CHECK(ctx);
+  } else if (want_beta) {
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 63) / 64), dim3(256), 0, s, partial + h, groups, (size_t)2 * h, h, 1.0f, dbeta,
+                       0x7fffffff, nullptr);
     STP_LAUNCH_CHECK(ctx);
   }
   return STP_OK;
@@ -465,7 +477,8 @@ extern "C" int stp_colsum(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const v
   if (dtype == STP_BF16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)x, T, N, partial);
   else hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float *)x, T, N, partial);
   STP_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(partial_reduce_kernel, dim3((N + 63) / 64), dim3(256), 0, s, partial, slabs, (size_t)N, N, scale, out);
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3((N + 63) / 64), dim3(256), 0, s, partial, slabs, (size_t)N, N, scale, out, 0x7fffffff,
+                     nullptr);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }
