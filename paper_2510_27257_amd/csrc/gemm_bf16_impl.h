@@ -133,6 +133,10 @@ __device__ __forceinline__ void map_tile(int tiles_m, int tiles_n, int &tm, int 
 // Each wave stages one 32 x WN strip at a time in its own LDS area (fp32, pitch WN + 8 keeps the two
 // lane halves on different banks) and reads it back row-wise, 8 consecutive columns per lane, so
 // that every global access of the epilogue (C, C2, residual, aux, bias) is a 16- or 32-byte vector.
+// The staging area is private to the wave (LDS operations of a wave complete in order), so no barrier
+// is needed.  What the epilogue reads from global memory (residual, aux, the fp32 accumulator) is
+// fetched one strip ahead, all passes of a strip at once, so that its latency is paid once per tile
+// and not once per pass.  Rows / columns past M / N are read from a clamped address and never stored.
 // The caller guarantees that the operand stages in LDS are dead (barrier after the last K-tile).
 template <int MI, int NI, int WN, int EPI>
 __device__ __forceinline__ void store_tile(f32x16_t (&acc)[MI][NI], float *stage, int row_base, int col_base, int M, int N,
@@ -142,50 +146,80 @@ __device__ __forceinline__ void store_tile(f32x16_t (&acc)[MI][NI], float *stage
   const bool has_bias = ep.bias != nullptr, has_resid = ep.resid != nullptr;
   constexpr int LPR = WN / 8;             // lanes per staged row
   constexpr int PASSES = 32 * LPR / 64;
+  constexpr bool ACC = EPI == EPI_F32_ACCUM, AUX = EPI == EPI_GELU_BWD;
+  // pass p of a strip: staged row r_p, columns c_p .. c_p+7 (the same for every strip)
+  int pr[PASSES], pc[PASSES];
+  float bias[PASSES][8];
 #pragma unroll
-  for (int i = 0; i < MI; i++) {
+  for (int p = 0; p < PASSES; p++) {
+    const int idx = p * 64 + lane;
+    pr[p] = idx / LPR;
+    pc[p] = col_base + (idx % LPR) * 8;
+#pragma unroll
+    for (int e = 0; e < 8; e++) bias[p][e] = 0.f;
+    if (has_bias) {
+      Vec8<bf16_t>::load(ep.bias + min(pc[p], N - 8), bias[p]);
+#pragma unroll
+      for (int e = 0; e < 8; e++) bias[p][e] *= ep.bias_scale;
+    }
+  }
+  // what strip i needs from global memory
+  struct Pre { uint4 lo[PASSES], hi[PASSES]; };   // resid / aux: lo (8 bf16); fp32 accumulator: lo, hi (8 floats)
+  auto fetch = [&](int i, Pre &f) {
+#pragma unroll
+    for (int p = 0; p < PASSES; p++) {
+      const size_t row = (size_t)min(row_base + i * 32 + pr[p], M - 1);
+      const int col = min(pc[p], N - 8);
+      if (ACC) {
+        const uint4 *cp = reinterpret_cast<const uint4 *>(reinterpret_cast<const float *>(ep.C) + row * ep.ldc + col);
+        const uint4 a = cp[0], b = cp[1];
+        f.lo[p].x = a.x; f.lo[p].y = a.y; f.lo[p].z = a.z; f.lo[p].w = a.w;
+        f.hi[p].x = b.x; f.hi[p].y = b.y; f.hi[p].z = b.z; f.hi[p].w = b.w;
+      } else if (AUX) {
+        const uint4 a = *reinterpret_cast<const uint4 *>(ep.aux + row * ep.ld2 + col);
+        f.lo[p].x = a.x; f.lo[p].y = a.y; f.lo[p].z = a.z; f.lo[p].w = a.w;
+      } else if (has_resid) {
+        const uint4 a = *reinterpret_cast<const uint4 *>(ep.resid + row * ep.ldr + col);
+        f.lo[p].x = a.x; f.lo[p].y = a.y; f.lo[p].z = a.z; f.lo[p].w = a.w;
+      }
+    }
+  };
+  auto strip = [&](int i, const Pre &f) {
 #pragma unroll
     for (int j = 0; j < NI; j++)
 #pragma unroll
       for (int v = 0; v < 16; v++) stage[(8 * (v >> 2) + 4 * lg + (v & 3)) * SP + 32 * j + lr] = acc[i][j][v];
-    __syncthreads();
-#pragma unroll 1
+#pragma unroll
     for (int p = 0; p < PASSES; p++) {
-      const int idx = p * 64 + lane;
-      const int r = idx / LPR, c = (idx % LPR) * 8;
-      const int row = row_base + i * 32 + r, col = col_base + c;
-      if (row < M && col < N) {
-        float val[8];
-        Vec8<float>::load(stage + r * SP + c, val);
-        if (has_bias) {
-          float b[8];
-          Vec8<bf16_t>::load(ep.bias + col, b);
+      const int row = row_base + i * 32 + pr[p], col = pc[p];
+      float val[8];
+      Vec8<float>::load(stage + pr[p] * SP + (col - col_base), val);
 #pragma unroll
-          for (int e = 0; e < 8; e++) val[e] += b[e] * ep.bias_scale;
-        }
-        if (has_resid) {
-          float rr[8];
-          Vec8<bf16_t>::load(ep.resid + (size_t)row * ep.ldr + col, rr);
+      for (int e = 0; e < 8; e++) val[e] += bias[p][e];
+      if (ACC) {
+        float old[8];
+        old[0] = __builtin_bit_cast(float, f.lo[p].x); old[1] = __builtin_bit_cast(float, f.lo[p].y);
+        old[2] = __builtin_bit_cast(float, f.lo[p].z); old[3] = __builtin_bit_cast(float, f.lo[p].w);
+        old[4] = __builtin_bit_cast(float, f.hi[p].x); old[5] = __builtin_bit_cast(float, f.hi[p].y);
+        old[6] = __builtin_bit_cast(float, f.hi[p].z); old[7] = __builtin_bit_cast(float, f.hi[p].w);
 #pragma unroll
-          for (int e = 0; e < 8; e++) val[e] += rr[e] * ep.resid_scale;
-        }
-        if (EPI == EPI_F32_ACCUM) {
-          float *cp = reinterpret_cast<float *>(ep.C) + (size_t)row * ep.ldc + col;
-          float old[8];
-          Vec8<float>::load(cp, old);
+        for (int e = 0; e < 8; e++) old[e] += val[e];
+        if (row < M && col < N) Vec8<float>::store(reinterpret_cast<float *>(ep.C) + (size_t)row * ep.ldc + col, old);
+      } else {
+        if (AUX || has_resid) {
+          uint4 raw;
+          raw.x = f.lo[p].x; raw.y = f.lo[p].y; raw.z = f.lo[p].z; raw.w = f.lo[p].w;
+          const bf16x8_t h8 = __builtin_bit_cast(bf16x8_t, raw);
 #pragma unroll
-          for (int e = 0; e < 8; e++) old[e] += val[e];
-          Vec8<float>::store(cp, old);
-        } else {
-          if (EPI == EPI_GELU_BWD) {
-            float h[8];
-            Vec8<bf16_t>::load(ep.aux + (size_t)row * ep.ld2 + col, h);
-#pragma unroll
-            for (int e = 0; e < 8; e++) val[e] *= gelu_grad_f(h[e]);
+          for (int e = 0; e < 8; e++) {
+            if (AUX) val[e] *= gelu_grad_f((float)h8[e]);
+            else val[e] += (float)h8[e] * ep.resid_scale;
           }
-          bf16x8_t o;
+        }
+        bf16x8_t o;
 #pragma unroll
-          for (int e = 0; e < 8; e++) o[e] = (bf16_t)val[e];
+        for (int e = 0; e < 8; e++) o[e] = (bf16_t)val[e];
+        if (row < M && col < N) {
           *reinterpret_cast<bf16x8_t *>(reinterpret_cast<bf16_t *>(ep.C) + (size_t)row * ep.ldc + col) = o;
           if (EPI == EPI_GELU_DUAL) {
             float gv[8];
@@ -196,7 +230,16 @@ __device__ __forceinline__ void store_tile(f32x16_t (&acc)[MI][NI], float *stage
         }
       }
     }
-    __syncthreads();
+  };
+  // strips alternate between two prefetch buffers; MI is 2 or 4
+  Pre f0, f1;
+  fetch(0, f0);
+#pragma unroll
+  for (int i = 0; i < MI; i += 2) {
+    if (i + 1 < MI) fetch(i + 1, f1);
+    strip(i, f0);
+    if (i + 2 < MI) fetch(i + 2, f0);
+    if (i + 1 < MI) strip(i + 1, f1);
   }
 }
 
