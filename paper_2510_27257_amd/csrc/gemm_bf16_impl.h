@@ -398,11 +398,11 @@ struct DmaOp {
   }
 };
 
-template <int BM, int BN, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t *__restrict__ A, int lda, int a_bytes,
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTG, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(const bf16_t *__restrict__ A, int lda, int a_bytes,
                                                             const bf16_t *__restrict__ B, int ldb, int b_bytes, int M, int N, int K,
                                                             int tiles_m, int tiles_n, Epi ep) {
-  constexpr int WAVES_M = 2, WAVES_N = 4, NWAVES = 8;
+  constexpr int NWAVES = WAVES_M * WAVES_N;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, MI = WM / 32, NI = WN / 32;
   using OA = DmaOp<BM, A_KC, NWAVES>;
   using OB = DmaOp<BN, B_KC, NWAVES>;
@@ -459,11 +459,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t *__rest
       dma_load16(rb, st_ + OA::bytes + (wave * OB::NINST + (q) - OA::NINST) * 1024,                              \
                  offb[(q) >= OA::NINST ? (q) - OA::NINST : 0], kt_ * stepb);                                     \
   } while (0)
-  // prologue: tiles 0 .. DSTAGES-2 and the first LF loads of tile DSTAGES-1
+  // prologue: tiles 0 .. NSTG-2 and the first LF loads of tile NSTG-1
 #pragma unroll
-  for (int t = 0; t < DSTAGES; t++)
+  for (int t = 0; t < NSTG; t++)
 #pragma unroll
-    for (int q = 0; q < (t < DSTAGES - 1 ? LOADS_PER_TILE : LF); q++) STP_ISSUE(q, t, t);
+    for (int q = 0; q < (t < NSTG - 1 ? LOADS_PER_TILE : LF); q++) STP_ISSUE(q, t, t);
 
   u32x4_t fa0[MI], fb0[NI], fa1[MI], fb1[NI];
   using SeqM = std::make_integer_sequence<int, MI>;
@@ -494,21 +494,21 @@ __global__ __launch_bounds__(512) void gemm_bf16_dma_kernel(const bf16_t *__rest
     __builtin_amdgcn_sched_barrier(0);                                               \
   } while (0)
 
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((DSTAGES - 2) * LOADS_PER_TILE + LF) : "memory");
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSTG - 2) * LOADS_PER_TILE + LF) : "memory");
   STP_READ(0, fa0, fb0, 0);
 
   for (int kt = 0; kt < KT; kt++) {
-    const int st = kt % DSTAGES;
+    const int st = kt % NSTG;
     STP_READ(1, fa1, fb1, st);
     lds_wait<READS_PER_STEP>();          // the reads of half 0 (issued one step ago) have returned
-    STP_MFMAS(fa0, fb0, LF, LS, kt + DSTAGES - 1, (kt + DSTAGES - 1) % DSTAGES);
-    // tile kt+1 has landed once at most (DSTAGES-2) tiles' worth of this wave's loads remain in flight;
+    STP_MFMAS(fa0, fb0, LF, LS, kt + NSTG - 1, (kt + NSTG - 1) % NSTG);
+    // tile kt+1 has landed once at most (NSTG-2) tiles' worth of this wave's loads remain in flight;
     // lgkmcnt(0): this wave's reads of stage st are complete, so after the barrier the stage is free
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((DSTAGES - 2) * LOADS_PER_TILE) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NSTG - 2) * LOADS_PER_TILE) : "memory");
     __builtin_amdgcn_sched_barrier(0);
-    STP_READ(0, fa0, fb0, (kt + 1) % DSTAGES);   // past the last tile this reads a stale stage; never used
+    STP_READ(0, fa0, fb0, (kt + 1) % NSTG);   // past the last tile this reads a stale stage; never used
     lds_wait<READS_PER_STEP>();
-    STP_MFMAS(fa1, fb1, 0, LF, kt + DSTAGES, st);
+    STP_MFMAS(fa1, fb1, 0, LF, kt + NSTG, st);
   }
 #undef STP_READ
 #undef STP_MFMAS
@@ -527,11 +527,11 @@ inline long operand_bytes(bool kc, long rows, long K, long ld) {
   return el * 2 < 0x7fffffffL ? el * 2 : 0;
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTG, bool A_KC, bool B_KC, int EPI>
 int launch_dma(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t s) {
-  constexpr size_t smem = (size_t)DSTAGES * (BM + BN) * DK * 2;
-  static_assert(smem <= 160 * 1024 && smem >= (size_t)8 * 32 * (BN / 4 + 8) * sizeof(float), "LDS budget");
-  auto kern = gemm_bf16_dma_kernel<BM, BN, A_KC, B_KC, EPI>;
+  constexpr size_t smem = (size_t)NSTG * (BM + BN) * DK * 2;
+  static_assert(smem <= 160 * 1024 && smem >= (size_t)WAVES_M * WAVES_N * 32 * (BN / WAVES_N + 8) * sizeof(float), "LDS budget");
+  auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, NSTG, A_KC, B_KC, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
     STP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
@@ -539,7 +539,7 @@ int launch_dma(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t 
   }
   const int tiles_m = (a->M + BM - 1) / BM, tiles_n = (a->N + BN - 1) / BN;
   const long ab = operand_bytes(A_KC, a->M, a->K, a->lda), bb = operand_bytes(B_KC, a->N, a->K, a->ldb);
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(512), smem, s, (const bf16_t *)a->A, a->lda, (int)ab, (const bf16_t *)a->B,
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(64 * WAVES_M * WAVES_N), smem, s, (const bf16_t *)a->A, a->lda, (int)ab, (const bf16_t *)a->B,
                      a->ldb, (int)bb, a->M, a->N, a->K, tiles_m, tiles_n, ep);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
@@ -606,10 +606,10 @@ int launch_tile(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t
   if (!dma_ok) return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI>(ctx, a, ep, s);
   TileChoice c = pick_tile(a->M, a->N, a->K, A_KC, B_KC);
   if (a->tile_m) c = TileChoice{a->tile_m, a->tile_n};
-  if (c.bm == 256 && c.bn == 128) return launch_dma<256, 128, A_KC, B_KC, EPI>(ctx, a, ep, s);
-  if (c.bm == 128 && c.bn == 256) return launch_dma<128, 256, A_KC, B_KC, EPI>(ctx, a, ep, s);
-  if (c.bm == 128 && c.bn == 128) return launch_dma<128, 128, A_KC, B_KC, EPI>(ctx, a, ep, s);
-  return launch_dma<256, 256, A_KC, B_KC, EPI>(ctx, a, ep, s);
+  if (c.bm == 256 && c.bn == 128) return launch_dma<256, 128, 2, 4, DSTAGES, A_KC, B_KC, EPI>(ctx, a, ep, s);
+  if (c.bm == 128 && c.bn == 256) return launch_dma<128, 256, 2, 4, DSTAGES, A_KC, B_KC, EPI>(ctx, a, ep, s);
+  if (c.bm == 128 && c.bn == 128) return launch_dma<128, 128, 2, 4, DSTAGES, A_KC, B_KC, EPI>(ctx, a, ep, s);
+  return launch_dma<256, 256, 2, 4, DSTAGES, A_KC, B_KC, EPI>(ctx, a, ep, s);
 }
 
 template <bool A_KC, bool B_KC>
