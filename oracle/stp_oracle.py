@@ -50,10 +50,20 @@ class LayerCfg:
     has_bias: bool = True
     eps: float = 1e-5
     rope_base: float = 10000.0
+    kv_heads_local: int = 0   # key / value heads held by this rank; 0 = one per query head (the model table of
+                              # Section 5.1 lists 40 / 8 and 56 / 8 query / key-value heads: grouped-query attention)
 
     @property
     def attn_local(self) -> int:
         return self.heads_local * self.head_dim
+
+    @property
+    def kv_heads(self) -> int:
+        return self.kv_heads_local or self.heads_local
+
+    @property
+    def kv_local(self) -> int:
+        return self.kv_heads * self.head_dim
 
 
 # --------------------------------------------------------------------------
@@ -152,25 +162,31 @@ def _probs(q, k, causal: bool):
 
 
 def attention_fwd(q, k, v, causal: bool):
-    """q,k,v: [s, n, d] -> ctx [s, n, d]."""
+    """q: [s, n, d]; k, v: [s, n_kv, d] with n a multiple of n_kv -> ctx [s, n, d].
+
+    Query head i attends to key / value head i // (n / n_kv) (grouped-query attention; n_kv = n is the
+    ordinary multi-head case)."""
     out = np.empty_like(q)
+    group = q.shape[1] // k.shape[1]
     for hd in range(q.shape[1]):
-        out[:, hd, :] = _probs(q[:, hd, :], k[:, hd, :], causal) @ v[:, hd, :]
+        out[:, hd, :] = _probs(q[:, hd, :], k[:, hd // group, :], causal) @ v[:, hd // group, :]
     return out
 
 
 def attention_bwd(q, k, v, dctx, causal: bool):
     """Gradients of attention_fwd w.r.t. q, k, v."""
-    dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
+    dq, dk, dv = np.empty_like(q), np.zeros_like(k), np.zeros_like(v)
     d = q.shape[2]
+    group = q.shape[1] // k.shape[1]
     for hd in range(q.shape[1]):
-        P = _probs(q[:, hd, :], k[:, hd, :], causal)
+        kh = hd // group                      # a key / value head collects the gradients of its whole group
+        P = _probs(q[:, hd, :], k[:, kh, :], causal)
         do = dctx[:, hd, :]
-        dv[:, hd, :] = P.T @ do
-        dP = do @ v[:, hd, :].T
+        dv[:, kh, :] += P.T @ do
+        dP = do @ v[:, kh, :].T
         dS = P * (dP - (dP * P).sum(axis=1, keepdims=True))
-        dq[:, hd, :] = dS @ k[:, hd, :] / np.sqrt(d)
-        dk[:, hd, :] = dS.T @ q[:, hd, :] / np.sqrt(d)
+        dq[:, hd, :] = dS @ k[:, kh, :] / np.sqrt(d)
+        dk[:, kh, :] += dS.T @ q[:, hd, :] / np.sqrt(d)
     return dq, dk, dv
 
 
@@ -197,9 +213,10 @@ def forward_unit(cfg: LayerCfg, unit: int, w: Dict[str, np.ndarray], stash: dict
         qkv = stash["x_ln"] @ w["w_qkv"]
         if cfg.has_bias:
             qkv = qkv + w["b_qkv"]
-        q = qkv[:, 0 * a:1 * a].reshape(s, n, d)
-        k = qkv[:, 1 * a:2 * a].reshape(s, n, d)
-        v = qkv[:, 2 * a:3 * a].reshape(s, n, d)
+        nk, ak = cfg.kv_heads, cfg.kv_local       # columns of QKV: [Q heads | K heads | V heads]
+        q = qkv[:, :a].reshape(s, n, d)
+        k = qkv[:, a:a + ak].reshape(s, nk, d)
+        v = qkv[:, a + ak:a + 2 * ak].reshape(s, nk, d)
         if cfg.rope:
             q, k = rope(q, cfg.rope_base), rope(k, cfg.rope_base)
         ctx = attention_fwd(q, k, v, cfg.causal).reshape(s, a)
@@ -273,7 +290,7 @@ def backward_input_unit(cfg: LayerCfg, unit: int, w, stash: dict, dy, d_resid=No
         dq, dk, dv = attention_bwd(stash["q"], stash["k"], stash["v"], dctx, cfg.causal)
         if cfg.rope:
             dq, dk = rope(dq, cfg.rope_base, inverse=True), rope(dk, cfg.rope_base, inverse=True)
-        dqkv = np.concatenate([dq.reshape(s, a), dk.reshape(s, a), dv.reshape(s, a)], axis=1)
+        dqkv = np.concatenate([dq.reshape(s, a), dk.reshape(s, cfg.kv_local), dv.reshape(s, cfg.kv_local)], axis=1)
         stash["dqkv"] = dqkv
         return dqkv @ w["w_qkv"].T
     raise ValueError(unit)
@@ -352,11 +369,15 @@ def shard_weights(cfg_full: LayerCfg, W: Dict[str, np.ndarray], t: int, r: int):
     n, d = cfg_full.heads_local, cfg_full.head_dim
     a, f = n * d, cfg_full.ffn_local
     al, fl = a // t, f // t
+    nk, ak = cfg_full.kv_heads, cfg_full.kv_local
+    akl = ak // t                              # whole key / value heads per rank: n_kv must be a multiple of t
     out = {}
     for key in ("norm1_g", "norm1_b", "norm2_g", "norm2_b", "b_o", "b_fc2"):
         if key in W:
             out[key] = W[key]
-    cols = np.concatenate([np.arange(j * a + r * al, j * a + (r + 1) * al) for j in range(3)])
+    cols = np.concatenate([np.arange(r * al, (r + 1) * al),
+                           np.arange(a + r * akl, a + (r + 1) * akl),
+                           np.arange(a + ak + r * akl, a + ak + (r + 1) * akl)])
     out["w_qkv"] = W["w_qkv"][:, cols]
     if "b_qkv" in W:
         out["b_qkv"] = W["b_qkv"][cols]
@@ -367,7 +388,8 @@ def shard_weights(cfg_full: LayerCfg, W: Dict[str, np.ndarray], t: int, r: int):
     if "w_up" in W:
         out["w_up"] = W["w_up"][:, r * fl:(r + 1) * fl]
     out["w_fc2"] = W["w_fc2"][r * fl:(r + 1) * fl, :]
-    cfg_r = replace(cfg_full, heads_local=n // t, ffn_local=fl, tp=t)
+    cfg_r = replace(cfg_full, heads_local=n // t, ffn_local=fl, tp=t,
+                    kv_heads_local=(nk // t if cfg_full.kv_heads_local else 0))
     return cfg_r, out
 
 
@@ -391,7 +413,9 @@ def fused_layer_backward(cfg: LayerCfg, w, X, dX_out, reduce_fn=None):
     # ---- forward, keeping everything ----
     x_ln = norm_fwd(cfg, X, w["norm1_g"], w.get("norm1_b"))
     qkv = x_ln @ w["w_qkv"] + (w["b_qkv"] if cfg.has_bias else 0.0)
-    q, k, v = (qkv[:, i * a:(i + 1) * a].reshape(s, n, d) for i in range(3))
+    nk, ak = cfg.kv_heads, cfg.kv_local
+    q = qkv[:, :a].reshape(s, n, d)
+    k, v = (qkv[:, a + i * ak:a + (i + 1) * ak].reshape(s, nk, d) for i in range(2))
     if cfg.rope:
         q, k = rope(q, cfg.rope_base), rope(k, cfg.rope_base)
     ctx = attention_fwd(q, k, v, cfg.causal).reshape(s, a)
@@ -433,7 +457,7 @@ def fused_layer_backward(cfg: LayerCfg, w, X, dX_out, reduce_fn=None):
     dq, dk, dv = attention_bwd(q, k, v, dctx, cfg.causal)
     if cfg.rope:
         dq, dk = rope(dq, cfg.rope_base, True), rope(dk, cfg.rope_base, True)
-    dqkv = np.concatenate([dq.reshape(s, a), dk.reshape(s, a), dv.reshape(s, a)], 1)
+    dqkv = np.concatenate([dq.reshape(s, a), dk.reshape(s, ak), dv.reshape(s, ak)], 1)
     G["w_qkv"] = np.einsum("sh,sc->hc", x_ln, dqkv)
     if cfg.has_bias:
         G["b_qkv"] = dqkv.sum(0)

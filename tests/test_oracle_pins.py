@@ -19,8 +19,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 def rand_weights(cfg, rng, scale=0.3):
     h, a, f = cfg.hidden, cfg.attn_local, cfg.ffn_local
+    c = a + 2 * cfg.kv_local
     W = {"norm1_g": 1 + 0.2 * rng.standard_normal(h), "norm2_g": 1 + 0.2 * rng.standard_normal(h),
-         "w_qkv": scale * rng.standard_normal((h, 3 * a)), "w_o": scale * rng.standard_normal((a, h)),
+         "w_qkv": scale * rng.standard_normal((h, c)), "w_o": scale * rng.standard_normal((a, h)),
          "w_fc1": scale * rng.standard_normal((h, f)), "w_fc2": scale * rng.standard_normal((f, h))}
     if cfg.norm == "ln":
         W["norm1_b"] = 0.2 * rng.standard_normal(h)
@@ -28,7 +29,7 @@ def rand_weights(cfg, rng, scale=0.3):
     if cfg.act == "swiglu":
         W["w_up"] = scale * rng.standard_normal((h, f))
     if cfg.has_bias:
-        W.update(b_qkv=0.2 * rng.standard_normal(3 * a), b_o=0.2 * rng.standard_normal(h),
+        W.update(b_qkv=0.2 * rng.standard_normal(c), b_o=0.2 * rng.standard_normal(h),
                  b_fc1=0.2 * rng.standard_normal(f), b_fc2=0.2 * rng.standard_normal(h))
     return W
 
@@ -68,9 +69,13 @@ def torch_layer(cfg, W, X):
 
     xl = norm(X, W["norm1_g"], W.get("norm1_b"))
     qkv = xl @ W["w_qkv"] + (W["b_qkv"] if cfg.has_bias else 0)
-    q, k, v = (qkv[:, i * a:(i + 1) * a].reshape(s, n, d) for i in range(3))
+    nk = cfg.kv_heads
+    q = qkv[:, :a].reshape(s, n, d)
+    k, v = (qkv[:, a + i * nk * d:a + (i + 1) * nk * d].reshape(s, nk, d) for i in range(2))
     if cfg.rope:
         q, k = torch_rope(q, cfg.rope_base), torch_rope(k, cfg.rope_base)
+    # grouped-query attention written as ordinary attention over key / value heads repeated per group
+    k, v = k.repeat_interleave(n // nk, dim=1), v.repeat_interleave(n // nk, dim=1)
     ctx = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
                                          v.transpose(0, 1)[None], is_causal=cfg.causal)[0]
     ctx = ctx.transpose(0, 1).reshape(s, a)
@@ -82,12 +87,13 @@ def torch_layer(cfg, W, X):
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
-@pytest.mark.parametrize("t", [1, 2, 4])
-def test_tp_sum_equals_textbook_layer_and_autograd(variant, t):
+@pytest.mark.parametrize("t,heads,kv", [(1, 4, 0), (2, 4, 0), (4, 4, 0), (1, 6, 2), (2, 8, 2), (2, 8, 4), (4, 12, 4)])
+def test_tp_sum_equals_textbook_layer_and_autograd(variant, t, heads, kv):
     """Eq. 1-2: summing the t rank partials at the AR points reproduces the unsharded
-    layer and its gradients; shard weight grads are slices of the unsharded ones."""
+    layer and its gradients; shard weight grads are slices of the unsharded ones.
+    kv > 0: grouped-query attention (heads / kv query heads share a key / value head)."""
     rng = np.random.default_rng(7)
-    cfg = O.LayerCfg(hidden=24, heads_local=4, head_dim=8, ffn_local=32, tp=1, **variant)
+    cfg = O.LayerCfg(hidden=24, heads_local=heads, head_dim=8, ffn_local=32, tp=1, kv_heads_local=kv, **variant)
     s = 11
     W = rand_weights(cfg, rng)
     X = rng.standard_normal((s, cfg.hidden))
@@ -106,12 +112,13 @@ def test_tp_sum_equals_textbook_layer_and_autograd(variant, t):
     dX, grads = O.layer_backward_all_ranks(cfg_r, ws, stashes, R)
     np.testing.assert_allclose(dX, Xt.grad.numpy(), rtol=1e-9, atol=1e-10)
 
-    a, f = cfg.attn_local, cfg.ffn_local
-    al, fl = a // t, f // t
+    a, f, ak = cfg.attn_local, cfg.ffn_local, cfg.kv_local
+    al, fl, akl = a // t, f // t, ak // t
     for r in range(t):
         g = grads[r]
         full = {k: v.grad.numpy() for k, v in Wt.items()}
-        cols = np.concatenate([np.arange(j * a + r * al, j * a + (r + 1) * al) for j in range(3)])
+        cols = np.concatenate([np.arange(r * al, (r + 1) * al), np.arange(a + r * akl, a + (r + 1) * akl),
+                               np.arange(a + ak + r * akl, a + ak + (r + 1) * akl)])
         np.testing.assert_allclose(g["w_qkv"], full["w_qkv"][:, cols], rtol=1e-9, atol=1e-10)
         np.testing.assert_allclose(g["w_o"], full["w_o"][r * al:(r + 1) * al], rtol=1e-9, atol=1e-10)
         np.testing.assert_allclose(g["w_fc1"], full["w_fc1"][:, r * fl:(r + 1) * fl], rtol=1e-9, atol=1e-10)
@@ -189,15 +196,51 @@ def test_finite_differences(variant, t):
             assert abs(fd - sum(g[key][3] for g in grads)) < 2e-6 * max(1.0, abs(fd))
 
 
+def test_finite_differences_grouped_query():
+    """Central differences of a 2-rank layer with 4 query heads over 2 key / value heads: dX and the gradient
+    of the K and V columns of the QKV weight (which collect the contributions of a whole head group)."""
+    rng = np.random.default_rng(4)
+    cfg = O.LayerCfg(hidden=8, heads_local=4, head_dim=4, ffn_local=16, tp=1, kv_heads_local=2, rope=True)
+    s, t = 5, 2
+    W = rand_weights(cfg, rng)
+    X = rng.standard_normal((s, cfg.hidden))
+    R = rng.standard_normal((s, cfg.hidden))
+
+    def loss(Wd, Xd):
+        sh = [O.shard_weights(cfg, Wd, t, r) for r in range(t)]
+        out, _ = O.layer_forward_all_ranks(sh[0][0], [w for _, w in sh], Xd)
+        return float((out * R).sum())
+
+    sh = [O.shard_weights(cfg, W, t, r) for r in range(t)]
+    out, st = O.layer_forward_all_ranks(sh[0][0], [w for _, w in sh], X)
+    dX, grads = O.layer_backward_all_ranks(sh[0][0], [w for _, w in sh], st, R)
+    eps = 1e-6
+    for idx in [(0, 0), (3, 5), (4, 2)]:
+        Xp, Xm = X.copy(), X.copy()
+        Xp[idx] += eps
+        Xm[idx] -= eps
+        fd = (loss(W, Xp) - loss(W, Xm)) / (2 * eps)
+        assert abs(fd - dX[idx]) < 1e-6 * max(1.0, abs(fd))
+    a, ak = cfg.attn_local, cfg.kv_local          # 16, 8: rank 0 holds Q cols 0..7, K cols 16..19, V cols 24..27
+    al, akl = a // t, ak // t
+    for loc, full in [((2, 1), (2, 1)), ((5, al + 2), (5, a + 2)), ((1, al + akl + 3), (1, a + ak + 3))]:
+        Wp = {k: v.copy() for k, v in W.items()}
+        Wm = {k: v.copy() for k, v in W.items()}
+        Wp["w_qkv"][full] += eps
+        Wm["w_qkv"][full] -= eps
+        fd = (loss(Wp, X) - loss(Wm, X)) / (2 * eps)
+        assert abs(fd - grads[0]["w_qkv"][loc]) < 2e-6 * max(1.0, abs(fd)), (loc, fd, grads[0]["w_qkv"][loc])
+
+
 # ---------------------------------------------------------------------------
 # 3. B units + W units == independently written fused backward
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("variant", VARIANTS)
-@pytest.mark.parametrize("t", [1, 2, 8])
-def test_b_plus_w_equals_fused_backward(variant, t):
+@pytest.mark.parametrize("t,heads,kv", [(1, 2, 0), (2, 2, 0), (8, 2, 0), (4, 6, 2), (8, 5, 1)])
+def test_b_plus_w_equals_fused_backward(variant, t, heads, kv):
     """Single rank, identity at the AR points (the configuration the GPU is timed in)."""
     rng = np.random.default_rng(11)
-    cfg = O.LayerCfg(hidden=16, heads_local=2, head_dim=8, ffn_local=24, tp=t, **variant)
+    cfg = O.LayerCfg(hidden=16, heads_local=heads, head_dim=8, ffn_local=24, tp=t, kv_heads_local=kv, **variant)
     s = 9
     W = rand_weights(cfg, rng)
     X = rng.standard_normal((s, cfg.hidden))
@@ -257,6 +300,26 @@ def test_attention_brute_force_loops():
                 for c in range(d):
                     want = sum(e[jj] / z * v[j, hd, c] for jj, j in enumerate(js))
                     assert abs(got[i, hd, c] - want) < 1e-12
+
+
+def test_grouped_query_attention_is_attention_over_repeated_heads():
+    """n query heads over n_kv key / value heads equals ordinary attention with every key / value head repeated
+    n / n_kv times; the gradient of a shared head is the sum over its group.  (The multi-head path used on the
+    right-hand side is pinned by the brute-force and library tests.)"""
+    rng = np.random.default_rng(21)
+    s, n, nk, d = 9, 6, 2, 4
+    q, dctx = rng.standard_normal((s, n, d)), rng.standard_normal((s, n, d))
+    k, v = rng.standard_normal((s, nk, d)), rng.standard_normal((s, nk, d))
+    kr, vr = np.repeat(k, n // nk, axis=1), np.repeat(v, n // nk, axis=1)
+    for causal in (True, False):
+        np.testing.assert_allclose(O.attention_fwd(q, k, v, causal), O.attention_fwd(q, kr, vr, causal), rtol=1e-12)
+        dq, dk, dv = O.attention_bwd(q, k, v, dctx, causal)
+        dq_r, dk_r, dv_r = O.attention_bwd(q, kr, vr, dctx, causal)
+        np.testing.assert_allclose(dq, dq_r, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(dk, dk_r.reshape(s, nk, n // nk, d).sum(axis=2), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(dv, dv_r.reshape(s, nk, n // nk, d).sum(axis=2), rtol=1e-12, atol=1e-13)
+    # a wrong head-to-group map (i % n_kv instead of i // group) changes the result
+    assert not np.allclose(O.attention_fwd(q, k, v, True), O.attention_fwd(q, np.tile(k, (1, n // nk, 1)), np.tile(v, (1, n // nk, 1)), True))
 
 
 def test_attention_special_cases():
