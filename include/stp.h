@@ -84,6 +84,9 @@ typedef struct {
   int32_t has_bias;     /* 1: linear layers carry biases */
   float eps;            /* norm epsilon */
   float rope_base;      /* e.g. 10000 */
+  int32_t kv_heads_local; /* key / value heads on this rank (grouped-query attention: the model table of Section 5.1
+                           * lists 40 / 8 and 56 / 8 query / key-value heads); 0 = heads_local; must divide heads_local.
+                           * QKV activations are [tokens][(heads_local + 2 kv_heads_local) head_dim]: Q heads, K heads, V heads */
 } stp_layer_desc;
 
 /* Device pointers to one rank's weights; entries a configuration does not use

@@ -42,7 +42,7 @@ class StpError(RuntimeError):
 class LayerDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("hidden", "heads_local", "head_dim", "ffn_local", "seq", "mbsz", "tp",
                                          "dtype", "norm", "act", "causal", "rope", "has_bias")] + \
-               [("eps", C.c_float), ("rope_base", C.c_float)]
+               [("eps", C.c_float), ("rope_base", C.c_float), ("kv_heads_local", C.c_int32)]
 
 
 _W_NAMES = ("norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o", "norm2_g", "norm2_b", "w_fc1", "b_fc1",
@@ -154,7 +154,7 @@ def make_desc(wl, mbsz: int = 1, seq: Optional[int] = None) -> LayerDesc:
                      norm=NORM_LN if wl.norm == "ln" else NORM_RMS,
                      act=ACT_GELU if wl.act == "gelu" else ACT_SWIGLU,
                      causal=int(wl.causal), rope=int(wl.rope), has_bias=int(wl.has_bias),
-                     eps=wl.eps, rope_base=wl.rope_base)
+                     eps=wl.eps, rope_base=wl.rope_base, kv_heads_local=int(getattr(wl, "kv_heads", 0)))
 
 
 def _ptr(t) -> Optional[int]:

@@ -9,6 +9,8 @@
 // waves 0-3 (group A) take keys 0..63 and waves 4-7 (group B) keys 64..127; a SIMD holds one wave of
 // each group.  The two halves are merged through LDS at the end.
 //
+// Grouped-query attention: query head i reads key / value head i / (n / nk); only the tile addresses change.
+//
 // Per wave the kernel works on the TRANSPOSED score tile, S^T = K Q^T: with the 32x32x16 MFMA the
 // accumulator of lane l then holds column q = l % 32, i.e. every softmax statistic (running max,
 // running sum, rescale factor) is a per-lane scalar and a row reduction is an in-lane loop plus one
@@ -94,7 +96,7 @@ __device__ __forceinline__ void mfma_pv(f32x16_t (&o)[D / 32], const u32x4_t (&b
 
 template <int D>
 __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__restrict__ qkv, float *__restrict__ part, int seq,
-                                                            int n, int causal, int max_chunks, int chunk_steps, float scale_log2) {
+                                                            int n, int nk, int causal, int max_chunks, int chunk_steps, float scale_log2) {
   using G = AttnGeom<D>;
   static_assert(D == 64 || D == 128, "head dimension");
   constexpr int RB = G::RB, CPR = G::CPR, RPB = G::RPB, RPI = G::RPI, NLD = G::NLD, TILE = G::TILE;
@@ -114,7 +116,8 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
   const int ns = s_end - s_begin;
 
   const int a = n * D;
-  const int ld = 3 * a;
+  const int ld = (n + 2 * nk) * D;              // a qkv row: n Q heads, nk K heads, nk V heads
+  const int kcol = a + (head / (n / nk)) * D, vcol = kcol + nk * D;   // this head's key / value head
   const bf16_t *bbase = qkv + (size_t)b * seq * ld;           // this sequence's [seq][3a] block
   const int q_wave0 = qb * QB + qsub * 32;
   const int qg = q_wave0 + lr;                  // this lane's query row
@@ -135,8 +138,8 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
   for (int j = 0; j < NLD; j++) {
     const int row = (wave * NLD + j) * RPI + lane / CPR, slot = lane % CPR;
     ld_row[j] = row;
-    ld_kcol[j] = (unsigned)(head * D + a + (slot ^ ((row / RPB) & (CPR - 1))) * 8) * 2u;
-    ld_vcol[j] = (unsigned)(head * D + 2 * a + (slot ^ (4 * ((row & 3) / RPB))) * 8) * 2u;
+    ld_kcol[j] = (unsigned)(kcol + (slot ^ ((row / RPB) & (CPR - 1))) * 8) * 2u;
+    ld_vcol[j] = (unsigned)(vcol + (slot ^ (4 * ((row & 3) / RPB))) * 8) * 2u;
   }
   // load j (0 .. NLD-1) of the K or V tile of local step k, into ring slot k & 1
   auto issue_one = [&](int k, bool is_v, int j) {
@@ -443,7 +446,7 @@ int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out
     STP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_set = true;
   }
-  if ((size_t)d->seq * 3 * d->heads_local * D * sizeof(bf16_t) > (size_t)0x7fffffff)
+  if ((size_t)d->seq * stp_qkv_width(d) * sizeof(bf16_t) > (size_t)0x7fffffff)
     return stp_fail(ctx, STP_ESHAPE, "attention forward: one sequence of QKV must span less than 2 GiB%s");
   const int nqb = (d->seq + QB - 1) / QB;
   const int chunk_steps = fwd_chunk_steps(d);
@@ -453,7 +456,8 @@ int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out
     return stp_fail(ctx, STP_ENOSPACE, "attention forward: workspace lane too small%s (need %ld bytes)", "", (long)need);
   dim3 grid(nqb, max_chunks, d->heads_local * d->mbsz), block(512);
   float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
-  hipLaunchKernelGGL(kern, grid, block, smem, s, (const bf16_t *)qkv, ws, d->seq, d->heads_local, d->causal, max_chunks, chunk_steps, scale_log2);
+  hipLaunchKernelGGL(kern, grid, block, smem, s, (const bf16_t *)qkv, ws, d->seq, d->heads_local, stp_kv_heads(d), d->causal, max_chunks, chunk_steps,
+                     scale_log2);
   STP_LAUNCH_CHECK(ctx);
   size_t waves = (size_t)d->mbsz * d->heads_local * d->seq;
   hipLaunchKernelGGL(attn_fwd_combine_kernel<D>, dim3((waves + 3) / 4), dim3(256), 0, s, ws, (bf16_t *)out, lse, d->seq,

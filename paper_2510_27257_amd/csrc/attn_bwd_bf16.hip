@@ -12,6 +12,9 @@
 //   * dq: a workgroup owns 128 queries and one chunk of up to 16 steps of 128 keys; 8 waves = 4 query sub-tiles
 //     x 2 halves of each 128-key step, with the transposed tiles S^T = K Q^T, dP^T = V dO^T (queries
 //     as MFMA columns: L and delta are per-lane scalars) and dQ^T += K^T dS^T.
+// Grouped-query attention: a key / value head serves n / nk query heads.  dq only changes its tile addresses;
+// a dkv workgroup runs over the (query head of the group, query step) pairs of its key block, so dK and dV
+// collect the whole group in a fixed order.
 // In both, the two wave halves are summed through LDS, every chunk writes an fp32 partial, and a
 // small combine kernel adds the chunks in a fixed order.  Chunking balances the causal triangle over
 // the 256 compute units; the 8-wave layout puts two waves on every SIMD so one wave's exponentials
@@ -112,7 +115,7 @@ __host__ __device__ inline int dq_steps(int qb, int seq, int causal) {
 template <int D>
 __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                                            const float *__restrict__ lse, const float *__restrict__ delta,
-                                                           float *__restrict__ part, int seq, int n, int causal,
+                                                           float *__restrict__ part, int seq, int n, int nk, int causal,
                                                            int max_chunks, int chunk_steps, float scale) {
   using G = BG<D>;
   constexpr int RB = G::RB;
@@ -124,44 +127,50 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
   const int lr = lane & 31, lg = lane >> 5;
   const int ksub = wave & 3, qhalf = wave >> 2;
   const int kvb = blockIdx.x, chunk = blockIdx.y;      // key block 0 owns the most chunks and is scheduled first
-  const int head = blockIdx.z % n, b = blockIdx.z / n;
+  const int kh = blockIdx.z % nk, b = blockIdx.z / nk;     // key / value head
+  const int group = n / nk;                                // query heads kh*group .. kh*group+group-1 share it
   const int nq = (seq + QSTEP - 1) / QSTEP;
-  const int s_begin = dkv_first_step(kvb, causal) + chunk * chunk_steps, s_end = min(nq, s_begin + chunk_steps);
-  if (s_begin >= nq) return;
+  // the workgroup's steps run over (query head of the group, 64-query step): step u is query head
+  // kh*group + u / nq_k, queries (first + u % nq_k) * 64 ..
+  const int first = dkv_first_step(kvb, causal), nq_k = nq - first;
+  const int s_begin = chunk * chunk_steps, s_end = min(group * nq_k, s_begin + chunk_steps);
+  if (s_begin >= group * nq_k) return;
   const int ns = s_end - s_begin;
 
   const int a = n * D;
-  const unsigned ldq = 3u * a * 2u, ldo = (unsigned)a * 2u;       // row pitches in bytes
-  const bf16_t *qkv_b = qkv + (size_t)b * seq * 3 * a;
+  const unsigned ldq = (unsigned)(n + 2 * nk) * D * 2u, ldo = (unsigned)a * 2u;       // row pitches in bytes
+  const bf16_t *qkv_b = qkv + (size_t)b * seq * (n + 2 * nk) * D;
   const bf16_t *do_b = dout + (size_t)b * seq * a;
-  const float *lse_b = lse + ((size_t)b * n + head) * seq;
-  const float *del_b = delta + ((size_t)b * n + head) * seq;
   const __amdgpu_buffer_rsrc_t rs_qkv =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv_b), 0, (int)min((size_t)seq * ldq, (size_t)0x7fffffff), 0x00020000);
   const __amdgpu_buffer_rsrc_t rs_do =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(do_b), 0, (int)min((size_t)seq * ldo, (size_t)0x7fffffff), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rs_lse = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(lse_b), 0, seq * 4, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rs_del = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(del_b), 0, seq * 4, 0x00020000);
+  // lse and delta of this sequence, all heads: [n][seq]
+  const __amdgpu_buffer_rsrc_t rs_lse =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(lse + (size_t)b * n * seq), 0, n * seq * 4, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_del =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(delta + (size_t)b * n * seq), 0, n * seq * 4, 0x00020000);
   const int kv_wave0 = kvb * KVB + ksub * 32;
   const int kvg = kv_wave0 + lr;
   const float scale_log2 = scale * LOG2E;
 
-  // tile k of the chunk (64 queries): Q, dO, lse, delta into ring stage k & 1
+  // tile k of the chunk (64 queries of one query head): Q, dO, lse, delta into ring stage k & 1
   auto issue_step = [&](int k) {
-    const int q0 = (s_begin + k) * QSTEP;
+    const int u = s_begin + k, head = kh * group + u / nq_k;
+    const int q0 = (first + u % nq_k) * QSTEP;
     char *st = smem_raw + OFF_RING + (k & 1) * STAGE;
     dma_tile<D, QSTEP>(rs_qkv, st, q0, seq, ldq, (unsigned)(head * D) * 2u, wave, lane);
     dma_tile<D, QSTEP>(rs_do, st + Q_TILE, q0, seq, ldo, (unsigned)(head * D) * 2u, wave, lane);
     if (wave < 2) {   // one 4-byte-per-lane instruction each for the 64 lse and delta values
-      const unsigned off = (unsigned)min(q0 + lane, seq - 1) * 4u;
+      const unsigned off = (unsigned)(head * seq + min(q0 + lane, seq - 1)) * 4u;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(wave == 0 ? rs_lse : rs_del,
                                                (lptr_t)(smem_raw + OFF_STAT + (k & 1) * 512 + wave * 256), 4, off, 0, 0, 0);
     }
   };
 
   // K and V of the 128 keys: loaded once
-  dma_tile<D, KVB>(rs_qkv, smem_raw + OFF_K, kvb * KVB, seq, ldq, (unsigned)(a + head * D) * 2u, wave, lane);
-  dma_tile<D, KVB>(rs_qkv, smem_raw + OFF_V, kvb * KVB, seq, ldq, (unsigned)(2 * a + head * D) * 2u, wave, lane);
+  dma_tile<D, KVB>(rs_qkv, smem_raw + OFF_K, kvb * KVB, seq, ldq, (unsigned)(a + kh * D) * 2u, wave, lane);
+  dma_tile<D, KVB>(rs_qkv, smem_raw + OFF_V, kvb * KVB, seq, ldq, (unsigned)(a + (nk + kh) * D) * 2u, wave, lane);
   issue_step(0);
 
   const unsigned lds0 = (unsigned)(size_t)(const __attribute__((address_space(3))) char *)smem_raw;
@@ -182,7 +191,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     STP_SB();
     if (k + 1 < ns) issue_step(k + 1);
-    const int q0 = (s_begin + k) * QSTEP;
+    const int q0 = (first + (s_begin + k) % nq_k) * QSTEP;
     const int qs0 = q0 + 32 * qhalf;                        // this wave's 32 queries of the step
     const bool active = !causal || qs0 + 31 >= kv_wave0;    // some query sees some key of the wave
     if (!active) continue;
@@ -278,7 +287,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
   __syncthreads();
   if (qhalf == 0 && kvg < seq) {
     const int nkvb = (seq + KVB - 1) / KVB;
-    const size_t piece = (((size_t)b * n + head) * nkvb + kvb) * max_chunks + chunk;
+    const size_t piece = (((size_t)b * nk + kh) * nkvb + kvb) * max_chunks + chunk;
     float *pk = part + piece * (size_t)(2 * KVB * D) + (size_t)(ksub * 32 + lr) * D;
     float *pv = pk + (size_t)KVB * D;
 #pragma unroll
@@ -301,18 +310,18 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
 // dK = scale * sum_c, dV = sum_c over the chunks of a key block (fixed order).  One thread per 8 columns of a key row.
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ dqkv,
-                                                                   int seq, int n, int mbsz, int causal, int max_chunks,
+                                                                   int seq, int n, int nk, int mbsz, int causal, int max_chunks,
                                                                    int chunk_steps, float scale) {
   const size_t idx = blockIdx.x * (size_t)256 + threadIdx.x;
   constexpr int CPR = D / 8;
-  if (idx >= (size_t)mbsz * n * seq * CPR) return;
+  if (idx >= (size_t)mbsz * nk * seq * CPR) return;
   const int c8 = (idx % CPR) * 8;
   const size_t row = idx / CPR;
-  const int kv = row % seq, head = (row / seq) % n, b = row / ((size_t)seq * n);
+  const int kv = row % seq, kh = (row / seq) % nk, b = row / ((size_t)seq * nk);
   const int kvb = kv / KVB, kloc = kv % KVB;
   const int nkvb = (seq + KVB - 1) / KVB, nq = (seq + QSTEP - 1) / QSTEP;
-  const int nch = (nq - dkv_first_step(kvb, causal) + chunk_steps - 1) / chunk_steps;
-  const float *p0 = part + ((((size_t)b * n + head) * nkvb + kvb) * max_chunks) * (size_t)(2 * KVB * D) + (size_t)kloc * D + c8;
+  const int nch = ((n / nk) * (nq - dkv_first_step(kvb, causal)) + chunk_steps - 1) / chunk_steps;
+  const float *p0 = part + ((((size_t)b * nk + kh) * nkvb + kvb) * max_chunks) * (size_t)(2 * KVB * D) + (size_t)kloc * D + c8;
   float sk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sv[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int c = 0; c < nch; c++) {
     float a8[8], b8[8];
@@ -323,10 +332,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_combine_kernel(const float *
   }
 #pragma unroll
   for (int e = 0; e < 8; e++) sk[e] *= scale;
-  const int a = n * D;
-  bf16_t *dkp = dqkv + ((size_t)b * seq + kv) * (3 * (size_t)a) + a + head * D + c8;
+  bf16_t *dkp = dqkv + ((size_t)b * seq + kv) * ((size_t)(n + 2 * nk) * D) + (n + kh) * D + c8;
   Vec8<bf16_t>::store(dkp, sk);
-  Vec8<bf16_t>::store(dkp + a, sv);
+  Vec8<bf16_t>::store(dkp + nk * D, sv);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -335,7 +343,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_combine_kernel(const float *
 template <int D>
 __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                                           const float *__restrict__ lse, const float *__restrict__ delta,
-                                                          float *__restrict__ part, int seq, int n, int causal, int max_chunks,
+                                                          float *__restrict__ part, int seq, int n, int nk, int causal, int max_chunks,
                                                           int chunk_steps, float scale) {
   using G = BG<D>;
   constexpr int RB = G::RB;
@@ -355,8 +363,9 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
   const int ns = s_end - s_begin;
 
   const int a = n * D;
-  const size_t ld = 3 * (size_t)a;
-  const unsigned ldq = 3u * a * 2u;
+  const size_t ld = (size_t)(n + 2 * nk) * D;            // a qkv row: n Q heads, nk K heads, nk V heads
+  const unsigned ldq = (unsigned)ld * 2u;
+  const int kcol = a + (head / (n / nk)) * D, vcol = kcol + nk * D;   // this head's key / value head
   const bf16_t *qkv_b = qkv + (size_t)b * seq * ld;
   const bf16_t *qbase = qkv_b + head * D;
   const bf16_t *dobase = dout + (size_t)b * seq * a + head * D;
@@ -364,8 +373,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
       __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(qkv_b), 0, (int)min((size_t)seq * ldq, (size_t)0x7fffffff), 0x00020000);
   auto issue_step = [&](int k) {
     char *st = smem_raw + (k & 1) * STAGE;
-    dma_tile<D, KVB>(rs_qkv, st, (s_begin + k) * KVB, seq, ldq, (unsigned)(a + head * D) * 2u, wave, lane);
-    dma_tile<D, KVB>(rs_qkv, st + KV_TILE, (s_begin + k) * KVB, seq, ldq, (unsigned)(2 * a + head * D) * 2u, wave, lane);
+    dma_tile<D, KVB>(rs_qkv, st, (s_begin + k) * KVB, seq, ldq, (unsigned)kcol * 2u, wave, lane);
+    dma_tile<D, KVB>(rs_qkv, st + KV_TILE, (s_begin + k) * KVB, seq, ldq, (unsigned)vcol * 2u, wave, lane);
   };
   issue_step(0);
 
@@ -495,7 +504,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
 
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dq_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ dqkv,
-                                                                  int seq, int n, int mbsz, int causal, int max_chunks,
+                                                                  int seq, int n, int nk, int mbsz, int causal, int max_chunks,
                                                                   int chunk_steps, float scale) {
   const size_t idx = blockIdx.x * (size_t)256 + threadIdx.x;
   constexpr int CPR = D / 8;
@@ -516,15 +525,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_combine_kernel(const float *_
   }
 #pragma unroll
   for (int e = 0; e < 8; e++) sq[e] *= scale;
-  const int a = n * D;
-  Vec8<bf16_t>::store(dqkv + ((size_t)b * seq + q) * (3 * (size_t)a) + head * D + c8, sq);
+  Vec8<bf16_t>::store(dqkv + ((size_t)b * seq + q) * ((size_t)(n + 2 * nk) * D) + head * D + c8, sq);
 }
 
 // steps per chunk for this shape (grid x: key blocks in order for dkv; query blocks, last first, for dq)
 inline int dkv_chunk_steps(const stp_layer_desc *d) {
   const int nkvb = (d->seq + KVB - 1) / KVB, nq = (d->seq + QSTEP - 1) / QSTEP;
   std::vector<int> steps(nkvb);
-  for (int x = 0; x < nkvb; x++) steps[x] = nq - dkv_first_step(x, d->causal);
+  const int group = d->heads_local / stp_kv_heads(d);     // a key block runs over the steps of its whole head group
+  for (int x = 0; x < nkvb; x++) steps[x] = group * (nq - dkv_first_step(x, d->causal));
   return stp_pick_chunk(1, nkvb, steps.data());
 }
 inline int dq_chunk_steps(const stp_layer_desc *d) {
@@ -533,7 +542,9 @@ inline int dq_chunk_steps(const stp_layer_desc *d) {
   for (int x = 0; x < nqb; x++) steps[x] = dq_steps(nqb - 1 - x, d->seq, d->causal);
   return stp_pick_chunk(2, nqb, steps.data());
 }
-inline int dkv_max_chunks(int seq, int chunk_steps) { return ((seq + QSTEP - 1) / QSTEP + chunk_steps - 1) / chunk_steps; }
+inline int dkv_max_chunks(int seq, int group, int chunk_steps) {
+  return (group * ((seq + QSTEP - 1) / QSTEP) + chunk_steps - 1) / chunk_steps;
+}
 inline int dq_max_chunks(int seq, int causal, int chunk_steps) {
   return (dq_steps((seq + 127) / 128 - 1, seq, causal) + chunk_steps - 1) / chunk_steps;
 }
@@ -546,7 +557,7 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
   constexpr size_t smem_q = (size_t)4 * KVB * G::RB;                              // ring of {K, V}
   static_assert(smem_kv <= 160 * 1024 && smem_kv >= (size_t)4 * D * 64 * sizeof(float), "dkv LDS budget");
   static_assert(smem_q <= 160 * 1024 && smem_q >= (size_t)4 * (D / 2) * 64 * sizeof(float), "dq LDS budget");
-  if ((size_t)d->seq * 3 * d->heads_local * D * sizeof(bf16_t) > (size_t)0x7fffffff)
+  if ((size_t)d->seq * stp_qkv_width(d) * sizeof(bf16_t) > (size_t)0x7fffffff)
     return stp_fail(ctx, STP_ESHAPE, "attention backward: one sequence of QKV must span less than 2 GiB%s");
   auto kkv = attn_bwd_dkv_kernel<D>;
   auto kq = attn_bwd_dq_kernel<D>;
@@ -558,25 +569,26 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
   }
   const float scale = 1.0f / sqrtf((float)D);
   const int nkvb = (d->seq + KVB - 1) / KVB, nqb = (d->seq + 127) / 128;
+  const int nk = stp_kv_heads(d), group = d->heads_local / nk;
   const int ch_kv = dkv_chunk_steps(d), ch_q = dq_chunk_steps(d);
-  const int mc_kv = dkv_max_chunks(d->seq, ch_kv), mc_q = dq_max_chunks(d->seq, d->causal, ch_q);
-  const size_t bh = (size_t)d->mbsz * d->heads_local;
-  const size_t need_kv = bh * nkvb * mc_kv * 2 * KVB * D * sizeof(float), need_q = bh * nqb * mc_q * 128 * D * sizeof(float);
+  const int mc_kv = dkv_max_chunks(d->seq, group, ch_kv), mc_q = dq_max_chunks(d->seq, d->causal, ch_q);
+  const size_t bh = (size_t)d->mbsz * d->heads_local, bk = (size_t)d->mbsz * nk;
+  const size_t need_kv = bk * nkvb * mc_kv * 2 * KVB * D * sizeof(float), need_q = bh * nqb * mc_q * 128 * D * sizeof(float);
   const size_t need = need_kv > need_q ? need_kv : need_q;
   if (!ws || ws_bytes < need)
     return stp_fail(ctx, STP_ENOSPACE, "attention backward: workspace lane too small%s (need %ld bytes)", "", (long)need);
-  const size_t rows8 = bh * d->seq * (D / 8);
-  hipLaunchKernelGGL(kkv, dim3(nkvb, mc_kv, (unsigned)bh), dim3(512), smem_kv, s, (const bf16_t *)qkv, (const bf16_t *)dout, lse,
-                     delta, ws, d->seq, d->heads_local, d->causal, mc_kv, ch_kv, scale);
+  const size_t rows8 = bh * d->seq * (D / 8), rows8_kv = bk * d->seq * (D / 8);
+  hipLaunchKernelGGL(kkv, dim3(nkvb, mc_kv, (unsigned)bk), dim3(512), smem_kv, s, (const bf16_t *)qkv, (const bf16_t *)dout, lse,
+                     delta, ws, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv, scale);
   STP_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(attn_bwd_dkv_combine_kernel<D>, dim3((rows8 + 255) / 256), dim3(256), 0, s, ws, (bf16_t *)dqkv, d->seq,
-                     d->heads_local, d->mbsz, d->causal, mc_kv, ch_kv, scale);
+  hipLaunchKernelGGL(attn_bwd_dkv_combine_kernel<D>, dim3((rows8_kv + 255) / 256), dim3(256), 0, s, ws, (bf16_t *)dqkv, d->seq,
+                     d->heads_local, nk, d->mbsz, d->causal, mc_kv, ch_kv, scale);
   STP_LAUNCH_CHECK(ctx);
   hipLaunchKernelGGL(kq, dim3(nqb, mc_q, (unsigned)bh), dim3(512), smem_q, s, (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta,
-                     ws, d->seq, d->heads_local, d->causal, mc_q, ch_q, scale);
+                     ws, d->seq, d->heads_local, nk, d->causal, mc_q, ch_q, scale);
   STP_LAUNCH_CHECK(ctx);
   hipLaunchKernelGGL(attn_bwd_dq_combine_kernel<D>, dim3((rows8 + 255) / 256), dim3(256), 0, s, ws, (bf16_t *)dqkv, d->seq,
-                     d->heads_local, d->mbsz, d->causal, mc_q, ch_q, scale);
+                     d->heads_local, nk, d->mbsz, d->causal, mc_q, ch_q, scale);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }
@@ -585,8 +597,9 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
 
 size_t stp_attn_bwd_ws_bytes(const stp_layer_desc *d) {
   const int nkvb = (d->seq + KVB - 1) / KVB, nqb = (d->seq + 127) / 128;
-  const size_t bh = (size_t)d->mbsz * d->heads_local;
-  const size_t need_kv = bh * nkvb * dkv_max_chunks(d->seq, dkv_chunk_steps(d)) * 2 * KVB * d->head_dim * sizeof(float);
+  const int nk = stp_kv_heads(d);
+  const size_t bh = (size_t)d->mbsz * d->heads_local, bk = (size_t)d->mbsz * nk;
+  const size_t need_kv = bk * nkvb * dkv_max_chunks(d->seq, d->heads_local / nk, dkv_chunk_steps(d)) * 2 * KVB * d->head_dim * sizeof(float);
   const size_t need_q = bh * nqb * dq_max_chunks(d->seq, d->causal, dq_chunk_steps(d)) * 128 * d->head_dim * sizeof(float);
   return need_kv > need_q ? need_kv : need_q;
 }

@@ -124,6 +124,10 @@ int stp_launch_attn_fwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *
                              size_t ws_bytes, hipStream_t s);
 int stp_launch_attn_bwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const void *out, const float *lse,
                              const void *dout, float *delta, void *dqkv, float *ws, size_t ws_bytes, hipStream_t s);
+// grouped-query attention: key / value heads of a rank and the width of its QKV activation
+static inline int stp_kv_heads(const stp_layer_desc *d) { return d->kv_heads_local > 0 ? d->kv_heads_local : d->heads_local; }
+static inline int stp_qkv_width(const stp_layer_desc *d) { return (d->heads_local + 2 * stp_kv_heads(d)) * d->head_dim; }
+
 // Steps per chunk for the attention kernels, whose workgroups own one chunk of a block's step range (grid =
 // blocks x chunks x heads).  kind: 0 forward, 1 dkv, 2 dq; steps[x] is the number of steps of block x.
 int stp_pick_chunk(int kind, int nblocks, const int *steps);

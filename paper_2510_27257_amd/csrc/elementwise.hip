@@ -284,22 +284,22 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T *__restrict__ g
 }
 
 // ======================================================================
-// Rotary embedding, in place on the Q and K thirds of qkv [T, 3a].
-// One thread rotates 8 pairs (i, i + d/2) of one head of one token.
+// Rotary embedding, in place on the Q and K heads of qkv [T, (n + 2 n_kv) d] (the first nrot = n + n_kv heads
+// of a row).  One thread rotates 8 pairs (i, i + d/2) of one head of one token.
 // ======================================================================
 template <typename T>
-__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int tokens, int seq, int n, int d,
+__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int tokens, int seq, int nrot, int row_width, int d,
                                                    float log2_base, float sign) {
   const int half = d / 2, per_head = half / 8;
-  size_t total = (size_t)tokens * 2 * n * per_head;
+  size_t total = (size_t)tokens * nrot * per_head;
   size_t idx = blockIdx.x * (size_t)256 + threadIdx.x;
   if (idx >= total) return;
   int c = idx % per_head;
   size_t r = idx / per_head;
-  int head = r % (2 * n);  // 0..n-1: Q heads, n..2n-1: K heads (contiguous thirds)
-  size_t tok = r / (2 * n);
+  int head = r % nrot;     // Q heads, then K heads (contiguous in a row)
+  size_t tok = r / nrot;
   int pos = tok % seq;
-  T *p = qkv + tok * (size_t)(3 * n * d) + (size_t)head * d + c * 8;
+  T *p = qkv + tok * (size_t)row_width + (size_t)head * d + c * 8;
   float a[8], b[8], oa[8], ob[8];
   Vec8<T>::load(p, a);
   Vec8<T>::load(p + half, b);
@@ -540,14 +540,15 @@ extern "C" int stp_rope(stp_ctx *ctx, const stp_layer_desc *d, void *qkv, int in
   if (!stp_aligned16(qkv)) return stp_fail(ctx, STP_EALIGN, "stp_rope: alignment%s");
   int tokens = d->seq * d->mbsz;
   if (tokens == 0) return STP_OK;
-  size_t total = (size_t)tokens * 2 * d->heads_local * (d->head_dim / 16);
+  const int nrot = d->heads_local + stp_kv_heads(d);
+  size_t total = (size_t)tokens * nrot * (d->head_dim / 16);
   dim3 grid((total + 255) / 256), block(256);
   float log2_base = log2f(d->rope_base), sign = inverse ? -1.0f : 1.0f;
   hipStream_t s = (hipStream_t)hip_stream;
   if (d->dtype == STP_BF16)
-    hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, block, 0, s, (bf16_t *)qkv, tokens, d->seq, d->heads_local, d->head_dim, log2_base, sign);
+    hipLaunchKernelGGL(rope_kernel<bf16_t>, grid, block, 0, s, (bf16_t *)qkv, tokens, d->seq, nrot, stp_qkv_width(d), d->head_dim, log2_base, sign);
   else
-    hipLaunchKernelGGL(rope_kernel<float>, grid, block, 0, s, (float *)qkv, tokens, d->seq, d->heads_local, d->head_dim, log2_base, sign);
+    hipLaunchKernelGGL(rope_kernel<float>, grid, block, 0, s, (float *)qkv, tokens, d->seq, nrot, stp_qkv_width(d), d->head_dim, log2_base, sign);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }

@@ -55,6 +55,7 @@ extern "C" int stp_check_desc(const stp_layer_desc *d) {
   if (d->norm != STP_NORM_LN && d->norm != STP_NORM_RMS) return STP_EINVAL;
   if (d->act != STP_ACT_GELU && d->act != STP_ACT_SWIGLU) return STP_EINVAL;
   if (d->tp < 1 || d->seq < 1 || d->mbsz < 1 || d->heads_local < 1) return STP_ESHAPE;
+  if (d->kv_heads_local < 0 || (d->kv_heads_local > 0 && d->heads_local % d->kv_heads_local)) return STP_ESHAPE;
   if (d->hidden < 8 || d->hidden % 8 || d->hidden > 8192) return STP_ESHAPE;
   if (d->ffn_local < 8 || d->ffn_local % 8) return STP_ESHAPE;
   if (d->head_dim < 8 || d->head_dim % 8 || d->head_dim > 128) return STP_ESHAPE;
@@ -75,7 +76,7 @@ static size_t field_bytes(const stp_layer_desc *d, int f) {
     case STP_ST_X_LN: case STP_ST_Z_LN: case STP_ST_X_ATTN: case STP_ST_DX_ATTN: case STP_ST_DZ: case STP_ST_DX_LN:
       return T * h * es;
     case STP_ST_STATS1: case STP_ST_STATS2: return T * 2 * sizeof(float);
-    case STP_ST_QKV: case STP_ST_DQKV: return T * 3 * a * es;
+    case STP_ST_QKV: case STP_ST_DQKV: return T * (size_t)stp_qkv_width(d) * es;
     case STP_ST_CTX: case STP_ST_DCTX: return T * a * es;
     case STP_ST_LSE: case STP_ST_DELTA: return (size_t)d->mbsz * d->heads_local * d->seq * sizeof(float);
     case STP_ST_H: case STP_ST_G: case STP_ST_DH: return T * ff * es;
@@ -107,7 +108,7 @@ extern "C" int stp_stash_bytes(const stp_layer_desc *d, size_t *bytes) {
 
 static size_t ws_lane_bytes(const stp_layer_desc *d) {
   const size_t T = (size_t)d->seq * d->mbsz;
-  const size_t h = d->hidden, a3 = 3 * (size_t)d->heads_local * d->head_dim, ff = d->ffn_local;
+  const size_t h = d->hidden, a3 = (size_t)stp_qkv_width(d), ff = d->ffn_local;
   size_t groups = T < 512 ? T : 512;
   size_t norm = groups * 2 * h * sizeof(float);
   size_t widest = h > a3 ? h : a3;
@@ -282,10 +283,10 @@ extern "C" int stp_forward_unit(stp_ctx *ctx, const stp_layer_desc *d, int unit,
       RET_IF(need_ptr(ctx, w->w_qkv, "w_qkv"));
       RET_IF(need_ptr(ctx, w->w_o, "w_o"));
       if (bias) { RET_IF(need_ptr(ctx, w->b_qkv, "b_qkv")); RET_IF(need_ptr(ctx, w->b_o, "b_o")); }
-      stp_gemm_args g = gemm_base(d, T, 3 * a, h);
+      stp_gemm_args g = gemm_base(d, T, stp_qkv_width(d), h);
       g.A = f.p[STP_ST_X_LN]; g.lda = h;
-      g.B = w->w_qkv; g.ldb = 3 * a;
-      g.C = f.p[STP_ST_QKV]; g.ldc = 3 * a;
+      g.B = w->w_qkv; g.ldb = stp_qkv_width(d);
+      g.C = f.p[STP_ST_QKV]; g.ldc = stp_qkv_width(d);
       g.bias = bias ? w->b_qkv : nullptr;
       RET_IF(stp_gemm(ctx, &g, hip_stream));
       if (d->rope) RET_IF(stp_rope(ctx, d, f.p[STP_ST_QKV], 0, hip_stream));
@@ -397,9 +398,9 @@ extern "C" int stp_backward_input_unit(stp_ctx *ctx, const stp_layer_desc *d, in
       RET_IF(stp_attention_backward(ctx, d, f.p[STP_ST_QKV], f.p[STP_ST_CTX], (const float *)f.p[STP_ST_LSE],
                                     f.p[STP_ST_DCTX], (float *)f.p[STP_ST_DELTA], f.p[STP_ST_DQKV], lane, hip_stream));
       if (d->rope) RET_IF(stp_rope(ctx, d, f.p[STP_ST_DQKV], 1, hip_stream));
-      g = gemm_base(d, T, h, 3 * a);
-      g.A = f.p[STP_ST_DQKV]; g.lda = 3 * a;
-      g.B = w->w_qkv; g.ldb = 3 * a; g.b_trans = 1;
+      g = gemm_base(d, T, h, stp_qkv_width(d));
+      g.A = f.p[STP_ST_DQKV]; g.lda = stp_qkv_width(d);
+      g.B = w->w_qkv; g.ldb = stp_qkv_width(d); g.b_trans = 1;
       g.C = dx; g.ldc = h;
       return stp_gemm(ctx, &g, hip_stream);
     }
@@ -439,9 +440,9 @@ extern "C" int stp_backward_weight_unit(stp_ctx *ctx, const stp_layer_desc *d, i
     return STP_OK;
   }
   RET_IF(wgemm(f.p[STP_ST_CTX], a, dy, h, wg->w_o));
-  RET_IF(wgemm(f.p[STP_ST_X_LN], h, f.p[STP_ST_DQKV], 3 * a, wg->w_qkv));
+  RET_IF(wgemm(f.p[STP_ST_X_LN], h, f.p[STP_ST_DQKV], stp_qkv_width(d), wg->w_qkv));
   if (d->has_bias) {
-    if (wg->b_qkv) RET_IF(stp_colsum(ctx, d->dtype, T, 3 * a, f.p[STP_ST_DQKV], 1.0f, wg->b_qkv, lane, hip_stream));
+    if (wg->b_qkv) RET_IF(stp_colsum(ctx, d->dtype, T, stp_qkv_width(d), f.p[STP_ST_DQKV], 1.0f, wg->b_qkv, lane, hip_stream));
     if (wg->b_o) RET_IF(stp_colsum(ctx, d->dtype, T, h, dy, inv_t, wg->b_o, lane, hip_stream));
   }
   return STP_OK;

@@ -35,10 +35,16 @@ class Workload:
     has_bias: bool = True
     eps: float = 1e-5
     rope_base: float = 10000.0
+    kv_heads: int = 0        # key / value heads on this rank (grouped-query attention); 0 = heads_local
 
     @property
     def attn_local(self) -> int:
         return self.heads_local * self.head_dim
+
+    @property
+    def qkv_local(self) -> int:
+        """Width of the rank's QKV activation: Q heads, then K heads, then V heads."""
+        return (self.heads_local + 2 * (self.kv_heads or self.heads_local)) * self.head_dim
 
 
 WORKLOADS = {
@@ -53,6 +59,10 @@ WORKLOADS = {
     "gpt7b_tp8_s4096": Workload("gpt7b_tp8_s4096", 4096, 4, 128, 2048, 4096, 8),
     # ViT encoder layer, unsharded, bidirectional
     "vit": Workload("vit", 1024, 16, 64, 4096, 1024, 1, causal=False),
+    # layer with the head counts of the 12.1B model of Section 5.1 (40 query / 8 key-value heads, hidden 5120),
+    # TP=4 shard: 10 query heads over 2 key / value heads; the FFN width is not given in the paper (synthetic)
+    "gqa12b_tp4": Workload("gqa12b_tp4", 5120, 10, 128, 3456, 4096, 4, norm="rms", act="swiglu", rope=True,
+                           has_bias=False, kv_heads=2),
 }
 
 
@@ -90,14 +100,15 @@ WEIGHT_KEYS = ("norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
 
 def weight_shapes(wl: Workload) -> dict:
     h, a, f = wl.hidden, wl.attn_local, wl.ffn_local
-    shp = {"norm1_g": (h,), "norm2_g": (h,), "w_qkv": (h, 3 * a), "w_o": (a, h),
+    c = wl.qkv_local
+    shp = {"norm1_g": (h,), "norm2_g": (h,), "w_qkv": (h, c), "w_o": (a, h),
            "w_fc1": (h, f), "w_fc2": (f, h)}
     if wl.norm == "ln":
         shp.update(norm1_b=(h,), norm2_b=(h,))
     if wl.act == "swiglu":
         shp["w_up"] = (h, f)
     if wl.has_bias:
-        shp.update(b_qkv=(3 * a,), b_o=(h,), b_fc1=(f,), b_fc2=(h,))
+        shp.update(b_qkv=(c,), b_o=(h,), b_fc1=(f,), b_fc2=(h,))
     return shp
 
 

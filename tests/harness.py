@@ -35,7 +35,7 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
 def oracle_cfg(wl: synth.Workload) -> O.LayerCfg:
     return O.LayerCfg(hidden=wl.hidden, heads_local=wl.heads_local, head_dim=wl.head_dim, ffn_local=wl.ffn_local,
                       tp=wl.tp, norm=wl.norm, act=wl.act, causal=wl.causal, rope=wl.rope, has_bias=wl.has_bias,
-                      eps=wl.eps, rope_base=wl.rope_base)
+                      eps=wl.eps, rope_base=wl.rope_base, kv_heads_local=wl.kv_heads)
 
 
 TOL = {"f32": 1e-5, "bf16": 2e-2}

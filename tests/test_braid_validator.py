@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header():
-    assert C.sizeof(stp.LayerDesc) == 15 * 4
+    assert C.sizeof(stp.LayerDesc) == 16 * 4
     assert C.sizeof(stp.Weights) == 13 * 8 and C.sizeof(stp.WGrads) == 13 * 8
     assert C.sizeof(stp.Op) == 16 and C.sizeof(stp.Stash) == 16
     assert C.sizeof(stp.Stage) == 8 + 9 * 8

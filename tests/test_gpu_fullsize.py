@@ -15,7 +15,7 @@ from oracle import stp_oracle as O
 from harness import TOL, oracle_cfg, oracle_layer_pass, rel_err, to_host
 
 
-@pytest.mark.parametrize("name", ["gpt7b_tp8", "llama13b_tp4", "vit"])
+@pytest.mark.parametrize("name", ["gpt7b_tp8", "llama13b_tp4", "vit", "gqa12b_tp4"])
 def test_full_size_braided_block_matches_oracle(name):
     wl = synth.WORKLOADS[name]
     tol = TOL[wl.dtype]

@@ -195,25 +195,27 @@ def test_rope(ctx, dtype, seq, mbsz, n, d):
     if dtype == "bf16" and d not in (64, 128):
         pytest.skip("bf16 layers take head_dim 64 or 128")
     rng = np.random.default_rng(seq)
-    a = n * d
     T = seq * mbsz
-    x = q(rng.standard_normal((T, 3 * a), dtype=np.float32), dtype)
-    xd = to_dev(x, dtype)
-    wl = synth.Workload("r", 64, n, d, 64, seq, 1, dtype=dtype, rope=True)
-    desc = stp.make_desc(wl, mbsz=mbsz)
-    for inverse in (False, True):
-        buf = xd.clone()
-        ctx.rope(desc, buf, inverse=inverse)
-        torch.cuda.synchronize()
-        got = to_host(buf)
-        ref = x.astype(np.float64).copy()
-        for b in range(mbsz):
-            rows = slice(b * seq, (b + 1) * seq)
-            for part in (0, 1):
-                blk = ref[rows, part * a:(part + 1) * a].reshape(seq, n, d)
-                ref[rows, part * a:(part + 1) * a] = O.rope(blk, 10000.0, inverse).reshape(seq, a)
-        assert rel_err(got, ref) < (8e-3 if dtype == "bf16" else 3e-6)
-        np.testing.assert_array_equal(got[:, 2 * a:], x[:, 2 * a:])  # V untouched
+    for nk in (0, 1):                      # one key / value head per query head, and a single shared one
+        nkv = nk or n
+        a, ak = n * d, nkv * d
+        x = q(rng.standard_normal((T, a + 2 * ak), dtype=np.float32), dtype)
+        xd = to_dev(x, dtype)
+        wl = synth.Workload("r", 64, n, d, 64, seq, 1, dtype=dtype, rope=True, kv_heads=nk)
+        desc = stp.make_desc(wl, mbsz=mbsz)
+        for inverse in (False, True):
+            buf = xd.clone()
+            ctx.rope(desc, buf, inverse=inverse)
+            torch.cuda.synchronize()
+            got = to_host(buf)
+            ref = x.astype(np.float64).copy()
+            for b in range(mbsz):
+                rows = slice(b * seq, (b + 1) * seq)
+                for lo, heads in ((0, n), (a, nkv)):      # the Q heads, then the K heads
+                    blk = ref[rows, lo:lo + heads * d].reshape(seq, heads, d)
+                    ref[rows, lo:lo + heads * d] = O.rope(blk, 10000.0, inverse).reshape(seq, heads * d)
+            assert rel_err(got, ref) < (8e-3 if dtype == "bf16" else 3e-6)
+            np.testing.assert_array_equal(got[:, a + ak:], x[:, a + ak:])  # V untouched
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -229,21 +231,27 @@ def test_colsum(ctx, dtype, T, N):
 
 
 # ------------------------------------------------------------------ attention core
-ATTN_CASES = [("f32", 128, 1, 4, 64, True), ("f32", 52, 2, 2, 32, False), ("f32", 72, 1, 1, 128, True),
-              ("bf16", 128, 1, 2, 128, True), ("bf16", 200, 1, 3, 128, True), ("bf16", 456, 2, 2, 64, True),
-              ("bf16", 328, 1, 2, 64, False), ("bf16", 1000, 1, 1, 128, False), ("bf16", 8, 1, 1, 128, True),
-              # longer than one 1024-key / 1024-query chunk: the chunk partials and combine kernels
-              ("bf16", 2568, 1, 1, 128, True), ("bf16", 1288, 2, 2, 64, False), ("bf16", 2104, 1, 1, 64, True)]
+# (dtype, seq, mbsz, query heads, head dim, causal, key / value heads; 0 = one per query head)
+ATTN_CASES = [("f32", 128, 1, 4, 64, True, 0), ("f32", 52, 2, 2, 32, False, 0), ("f32", 72, 1, 1, 128, True, 0),
+              ("bf16", 128, 1, 2, 128, True, 0), ("bf16", 200, 1, 3, 128, True, 0), ("bf16", 456, 2, 2, 64, True, 0),
+              ("bf16", 328, 1, 2, 64, False, 0), ("bf16", 1000, 1, 1, 128, False, 0), ("bf16", 8, 1, 1, 128, True, 0),
+              # longer than one chunk of keys / queries: the chunk partials and combine kernels
+              ("bf16", 2568, 1, 1, 128, True, 0), ("bf16", 1288, 2, 2, 64, False, 0), ("bf16", 2104, 1, 1, 64, True, 0),
+              ("bf16", 4360, 1, 1, 128, True, 0),
+              # grouped-query attention: groups of 2, 3 and 5 query heads per key / value head
+              ("f32", 96, 2, 4, 32, True, 2), ("bf16", 264, 1, 6, 128, True, 2), ("bf16", 520, 2, 4, 64, False, 2),
+              ("bf16", 1160, 1, 5, 128, True, 1)]
 
 
-@pytest.mark.parametrize("dtype,seq,mbsz,n,d,causal", ATTN_CASES)
-def test_attention_forward_backward(ctx, dtype, seq, mbsz, n, d, causal):
+@pytest.mark.parametrize("dtype,seq,mbsz,n,d,causal,nk", ATTN_CASES)
+def test_attention_forward_backward(ctx, dtype, seq, mbsz, n, d, causal, nk):
     rng = np.random.default_rng(seq * 3 + d)
-    a, T = n * d, seq * mbsz
-    qkv = q(rng.standard_normal((T, 3 * a), dtype=np.float32), dtype)
+    nkv = nk or n
+    a, ak, T = n * d, nkv * d, seq * mbsz
+    qkv = q(rng.standard_normal((T, a + 2 * ak), dtype=np.float32), dtype)
     dctx = q(rng.standard_normal((T, a), dtype=np.float32), dtype)
     qkvd, dctxd = to_dev(qkv, dtype), to_dev(dctx, dtype)
-    wl = synth.Workload("a", 64, n, d, 64, seq, 1, dtype=dtype, causal=causal)
+    wl = synth.Workload("a", 64, n, d, 64, seq, 1, dtype=dtype, causal=causal, kv_heads=nk)
     desc = stp.make_desc(wl, mbsz=mbsz)
     out = torch.zeros((T, a), dtype=qkvd.dtype, device="cuda")
     lse = torch.zeros((mbsz, n, seq), dtype=torch.float32, device="cuda")
@@ -257,16 +265,16 @@ def test_attention_forward_backward(ctx, dtype, seq, mbsz, n, d, causal):
     got_o, got_d, got_l = to_host(out), to_host(dqkv), to_host(lse)
     for b in range(mbsz):
         rows = slice(b * seq, (b + 1) * seq)
-        Q, K, V = (q64[rows, i * a:(i + 1) * a].reshape(seq, n, d) for i in range(3))
+        Q = q64[rows, :a].reshape(seq, n, d)
+        K, V = (q64[rows, a + i * ak:a + (i + 1) * ak].reshape(seq, nkv, d) for i in range(2))
         ref = O.attention_fwd(Q, K, V, causal)
         assert rel_err(got_o[rows], ref.reshape(seq, a)) < tol
         dq, dk, dv = O.attention_bwd(Q, K, V, dctx.astype(np.float64)[rows].reshape(seq, n, d), causal)
-        ref_d = np.concatenate([x.reshape(seq, a) for x in (dq, dk, dv)], axis=1)
-        for part, name in enumerate("qkv"):
-            sl = slice(part * a, (part + 1) * a)
+        ref_d = np.concatenate([dq.reshape(seq, a), dk.reshape(seq, ak), dv.reshape(seq, ak)], axis=1)
+        for name, sl in (("q", slice(0, a)), ("k", slice(a, a + ak)), ("v", slice(a + ak, a + 2 * ak))):
             assert rel_err(got_d[rows, sl], ref_d[:, sl]) < tol, name
         for hd in range(n):  # log-sum-exp of the scaled, masked scores
-            S = Q[:, hd] @ K[:, hd].T / math.sqrt(d)
+            S = Q[:, hd] @ K[:, hd // (n // nkv)].T / math.sqrt(d)
             if causal:
                 S = np.where(np.tril(np.ones((seq, seq), bool)), S, -np.inf)
             mx = S.max(1)

@@ -20,6 +20,9 @@ CASES = {
     "llama_fp32": Workload("llama_fp32", 128, 2, 32, 200, 72, 4, dtype="f32", norm="rms", act="swiglu", rope=True,
                            has_bias=False),
     "gpt_fp32_tp2": Workload("gpt_fp32_tp2", 64, 2, 16, 96, 40, 2, dtype="f32"),
+    # grouped-query attention: 6 query heads over 2 key / value heads (bf16), 4 over 1 (fp32, with biases)
+    "gqa_bf16": Workload("gqa_bf16", 512, 6, 128, 712, 264, 4, norm="rms", act="swiglu", rope=True, has_bias=False, kv_heads=2),
+    "gqa_fp32": Workload("gqa_fp32", 96, 4, 32, 136, 56, 8, dtype="f32", rope=True, kv_heads=1),
 }
 
 
@@ -45,7 +48,7 @@ def test_units_match_oracle(ctx, name):
     errs = {}
     for k in ("x_attn", "x_out", "dz", "dx_attn", "dx_ln", "dx"):
         errs[k] = rel_err(to_host(got[k]), ref[k])
-    qkv_ref = np.concatenate([st[k].reshape(T, a) for k in ("q", "k", "v")], axis=1)
+    qkv_ref = np.concatenate([st[k].reshape(T, -1) for k in ("q", "k", "v")], axis=1)
     stash_checks = {"X_LN": st["x_ln"], "QKV": qkv_ref, "CTX": st["ctx"], "Z_LN": st["z_ln"], "H": st["h"],
                     "G": st["g"], "DH": st["dh"], "DQKV": st["dqkv"]}
     if wl.act == "swiglu":
