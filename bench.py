@@ -34,7 +34,7 @@ def unit_flops(wl):
     T, h, a, f = wl.seq, wl.hidden, wl.attn_local, wl.ffn_local
     pairs = T * (T + 1) // 2 if wl.causal else T * T
     n_in = 2 if wl.act == "swiglu" else 1
-    qkv, outp = 2 * T * h * 3 * a, 2 * T * a * h
+    qkv, outp = 2 * T * h * wl.qkv_local, 2 * T * a * h      # QKV width: Q heads + 2 x key / value heads
     fc1, fc2 = n_in * 2 * T * h * f, 2 * T * f * h
     F = qkv + 4 * a * pairs + outp + fc1 + fc2
     B = fc2 + fc1 + outp + 8 * a * pairs + qkv
@@ -61,7 +61,7 @@ def gemm_leg(ctx, wl, reps, torch, stp):
     T, h, a, f = wl.seq, wl.hidden, wl.attn_local, wl.ffn_local
     td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     code = stp.BF16 if wl.dtype == "bf16" else stp.F32
-    shapes = [(T, 3 * a, h), (T, h, a), (T, f, h), (T, h, f)]
+    shapes = [(T, wl.qkv_local, h), (T, h, a), (T, f, h), (T, h, f)]
     bufs = []
     for (M, N, K) in shapes:
         A = torch.randn((M, K), device="cuda").to(td)
@@ -305,7 +305,7 @@ def main():
         from oracle import stp_oracle as O
         cfg = O.LayerCfg(hidden=h, heads_local=wl.heads_local, head_dim=wl.head_dim, ffn_local=f, tp=wl.tp,
                          norm=wl.norm, act=wl.act, causal=wl.causal, rope=wl.rope, has_bias=wl.has_bias,
-                         eps=wl.eps, rope_base=wl.rope_base)
+                         eps=wl.eps, rope_base=wl.rope_base, kv_heads_local=wl.kv_heads)
         W64 = {k: v.astype(np.float64) for k, v in stg.w_host[0].items()}
         X = synth.make_activation(wl, 0, "x.mb0").astype(np.float64)
         dO = synth.make_activation(wl, 0, "dy.mb0").astype(np.float64)
