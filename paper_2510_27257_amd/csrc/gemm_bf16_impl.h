@@ -4,11 +4,14 @@
 // Serves every dense contraction of the units (QKV, out-proj, FC1, FC2 in F; their
 // transposed-weight forms in B; the token-contracting forms in W).
 //
-// Design (gfx950):
-//   * one workgroup = WAVES_M x WAVES_N waves (2 x 4 for the 256 x 256 tile: two waves per SIMD, so one
-//     wave's LDS waits and barrier stalls are covered by the other's MFMAs), block tile BM x BN x 64,
-//     each wave owns a (BM/WAVES_M) x (BN/WAVES_N) sub-tile as a grid of 32x32 accumulators fed by
-//     v_mfma_f32_32x32x16_bf16;
+// Two kernels share the fragment scheme, the tile map and the epilogue:
+//   * gemm_bf16_dma_kernel (further down): direct-to-LDS loads, 4-stage ring of 32-deep K-tiles, the path of
+//     every problem with K a multiple of 32;
+//   * gemm_bf16_kernel: the fallback for any K and for operands of 2 GiB and more, described here.
+//
+// Fallback design (gfx950):
+//   * one workgroup = WAVES_M x WAVES_N waves, block tile BM x BN x 64, each wave owns a
+//     (BM/WAVES_M) x (BN/WAVES_N) sub-tile as a grid of 32x32 accumulators fed by v_mfma_f32_32x32x16_bf16;
 //   * global -> registers -> LDS with two LDS stages: the loads of K-tile kt+1 are in
 //     flight while the MFMAs of K-tile kt run, one barrier per K-tile;
 //   * an operand whose contraction index is contiguous in memory sits in LDS as
