@@ -110,6 +110,23 @@ def test_gemm_epilogues(ctx, dtype, tile):
     assert rel_err(to_host(C32), 0.5 + 2 * AB) < (3e-6 if dtype == "f32" else 1e-5)
 
 
+def test_gemm_operand_of_two_gib_takes_the_fallback_kernel(ctx):
+    """An A operand of 2 GiB or more cannot be addressed with the 32-bit offsets of the direct-to-LDS kernel; the
+    library must fall back to the register-staged kernel (K a multiple of 32, so only the size decides).
+    Checked on sampled rows, including the last ones (past the 2 GiB mark)."""
+    M, N, K = 264200, 64, 4096                      # A: 264200 x 4096 bf16 = 2.16 GB
+    g = torch.Generator(device="cuda").manual_seed(3)
+    A = torch.randn((M, K), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    Bm = (torch.randn((K, N), generator=g, device="cuda", dtype=torch.float32) * 0.05).to(torch.bfloat16)
+    Cd = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    ctx.gemm(stp.GemmArgs(dtype=stp.BF16, M=M, N=N, K=K, A=A.data_ptr(), lda=K, B=Bm.data_ptr(), ldb=N, C=Cd.data_ptr(),
+                          ldc=N, bias_scale=1.0, resid_scale=1.0))
+    torch.cuda.synchronize()
+    rows = [0, 1, 255, 256, 131071, 262143, 262144, 262145, M - 2, M - 1]
+    ref = to_host(A[rows]) @ to_host(Bm)
+    assert rel_err(to_host(Cd[rows]), ref) < 4e-3
+
+
 def test_gemm_rejects_bad_arguments(ctx):
     x = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
     ok = dict(dtype=stp.BF16, M=64, N=64, K=64, A=x.data_ptr(), lda=64, B=x.data_ptr(), ldb=64, C=x.data_ptr(), ldc=64)
@@ -126,7 +143,7 @@ def test_gemm_rejects_bad_arguments(ctx):
 # ------------------------------------------------------------------ norms
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("norm", ["ln", "rms"])
-@pytest.mark.parametrize("T,h", [(37, 256), (130, 4096), (64, 5120), (9, 1024), (5, 8), (600, 2056)])
+@pytest.mark.parametrize("T,h", [(37, 256), (130, 4096), (64, 5120), (9, 1024), (5, 8), (600, 2056), (24, 8192)])
 def test_norm_forward_backward(ctx, dtype, norm, T, h):
     rng = np.random.default_rng(T + h)
     cfg = O.LayerCfg(h, 1, 8, 8, norm=norm)
