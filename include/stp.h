@@ -93,7 +93,7 @@ typedef struct {
  * may be NULL (norm*_b for RMSNorm, b_* when has_bias = 0, w_up for GELU). */
 typedef struct {
   const void *norm1_g, *norm1_b; /* [h] */
-  const void *w_qkv, *b_qkv;     /* [h, 3a], [3a]   a = n*d */
+  const void *w_qkv, *b_qkv;     /* [h, c], [c]   c = (n + 2 n_kv) d: Q heads | K heads | V heads; a = n*d */
   const void *w_o, *b_o;         /* [a, h],  [h]   (row-parallel: bias enters as b_o/t) */
   const void *norm2_g, *norm2_b; /* [h] */
   const void *w_fc1, *b_fc1;     /* [h, f],  [f]   (SwiGLU: the gate projection) */
@@ -115,7 +115,7 @@ typedef struct { void *base; size_t bytes; } stp_stash;
 typedef enum {
   STP_ST_X_LN = 0,   /* [T, h]   Pre-Attn output                          */
   STP_ST_STATS1,     /* [T, 2]   fp32 (mean, rstd) of Pre-Attn            */
-  STP_ST_QKV,        /* [T, 3a]  Q|K|V after bias and RoPE                */
+  STP_ST_QKV,        /* [T, c]   Q|K|V after bias and RoPE                */
   STP_ST_CTX,        /* [T, a]   attention output before the out-proj     */
   STP_ST_LSE,        /* [mbsz, n, seq] fp32 log-sum-exp of the score rows */
   STP_ST_Z_LN,       /* [T, h]   Pre-MLP output                           */
@@ -126,7 +126,7 @@ typedef enum {
   STP_ST_DH,         /* [T, f]   written by MLP-B, read by MLP-W          */
   STP_ST_DHU,        /* [T, f]   SwiGLU only                              */
   STP_ST_DG,         /* [T, f]   scratch of MLP-B (SwiGLU only)           */
-  STP_ST_DQKV,       /* [T, 3a]  written by Attn-B, read by Attn-W        */
+  STP_ST_DQKV,       /* [T, c]   written by Attn-B, read by Attn-W        */
   STP_ST_DCTX,       /* [T, a]   scratch of Attn-B                        */
   STP_ST_DELTA,      /* [mbsz, n, seq] fp32 rowsum(dctx * ctx)            */
   STP_ST_X_ATTN,     /* [T, h]   used by stp_braid_step: Attn output      */
@@ -265,11 +265,13 @@ int stp_norm_backward(stp_ctx *ctx, int dtype, int norm, int32_t T, int32_t h, c
                       const void *gamma, const float *stats, const void *dy, const void *d_resid,
                       void *dx, float *dgamma, float *dbeta, int lane, void *hip_stream);
 
-/* Attention core of one rank: qkv is [T, 3a] (Q|K|V), ctx [T,a], lse fp32 [mbsz,n,seq].  The bf16 kernels
- * cut the key range into chunks whose fp32 partials live in workspace lane `lane` (0..2). */
+/* Attention core of one rank: qkv is [T, (n + 2 n_kv) d] (n Q heads | n_kv K heads | n_kv V heads; n_kv = n
+ * unless desc->kv_heads_local is set), ctx [T, n d], lse fp32 [mbsz,n,seq].  The bf16 kernels cut the key
+ * range into chunks whose fp32 partials live in workspace lane `lane` (0..2), and address a sequence's QKV
+ * rows with 32-bit byte offsets: seq * (n + 2 n_kv) * d * 2 bytes must stay below 2 GiB (STP_ESHAPE). */
 int stp_attention_forward(stp_ctx *ctx, const stp_layer_desc *desc, const void *qkv, void *ctx_out,
                           float *lse, int lane, void *hip_stream);
-/* dqkv [T,3a] from dctx [T,a]; delta is fp32 scratch [mbsz,n,seq]. */
+/* dqkv [T, (n + 2 n_kv) d] from dctx [T, n d]; delta is fp32 scratch [mbsz,n,seq]. */
 int stp_attention_backward(stp_ctx *ctx, const stp_layer_desc *desc, const void *qkv, const void *ctx_in,
                            const float *lse, const void *dctx, float *delta, void *dqkv, int lane,
                            void *hip_stream);
@@ -280,7 +282,7 @@ int stp_gelu_backward(stp_ctx *ctx, int dtype, size_t n, const void *x, const vo
 int stp_swiglu_forward(stp_ctx *ctx, int dtype, size_t n, const void *gate, const void *up, void *y, void *hip_stream);
 int stp_swiglu_backward(stp_ctx *ctx, int dtype, size_t n, const void *gate, const void *up, const void *dy,
                         void *dgate, void *dup, void *hip_stream);
-/* In-place rotary embedding of the Q and K thirds of qkv [T,3a]; inverse = 1 applies the transpose. */
+/* In-place rotary embedding of the Q and K heads of qkv [T, (n + 2 n_kv) d]; inverse = 1 applies the transpose. */
 int stp_rope(stp_ctx *ctx, const stp_layer_desc *desc, void *qkv, int inverse, void *hip_stream);
 /* out[N] += scale * sum over rows of x[T,N]  (bias gradients). */
 int stp_colsum(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const void *x, float scale, float *out,
