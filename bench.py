@@ -270,7 +270,7 @@ def main():
     hbm = hbm_leg(ctx, wl, torch, stp)
 
     result = {
-        "metric": "braided F/B/W TFLOP/s, 7B layer TP=8 shard, seq 6144, 1 GPU",
+        "metric": "braided F/B/W TFLOP/s + MFMA util, 7B layer TP=8 shard, seq 6144, 1 GPU",
         "value": total_flops / (ms_braided * 1e-3) / 1e12,
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
