@@ -144,6 +144,10 @@ def stage_bench(ctx, args, torch, stp, synth):
     steps = [(stp.Op * len(st))(*st) for st in stage_sequence(L, n_mb)]
     sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     s0 = torch.cuda.current_stream()
+    off = None
+    if args.offload_alpha is not None:
+        from paper_2510_27257_amd.stage import Offloader
+        off = Offloader(stg)          # its copy streams are created next to the compute streams
 
     def run(streams):
         ctx.braid_reset()
@@ -167,6 +171,37 @@ def stage_bench(ctx, args, torch, stp, synth):
             sum_iso += n_mb * time_steps(lambda: ctx.braid_step(stg.stage, ops, s0, s0, s0), 10, 2, torch)
         fl = unit_flops(layers[l])
         flops += n_mb * (fl["F"] + fl["B"] + fl["W"])
+    offload = None
+    if args.offload_alpha is not None:
+        # Section 4.2 / 4.3: a share alpha of the long-lived stashes goes to page-locked host memory on a copy
+        # stream and comes back before its consumer; the paper's condition is T_o < T_F per model chunk
+        from paper_2510_27257_amd.binding import OFFLOAD_FWD
+        from paper_2510_27257_amd.stage import run_sequence_with_offload
+        alpha = args.offload_alpha
+        moved = [0]
+
+        def run_off():
+            ctx.braid_reset()
+            moved[0] = run_sequence_with_offload(ctx, stg, steps, (sF, sB, sW), off, alpha,
+                                                 forward_stash=args.offload_sets in ("fwd", "both"),
+                                                 w_stash=args.offload_sets in ("w", "both"),
+                                                 min_gap=args.offload_min_gap)
+
+        ms_off = time_steps(run_off, reps, 1, torch)
+        # T_o: the forward stash of the whole chunk (all layers, one microbatch), copied alone
+        def copy_alone():
+            for l in range(L):
+                off.offload(l, 0, OFFLOAD_FWD, alpha, off.copy_stream)
+        ms_to = time_steps(copy_alone, 5, 1, torch)
+        f_all = (stp.Op * (4 * L))(*forward_ops(L, 0))
+        ms_tf = time_steps(lambda: ctx.braid_step(stg.stage, f_all, s0, s0, s0), 5, 1, torch)
+        chunk_bytes = sum(off.bytes(l, OFFLOAD_FWD, alpha) for l in range(L))
+        offload = {"alpha": alpha, "sets": args.offload_sets, "min_gap_steps": args.offload_min_gap,
+                   "makespan_ms": ms_off, "makespan_without_ms": ms_braided,
+                   "bytes_to_host_per_sequence": moved[0], "bytes_back_per_sequence": moved[0],
+                   "T_o_ms_forward_stash_of_chunk": ms_to, "T_F_ms_chunk": ms_tf,
+                   "d2h_GBps": chunk_bytes / ms_to / 1e6 if ms_to > 0 else None,
+                   "T_o_below_T_F": ms_to < ms_tf}
     print(json.dumps({
         "metric": "braided stage sequence TFLOP/s", "value": flops / (ms_braided * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": ms_braided, "higher_is_better": True,
@@ -174,7 +209,8 @@ def stage_bench(ctx, args, torch, stp, synth):
         "config": {"workload": f"stage {args.stage}: {L} layers x {n_mb} microbatches, sequence of {len(steps)} braided blocks",
                    "flops_per_step": flops},
         "braid": {"makespan_ms": ms_braided, "serialized_ms": ms_serial, "sum_isolated_ms": sum_iso,
-                  "makespan_over_sum_isolated": ms_braided / sum_iso}}))
+                  "makespan_over_sum_isolated": ms_braided / sum_iso},
+        "offload": offload}))
 
 
 def main():
@@ -188,6 +224,14 @@ def main():
                     help="time one pipeline stage's whole braided sequence instead of the single block: "
                          "pp4 = 4 GPT-7B TP=8 layers at seq 4096, 8 microbatches; mllm = 2 ViT layers + 2 such "
                          "LM layers, 8 microbatches")
+    ap.add_argument("--offload-alpha", type=float, default=None,
+                    help="with --stage: also time the sequence with a share alpha of the long-lived stashes "
+                         "offloaded to page-locked host memory and reloaded (reported under \"offload\")")
+    ap.add_argument("--offload-min-gap", type=int, default=1,
+                    help="move only stashes whose consumer is at least this many braid steps after their producer")
+    ap.add_argument("--offload-sets", choices=["w", "fwd", "both"], default="w",
+                    help="what --offload-alpha moves: the W-stashes of microbatches whose weight gradients are "
+                         "deferred (long-lived), the forward stashes (short-lived in a one-stage sequence), or both")
     ap.add_argument("--print-gemm", action="store_true", help="with --only-gemm: print the leg's result as JSON")
     ap.add_argument("--only-gemm", action="store_true",
                     help="run only the dominant-kernel leg plus a 1 GiB device copy (counter calibration runs)")
@@ -196,6 +240,12 @@ def main():
         print("bench.py: this build runs on ONE GPU only (the TP all-reduce points are marked boundaries, "
               "no collectives); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.offload_alpha is not None:
+        # The offload adds two copy streams to the three compute streams.  HIP maps a process's streams onto 4
+        # hardware queues by default, so a fifth stream shares a queue with a compute stream, and a reload that
+        # is enqueued ahead of time then sits behind every kernel already queued there.  Read at HIP start-up.
+        if int(os.environ.get("GPU_MAX_HW_QUEUES", "4")) < 8:
+            os.environ["GPU_MAX_HW_QUEUES"] = "8"
 
     import torch
     import paper_2510_27257_amd as stp

@@ -233,6 +233,34 @@ int stp_validate_ops(const stp_stage *stage, const stp_op *ops, size_t n_ops, si
 /* Forget which B units earlier steps have run (start of a new iteration). */
 int stp_braid_reset(stp_ctx *ctx);
 
+/* ---- activation offload and reload (Section 4.2, last paragraph; Section 4.3) --------------------
+ * The schedule keeps some stashed activations for a long time: those of a microbatch whose weight
+ * gradients are separated from its backward pass and deferred, and those of model chunk 0 between its
+ * forward and its backward pass.  A fraction alpha of them is copied to host memory on a copy stream, in
+ * parallel with the compute streams, and copied back before the unit that reads them.
+ *
+ * `set` names the group of stash fields:
+ *   STP_OFFLOAD_W_ATTN  what only Attn-W still reads once Attn-B has run:  X_LN, CTX, DQKV
+ *   STP_OFFLOAD_W_MLP   what only MLP-W still reads once MLP-B has run:    Z_LN, G, DH (DHU)
+ *   STP_OFFLOAD_FWD     what the forward units leave for the backward side:
+ *                       X_LN, STATS1, QKV, CTX, LSE, Z_LN, STATS2, H, (HU), G, X_ATTN
+ * Of every field of the set the leading ceil(alpha * bytes / 256) * 256 bytes (at most the field) move;
+ * their copies lie back to back in `host`, in the order above.  stp_offload_bytes gives their total.
+ *
+ * stp_stash_offload enqueues: s_copy waits for the work enqueued so far on s_producer, then device -> host
+ * copies on s_copy.  Once s_copy has passed them the moved device ranges are dead until reloaded and the
+ * caller may reuse them.  stp_stash_reload enqueues the host -> device copies on s_copy and makes
+ * s_consumer wait for them.  `host` is host memory of at least stp_offload_bytes bytes, owned by the
+ * caller, and must stay untouched between the two calls; it should be page-locked (hipHostMalloc),
+ * otherwise the copies do not overlap the compute streams.  alpha outside [0, 1], an unknown set, a NULL
+ * pointer or a host buffer that is too small: STP_EINVAL.  A failing HIP call: STP_EHIP. */
+typedef enum { STP_OFFLOAD_W_ATTN = 0, STP_OFFLOAD_W_MLP = 1, STP_OFFLOAD_FWD = 2 } stp_offload_set;
+int stp_offload_bytes(const stp_layer_desc *desc, int set, float alpha, size_t *bytes);
+int stp_stash_offload(stp_ctx *ctx, const stp_layer_desc *desc, int set, float alpha, const stp_stash *stash,
+                      void *host, size_t host_bytes, void *s_producer, void *s_copy);
+int stp_stash_reload(stp_ctx *ctx, const stp_layer_desc *desc, int set, float alpha, const stp_stash *stash,
+                     const void *host, size_t host_bytes, void *s_copy, void *s_consumer);
+
 /* ---- the kernels the units are built from, exposed for per-kernel parity and
  * roofline measurement.  All pointers are device pointers. ------------------ */
 

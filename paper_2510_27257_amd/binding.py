@@ -11,6 +11,7 @@ __all__ = [
     "Context", "BOUNDARY_FN", "make_desc", "EXPORTED_SYMBOLS",
     "PRE_ATTN", "ATTN", "PRE_MLP", "MLP", "OP_F", "OP_B", "OP_W", "OP_BW", "F32", "BF16",
     "NORM_LN", "NORM_RMS", "ACT_GELU", "ACT_SWIGLU", "STASH_FIELDS", "STATUS",
+    "OFFLOAD_W_ATTN", "OFFLOAD_W_MLP", "OFFLOAD_FWD", "offload_bytes",
 ]
 
 PRE_ATTN, ATTN, PRE_MLP, MLP = 0, 1, 2, 3
@@ -18,6 +19,7 @@ OP_F, OP_B, OP_W, OP_BW = 0, 1, 2, 3
 F32, BF16 = 0, 1
 NORM_LN, NORM_RMS = 0, 1
 ACT_GELU, ACT_SWIGLU = 0, 1
+OFFLOAD_W_ATTN, OFFLOAD_W_MLP, OFFLOAD_FWD = 0, 1, 2
 STATUS = {0: "STP_OK", 1: "STP_EINVAL", 2: "STP_ESHAPE", 3: "STP_EALIGN", 4: "STP_ENOSPACE",
           5: "STP_ESEQ", 6: "STP_EUNSUPPORTED", 7: "STP_EHIP"}
 STASH_FIELDS = ["X_LN", "STATS1", "QKV", "CTX", "LSE", "Z_LN", "STATS2", "H", "HU", "G", "DH", "DHU", "DG",
@@ -30,6 +32,7 @@ EXPORTED_SYMBOLS = [
     "stp_braid_reset", "stp_gemm", "stp_norm_forward", "stp_norm_backward", "stp_attention_forward",
     "stp_attention_backward", "stp_gelu_forward", "stp_gelu_backward", "stp_swiglu_forward",
     "stp_swiglu_backward", "stp_rope", "stp_colsum", "stp_clock_probe",
+    "stp_offload_bytes", "stp_stash_offload", "stp_stash_reload",
 ]
 
 
@@ -136,6 +139,9 @@ def lib() -> C.CDLL:
     L.stp_rope.argtypes = [vp, P(LayerDesc), vp, C.c_int, vp]
     L.stp_colsum.argtypes = [vp, C.c_int, i32, i32, vp, f32, vp, C.c_int, vp]
     L.stp_clock_probe.argtypes = [vp, vp, C.c_double, vp]
+    L.stp_offload_bytes.argtypes = [P(LayerDesc), C.c_int, f32, P(sz)]
+    L.stp_stash_offload.argtypes = [vp, P(LayerDesc), C.c_int, f32, P(Stash), vp, sz, vp, vp]
+    L.stp_stash_reload.argtypes = [vp, P(LayerDesc), C.c_int, f32, P(Stash), vp, sz, vp, vp]
     for name in EXPORTED_SYMBOLS:
         fn = getattr(L, name)
         if fn.restype is C.c_int or fn.restype is None or fn.restype == C.c_int:
@@ -172,6 +178,15 @@ def _stream(s) -> Optional[int]:
     if isinstance(s, int):
         return s
     return s.cuda_stream
+
+
+def offload_bytes(desc: "LayerDesc", which: int, alpha: float) -> int:
+    """Host bytes stp_stash_offload moves for this layer, field set and fraction (no GPU needed)."""
+    n = C.c_size_t()
+    rc = lib().stp_offload_bytes(C.byref(desc), which, alpha, C.byref(n))
+    if rc != 0:
+        raise StpError(rc, "stp_offload_bytes")
+    return n.value
 
 
 class Context:
@@ -304,6 +319,17 @@ class Context:
 
     def rope(self, desc, qkv, inverse=False, stream=None):
         self.check(self._lib.stp_rope(self._h, C.byref(desc), _ptr(qkv), int(inverse), _stream(stream)), "stp_rope")
+
+    def stash_offload(self, desc, which, alpha, stash, host, s_producer, s_copy):
+        """host: page-locked CPU uint8 tensor of at least offload_bytes(desc, which, alpha) bytes."""
+        self.check(self._lib.stp_stash_offload(self._h, C.byref(desc), which, alpha, C.byref(stash), host.data_ptr(),
+                                               host.numel() * host.element_size(), _stream(s_producer), _stream(s_copy)),
+                   "stp_stash_offload")
+
+    def stash_reload(self, desc, which, alpha, stash, host, s_copy, s_consumer):
+        self.check(self._lib.stp_stash_reload(self._h, C.byref(desc), which, alpha, C.byref(stash), host.data_ptr(),
+                                              host.numel() * host.element_size(), _stream(s_copy), _stream(s_consumer)),
+                   "stp_stash_reload")
 
     def clock_probe(self, out2, milliseconds, stream=None):
         """out2: int64 device tensor with 2 elements -> (shader cycles, wall ticks at 100 MHz-class rate)."""

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libstp.so")
 SOURCES = ["elementwise.hip", "gemm_bf16.hip", "gemm_bf16_kk.hip", "gemm_bf16_kn.hip", "gemm_bf16_mk.hip", "gemm_bf16_mn.hip", "gemm_f32.hip", "attn_generic.hip", "attn_bf16.hip", "attn_bwd_bf16.hip",
-           "units.hip", "braid.hip"]
+           "units.hip", "braid.hip", "offload.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",

@@ -29,6 +29,10 @@ struct stp_ctx {
   uint8_t *b_done;
   size_t b_done_size;
   int b_layers, b_mbs;
+  // events that order the copy stream of the activation offload against its producer / consumer streams
+  // (a stream wait refers to the record that precedes it, so the ring may wrap)
+  hipEvent_t ev_copy[16];
+  int ev_copy_made, ev_copy_next;
 };
 
 static inline int stp_fail(stp_ctx *ctx, int status, const char *fmt, const char *a = "", long b = 0, long c = 0) {

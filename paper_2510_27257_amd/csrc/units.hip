@@ -41,6 +41,7 @@ extern "C" int stp_destroy(stp_ctx *ctx) {
   if (ctx->have_step_events)
     for (int i = 0; i < 3; i++) (void)hipEventDestroy(ctx->ev_step[i]);
   for (int i = 0; i < ctx->ev_pool_size; i++) (void)hipEventDestroy(ctx->ev_pool[i]);
+  for (int i = 0; i < ctx->ev_copy_made; i++) (void)hipEventDestroy(ctx->ev_copy[i]);
   free(ctx->ev_pool);
   free(ctx->b_done);
   delete ctx;

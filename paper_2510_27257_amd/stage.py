@@ -130,6 +130,116 @@ class StageOnDevice:
                 v.zero_()
 
 
+class Offloader:
+    """Page-locked host buffers and the two copy streams (device -> host, host -> device: the link is full
+    duplex) for the activation offload of one stage (Section 4.2, last paragraph; Section 4.3).  Buffers are
+    allocated on first use and kept."""
+
+    def __init__(self, stg: StageOnDevice):
+        self.stg = stg
+        self.copy_stream = torch.cuda.Stream()      # device -> host
+        self.reload_stream = torch.cuda.Stream()    # host -> device
+        self.host, self.alpha, self.done = {}, {}, {}
+
+    def bytes(self, l: int, which: int, alpha: float) -> int:
+        return B.offload_bytes(self.stg.descs[l], which, alpha)
+
+    def offload(self, l: int, mb: int, which: int, alpha: float, s_producer) -> int:
+        """Enqueues the device -> host copies behind the work already on s_producer; returns the bytes moved."""
+        n = self.bytes(l, which, alpha)
+        key = (l, mb, which)
+        buf = self.host.get(key)
+        if buf is None or buf.numel() < n:
+            buf = torch.empty(max(n, 1), dtype=torch.uint8, pin_memory=True)
+            self.host[key] = buf
+        self.alpha[key] = alpha
+        self.stg.ctx.stash_offload(self.stg.descs[l], which, alpha, self.stg.stash_arr[l * self.stg.n_mb + mb], buf,
+                                   s_producer, self.copy_stream)
+        ev = self.done.get(key)
+        if ev is None:
+            ev = self.done[key] = torch.cuda.Event()
+        ev.record(self.copy_stream)
+        return n
+
+    def reload(self, l: int, mb: int, which: int, s_consumer) -> None:
+        """Enqueues the host -> device copies behind the offload of the same stash; s_consumer waits for them."""
+        key = (l, mb, which)
+        self.reload_stream.wait_event(self.done[key])
+        self.stg.ctx.stash_reload(self.stg.descs[l], which, self.alpha[key], self.stg.stash_arr[l * self.stg.n_mb + mb],
+                                  self.host[key], self.reload_stream, s_consumer)
+
+
+def plan_offload(steps, n_mb: int, forward_stash: bool = True, w_stash: bool = True, min_gap: int = 1):
+    """Host-side plan of the offload policy of Section 4.2 / 4.3 for a list of braid steps (each a list of ops).
+
+    The W-stash of a microbatch whose weight gradients are separated (B in one step, W in a later one) leaves
+    the device right after its B and returns for its W; the forward stash of a microbatch leaves after the step
+    that holds its F (unless its B is in the same step) and returns for the step that holds its B.  Only a
+    stash whose consumer is at least `min_gap` steps after its producer is moved: the trip to the host and back
+    has to fit into that lifespan, or the consumer waits for it (the paper's T_o < T_F condition).  A reload is
+    enqueued one step ahead of its consumer, so that the copy runs under the step before.
+
+    Returns (before, after): per step index the lists of ("reload", kind, mb) to enqueue before the step is
+    issued and of ("offload" | "reload", kind, mb) to enqueue after it, kind in {"fwd", "w"}."""
+    kinds = [{(o.kind, o.microbatch) for o in st} for st in steps]
+    n = len(steps)
+    before, after = [[] for _ in range(n)], [[] for _ in range(n)]
+
+    def consumer(si, mb, consumer_kinds):
+        for sj in range(si + 1, n):
+            if any((k, mb) in kinds[sj] for k in consumer_kinds):
+                return sj
+        return None
+
+    for si in range(n):
+        for mb in range(n_mb):
+            moves = []
+            if forward_stash and (B.OP_F, mb) in kinds[si] and (B.OP_B, mb) not in kinds[si] \
+                    and (B.OP_BW, mb) not in kinds[si]:
+                moves.append(("fwd", consumer(si, mb, (B.OP_B, B.OP_BW))))
+            if w_stash and (B.OP_B, mb) in kinds[si]:
+                moves.append(("w", consumer(si, mb, (B.OP_W,))))
+            for kind, sj in moves:
+                if sj is None or sj - si < max(min_gap, 1):
+                    continue
+                after[si].append(("offload", kind, mb))
+                # one step ahead of the consumer; right behind the offload if the consumer is the next step
+                after[sj - 1].append(("reload", kind, mb))
+    return before, after
+
+
+def run_sequence_with_offload(ctx: B.Context, stg: StageOnDevice, steps, streams, off: Offloader, alpha: float,
+                              forward_stash: bool = True, w_stash: bool = True, min_gap: int = 1) -> int:
+    """Issues the braid steps of a stage sequence with the moves plan_offload lists.  Returns the bytes copied
+    device -> host (the same number returns)."""
+    L = len(stg.layers)
+    sF, sB, sW = streams
+    before, after = plan_offload(steps, stg.n_mb, forward_stash, w_stash, min_gap)
+    moved = 0
+
+    def do(action, kind, mb):
+        nonlocal moved
+        for l in reversed(range(L)):                    # the backward side starts at the last layer
+            if action == "offload" and kind == "fwd":
+                moved += off.offload(l, mb, B.OFFLOAD_FWD, alpha, sF)
+            elif action == "offload":
+                moved += off.offload(l, mb, B.OFFLOAD_W_MLP, alpha, sB)
+                moved += off.offload(l, mb, B.OFFLOAD_W_ATTN, alpha, sB)
+            elif kind == "fwd":
+                off.reload(l, mb, B.OFFLOAD_FWD, sB)
+            else:
+                off.reload(l, mb, B.OFFLOAD_W_MLP, sW)
+                off.reload(l, mb, B.OFFLOAD_W_ATTN, sW)
+
+    for si, step in enumerate(steps):
+        for m in before[si]:
+            do(*m)
+        ctx.braid_step(stg.stage, step, sF, sB, sW)
+        for m in after[si]:
+            do(*m)
+    return moved
+
+
 # ---- op lists -------------------------------------------------------------------
 def forward_ops(n_layers: int, mb: int) -> List[B.Op]:
     return [B.Op(B.OP_F, u, l, mb) for l in range(n_layers) for u in (B.PRE_ATTN, B.ATTN, B.PRE_MLP, B.MLP)]
