@@ -141,7 +141,17 @@ def stage_bench(ctx, args, torch, stp, synth):
     stg = StageOnDevice(ctx, layers, n_mb, seed=0, chain_break=cb)
     stg.load_inputs()
     L = len(layers)
-    steps = [(stp.Op * len(st))(*st) for st in stage_sequence(L, n_mb)]
+    if args.pattern:
+        from paper_2510_27257_amd.stage import two_chunk_sequence
+        first1 = cb.index(1) if cb and 1 in cb else L // 2          # chunk 1 starts at the chain break
+        step_lists = two_chunk_sequence(L, first1, n_mb, args.pattern)
+        seq_name = f"two chunks (layers 0-{first1 - 1} | {first1}-{L - 1}), pairing pattern {args.pattern}"
+    else:
+        step_lists = stage_sequence(L, n_mb, warmup=args.stage_warmup)
+        seq_name = f"three-phase sequence, {args.stage_warmup} forward pass(es) before the first backward"
+    from paper_2510_27257_amd.stage import peak_in_flight
+    peak = peak_in_flight(step_lists, L)
+    steps = [(stp.Op * len(st))(*st) for st in step_lists]
     sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     s0 = torch.cuda.current_stream()
     off = None
@@ -207,7 +217,7 @@ def stage_bench(ctx, args, torch, stp, synth):
         "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": ms_braided, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"stage {args.stage}: {L} layers x {n_mb} microbatches, sequence of {len(steps)} braided blocks",
-                   "flops_per_step": flops},
+                   "sequence": seq_name, "peak_layer_stashes_in_flight": peak, "flops_per_step": flops},
         "braid": {"makespan_ms": ms_braided, "serialized_ms": ms_serial, "sum_isolated_ms": sum_iso,
                   "makespan_over_sum_isolated": ms_braided / sum_iso},
         "offload": offload}))
@@ -224,6 +234,12 @@ def main():
                     help="time one pipeline stage's whole braided sequence instead of the single block: "
                          "pp4 = 4 GPT-7B TP=8 layers at seq 4096, 8 microbatches; mllm = 2 ViT layers + 2 such "
                          "LM layers, 8 microbatches")
+    ap.add_argument("--stage-warmup", type=int, default=1,
+                    help="with --stage: forward passes in flight before the first backward pass (1 = memory-efficient "
+                         "warm-up, more = throughput-efficient warm-up)")
+    ap.add_argument("--pattern", type=int, choices=[1, 2], default=None,
+                    help="with --stage: treat the stage as two model chunks and pair forward and backward units of "
+                         "the same chunk (2) or of different chunks (1)")
     ap.add_argument("--offload-alpha", type=float, default=None,
                     help="with --stage: also time the sequence with a share alpha of the long-lived stashes "
                          "offloaded to page-locked host memory and reloaded (reported under \"offload\")")

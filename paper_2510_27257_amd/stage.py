@@ -241,16 +241,22 @@ def run_sequence_with_offload(ctx: B.Context, stg: StageOnDevice, steps, streams
 
 
 # ---- op lists -------------------------------------------------------------------
-def forward_ops(n_layers: int, mb: int) -> List[B.Op]:
-    return [B.Op(B.OP_F, u, l, mb) for l in range(n_layers) for u in (B.PRE_ATTN, B.ATTN, B.PRE_MLP, B.MLP)]
+def _layers(n_layers, layers):
+    return list(range(n_layers)) if layers is None else list(layers)
 
 
-def backward_ops(n_layers: int, mb: int, kind: int = B.OP_BW) -> List[B.Op]:
-    return [B.Op(kind, u, l, mb) for l in reversed(range(n_layers)) for u in (B.MLP, B.PRE_MLP, B.ATTN, B.PRE_ATTN)]
+def forward_ops(n_layers: int, mb: int, layers=None) -> List[B.Op]:
+    """F units of a microbatch over all layers of the stage, or over the given layers (one model chunk)."""
+    return [B.Op(B.OP_F, u, l, mb) for l in _layers(n_layers, layers) for u in (B.PRE_ATTN, B.ATTN, B.PRE_MLP, B.MLP)]
 
 
-def weight_ops(n_layers: int, mb: int) -> List[B.Op]:
-    return [B.Op(B.OP_W, u, l, mb) for l in reversed(range(n_layers)) for u in (B.MLP, B.ATTN)]
+def backward_ops(n_layers: int, mb: int, kind: int = B.OP_BW, layers=None) -> List[B.Op]:
+    return [B.Op(kind, u, l, mb) for l in reversed(_layers(n_layers, layers))
+            for u in (B.MLP, B.PRE_MLP, B.ATTN, B.PRE_ATTN)]
+
+
+def weight_ops(n_layers: int, mb: int, layers=None) -> List[B.Op]:
+    return [B.Op(B.OP_W, u, l, mb) for l in reversed(_layers(n_layers, layers)) for u in (B.MLP, B.ATTN)]
 
 
 def braid(f_ops: List[B.Op], b_ops: List[B.Op]) -> List[B.Op]:
@@ -278,26 +284,79 @@ def braid(f_ops: List[B.Op], b_ops: List[B.Op]) -> List[B.Op]:
     return out
 
 
-def stage_sequence(n_layers: int, n_mb: int) -> List[List[B.Op]]:
+def stage_sequence(n_layers: int, n_mb: int, warmup: int = 1) -> List[List[B.Op]]:
     """One stage's projection of the three-phase schedule (Section 4.2), as a list of braid steps
     exercising every block kind the paper names: warm-up F, F&B with W separated, F&W, steady
-    F&BW (W separation off), degraded BW / B, cool-down W.  For 8 microbatches:
+    F&BW (W separation off), degraded BW / B, cool-down W.  For 8 microbatches and warmup = 1:
         F0; F1|B0; F2|B1; F3|W0; F4|BW2; F5|BW3; F6|BW4; F7|BW5; BW6; B7; W1; W7
-    Shorter runs keep the same pattern truncated."""
+    `warmup` is the number of forward passes in flight before the first backward pass (Appendix A): 1 is the
+    memory-efficient warm-up (one extra forward, then overlapped F&B at once), larger values the
+    throughput-efficient one (more microbatches in flight, more stashes alive), e.g. warmup = 2:
+        F0; F1; F2|B0; F3|B1; F4|W0; F5|BW2; F6|BW3; F7|BW4; BW5; BW6; B7; W1; W7
+    Runs too short for the pattern (n_mb < warmup + 3) fall back to F0; F1|BW0; ...; BW(last)."""
     F = lambda i: forward_ops(n_layers, i)
     Bk = lambda j, k: backward_ops(n_layers, j, k)
     W = lambda j: weight_ops(n_layers, j)
-    if n_mb < 4:
+    k = max(1, warmup)
+    if n_mb < k + 3:
         steps = [F(0)]
         for i in range(1, n_mb):
             steps.append(braid(F(i), Bk(i - 1, B.OP_BW)))
         steps.append(Bk(n_mb - 1, B.OP_BW))
         return steps
-    steps = [F(0), braid(F(1), Bk(0, B.OP_B)), braid(F(2), Bk(1, B.OP_B)), braid(F(3), W(0))]
-    for i in range(4, n_mb):
-        steps.append(braid(F(i), Bk(i - 2, B.OP_BW)))
-    steps.append(Bk(n_mb - 2, B.OP_BW))
+    steps = [F(i) for i in range(k)]
+    steps += [braid(F(k), Bk(0, B.OP_B)), braid(F(k + 1), Bk(1, B.OP_B)), braid(F(k + 2), W(0))]
+    for i in range(k + 3, n_mb):
+        steps.append(braid(F(i), Bk(i - k - 1, B.OP_BW)))
+    for j in range(n_mb - k - 1, n_mb - 1):
+        steps.append(Bk(j, B.OP_BW))
     steps.append(Bk(n_mb - 1, B.OP_B))
     steps.append(W(1))
     steps.append(W(n_mb - 1))
     return steps
+
+
+def two_chunk_sequence(n_layers: int, first_of_chunk1: int, n_mb: int, pattern: int = 2) -> List[List[B.Op]]:
+    """Braid steps of a device that holds two model chunks (layers [0, first_of_chunk1) and the rest; the
+    "V" shape of Section 4.1: a microbatch passes chunk 0, later chunk 1, and returns through chunk 1, then
+    chunk 0), built after either pattern of Section 4.1:
+      pattern 2 (the paper's choice): forward and backward units of the SAME chunk, different microbatches:
+          F(c0,0); F(c1,0); F(c0,1); then for i = 1 ..: F(c1,i)|BW(c1,i-1); F(c0,i+1)|BW(c0,i-1)
+      pattern 1: forward units of one chunk with backward units of the OTHER:
+          ... then for i = 1 ..: F(c0,i+1)|BW(c1,i-1); F(c1,i)|BW(c0,i-1)
+    Both issue the same units; only the pairing differs.  When the chunks hold different numbers of units
+    (a vision encoder and language-model layers) pattern 1 pairs lists of unequal length."""
+    c0, c1 = range(first_of_chunk1), range(first_of_chunk1, n_layers)
+    F = lambda c, i: forward_ops(n_layers, i, c)
+    BW = lambda c, j: backward_ops(n_layers, j, B.OP_BW, c)
+    if n_mb < 2:
+        return [F(c0, 0), F(c1, 0), BW(c1, 0), BW(c0, 0)]
+    steps = [F(c0, 0), F(c1, 0), F(c0, 1)]
+    for i in range(1, n_mb):
+        nxt = F(c0, i + 1) if i + 1 < n_mb else []
+        if pattern == 2:
+            steps.append(braid(F(c1, i), BW(c1, i - 1)))
+            steps.append(braid(nxt, BW(c0, i - 1)))
+        else:
+            steps.append(braid(nxt, BW(c1, i - 1)))
+            steps.append(braid(F(c1, i), BW(c0, i - 1)))
+    steps += [BW(c1, n_mb - 1), BW(c0, n_mb - 1)]
+    return steps
+
+
+def peak_in_flight(steps: List[List[B.Op]], n_layers: int) -> int:
+    """Largest number of (layer, microbatch) stashes alive at once over a list of braid steps: a stash is
+    alive from the step that holds the layer's first forward unit to the step that holds its last
+    weight-gradient unit (BW counts as both)."""
+    first, last = {}, {}
+    for si, st in enumerate(steps):
+        for o in st:
+            key = (o.layer, o.microbatch)
+            if o.kind == B.OP_F:
+                first.setdefault(key, si)
+            if o.kind in (B.OP_W, B.OP_BW) and o.unit == B.ATTN:
+                last[key] = si
+    peak = 0
+    for si in range(len(steps)):
+        peak = max(peak, sum(1 for key in first if first[key] <= si <= last.get(key, len(steps))))
+    return peak

@@ -119,3 +119,103 @@ def test_validator_chain_breaks():
     # backward of chain B ends at layer 2; a new backward chain starts at the last layer of a chain
     assert _validate(st, [Op(OP_B, PRE_ATTN, 2, 0), Op(OP_B, MLP, 1, 0)])[0] == 0
     assert _validate(st, [Op(OP_B, PRE_ATTN, 2, 0), Op(OP_B, MLP, 0, 0)])[0] == 5
+
+
+# ---- op-list variants: warm-up depth (Appendix A) and the two pairing patterns of Section 4.1 -------------
+def _census(steps):
+    """How often each (kind-of-work, unit, layer, microbatch) is issued; BW counts as a B and a W."""
+    from collections import Counter
+    c = Counter()
+    for st in steps:
+        for o in st:
+            if o.kind == OP_F:
+                c[("F", o.unit, o.layer, o.microbatch)] += 1
+            if o.kind in (OP_B, OP_BW):
+                c[("B", o.unit, o.layer, o.microbatch)] += 1
+            if o.kind == OP_W or (o.kind == OP_BW and o.unit in (ATTN, MLP)):
+                c[("W", o.unit, o.layer, o.microbatch)] += 1
+    return c
+
+
+def _complete(L_, M_):
+    exp = {}
+    for l in range(L_):
+        for mb in range(M_):
+            for u in (PRE_ATTN, ATTN, PRE_MLP, MLP):
+                exp[("F", u, l, mb)] = 1
+                exp[("B", u, l, mb)] = 1
+            for u in (ATTN, MLP):
+                exp[("W", u, l, mb)] = 1
+    return exp
+
+
+@pytest.mark.parametrize("warmup", [1, 2, 3, 5])
+@pytest.mark.parametrize("n_mb", [3, 4, 6, 8, 12])
+def test_warmup_depths_give_valid_complete_sequences(warmup, n_mb):
+    from paper_2510_27257_amd.stage import stage_sequence, peak_in_flight
+    L_ = 3
+    st, *_keep = _stage(L_, n_mb)
+    steps = stage_sequence(L_, n_mb, warmup=warmup)
+    # the validator carries "B already done" from step to step only inside a context; stand-alone it
+    # accepts a W whose B came in an earlier step, and checks everything else
+    for step in steps:
+        rc, bad = _validate(st, step)
+        assert rc == 0, (warmup, n_mb, bad)
+    assert dict(_census(steps)) == _complete(L_, n_mb)
+    # every W after its B
+    seen_b = set()
+    for step in steps:
+        for o in step:
+            if o.kind in (OP_B, OP_BW):
+                seen_b.add((o.unit, o.layer, o.microbatch))
+            if o.kind == OP_W:
+                assert (o.unit, o.layer, o.microbatch) in seen_b
+    if n_mb >= warmup + 3:
+        # `warmup` plain forward passes come first, and that many more microbatches stay in flight
+        assert all(all(o.kind == OP_F for o in s) for s in steps[:warmup])
+        assert any(o.kind != OP_F for o in steps[warmup])
+        assert peak_in_flight(steps, L_) == L_ * (warmup + 3)
+
+
+def test_deeper_warmup_keeps_more_stashes_alive():
+    from paper_2510_27257_amd.stage import stage_sequence, peak_in_flight
+    peaks = [peak_in_flight(stage_sequence(4, 12, warmup=k), 4) for k in (1, 2, 3, 4)]
+    assert peaks == sorted(peaks) and len(set(peaks)) == 4
+    assert peaks[0] == 16            # F0 .. F3 alive while W0 runs
+
+
+@pytest.mark.parametrize("pattern", [1, 2])
+@pytest.mark.parametrize("n_mb", [1, 2, 3, 6])
+@pytest.mark.parametrize("split", [(4, 2), (5, 3), (3, 1)])
+def test_two_chunk_patterns_are_valid_and_complete(pattern, n_mb, split):
+    from paper_2510_27257_amd.stage import two_chunk_sequence
+    L_, first1 = split
+    cb = [0] * (L_ + 1)
+    cb[first1] = 1
+    st, *_keep = _stage(L_, max(n_mb, 1), chain_break=cb)
+    steps = two_chunk_sequence(L_, first1, n_mb, pattern)
+    for step in steps:
+        rc, bad = _validate(st, step)
+        assert rc == 0, (pattern, n_mb, split, bad)
+    assert dict(_census(steps)) == _complete(L_, n_mb)
+    # "V" order per microbatch: forward chunk 0 before chunk 1, backward chunk 1 before chunk 0
+    pos = {}
+    for si, step in enumerate(steps):
+        for o in step:
+            pos.setdefault((o.kind == OP_F, o.layer >= first1, o.microbatch), si)
+    for mb in range(n_mb):
+        assert pos[(True, False, mb)] < pos[(True, True, mb)] < pos[(False, True, mb)] < pos[(False, False, mb)]
+
+
+def test_the_two_patterns_differ_only_in_the_pairing():
+    from paper_2510_27257_amd.stage import two_chunk_sequence
+    a, b = two_chunk_sequence(4, 2, 5, 1), two_chunk_sequence(4, 2, 5, 2)
+    as_tuples = lambda steps: [[(o.kind, o.unit, o.layer, o.microbatch) for o in st] for st in steps]
+    assert _census(a) == _census(b) and as_tuples(a) != as_tuples(b)
+    # pattern 2 pairs units of one chunk, pattern 1 of different chunks
+    for steps, same in ((b, True), (a, False)):
+        for st in steps:
+            fc = {o.layer >= 2 for o in st if o.kind == OP_F}
+            bc = {o.layer >= 2 for o in st if o.kind != OP_F}
+            if fc and bc:
+                assert (fc == bc) == same

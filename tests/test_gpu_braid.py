@@ -184,3 +184,79 @@ def test_heterogeneous_stage_with_chain_break(ctx):
     assert rel_err(to_host(stg.act_slot(4, 1)), ref_lm) < tol
     ref_vit = chain(layers, (0, 1), synth.make_activation(vit, 5, "vx.mb2").astype(np.float64))
     assert rel_err(to_host(stg.chain_out(1, 2)), ref_vit) < tol
+
+
+# ---- op-list variants ---------------------------------------------------------------------------------------
+def run_steps(ctx, stg, steps, streams):
+    ctx.braid_reset()
+    stg.zero_grads()
+    for step in steps:
+        ctx.braid_step(stg.stage, step, *streams)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["gpt_bf16_x2", "llama_bf16_x1"])
+def test_warmup_depth_changes_the_order_not_the_result(ctx, name):
+    """Memory-efficient (one forward in flight before the first backward) and throughput-efficient warm-up
+    (Appendix A) issue the same units; every microbatch's weight gradients are added in the same order."""
+    layers, _ = STAGES[name]
+    n_mb = 8
+    stg = StageOnDevice(ctx, layers, n_mb, seed=4)
+    stg.load_inputs()
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    run_steps(ctx, stg, stage_sequence(len(layers), n_mb, warmup=1), streams)
+    ref = snapshot(stg)
+    for k in (2, 4):
+        run_steps(ctx, stg, stage_sequence(len(layers), n_mb, warmup=k), streams)
+        for a, b in zip(ref, snapshot(stg)):
+            assert torch.equal(a, b), (name, k)
+
+
+def test_two_chunk_patterns_give_the_same_bits_and_match_the_oracle(ctx):
+    """Section 4.1: pairing forward and backward units of the same chunk (pattern 2) or of different chunks
+    (pattern 1) on a device that holds a short wide chunk and a long narrow one."""
+    from paper_2510_27257_amd.stage import two_chunk_sequence
+    vit = Workload("v", 256, 4, 64, 512, 200, 1, causal=False)
+    lm = Workload("g", 512, 2, 128, 1024, 264, 8)
+    layers, cb, n_mb = [vit, vit, vit, lm], [0, 0, 0, 1, 0], 4
+    stg = StageOnDevice(ctx, layers, n_mb, seed=6, chain_break=cb)
+    stg.load_inputs()
+    s0 = torch.cuda.current_stream()
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    run_steps(ctx, stg, two_chunk_sequence(4, 3, n_mb, 2), (s0, s0, s0))
+    ref = snapshot(stg)
+    for pattern in (2, 1):
+        run_steps(ctx, stg, two_chunk_sequence(4, 3, n_mb, pattern), streams)
+        for a, b in zip(ref, snapshot(stg)):
+            assert torch.equal(a, b), pattern
+    # oracle, chunk by chunk (identity at the AR points)
+    for (first, last), tag in zip(stg.chains(), ("c0.", "c1.")):
+        g_ref = {l: dict() for l in range(first, last + 1)}
+        for mb in range(n_mb):
+            x = synth.make_activation(layers[first], 6, f"{tag}x.mb{mb}").astype(np.float64)
+            dy = synth.make_activation(layers[last], 6, f"{tag}dy.mb{mb}").astype(np.float64)
+            xs, sts = [x], []
+            for l in range(first, last + 1):
+                cfg, W = oracle_cfg(layers[l]), {k: v.astype(np.float64) for k, v in stg.w_host[l].items()}
+                st = {}
+                O.forward_unit(cfg, O.PRE_ATTN, W, st, x_in=xs[-1])
+                xa = O.forward_unit(cfg, O.ATTN, W, st, x_resid=xs[-1])
+                O.forward_unit(cfg, O.PRE_MLP, W, st, x_in=xa)
+                xs.append(O.forward_unit(cfg, O.MLP, W, st, x_resid=xa))
+                sts.append(st)
+            tol = TOL[layers[first].dtype]
+            assert rel_err(to_host(stg.chain_output(last, mb)), xs[-1]) < tol
+            for l in reversed(range(first, last + 1)):
+                cfg, W = oracle_cfg(layers[l]), {k: v.astype(np.float64) for k, v in stg.w_host[l].items()}
+                st = sts[l - first]
+                dz = O.backward_input_unit(cfg, O.MLP, W, st, dy)
+                dxa = O.backward_input_unit(cfg, O.PRE_MLP, W, st, dz, d_resid=dy, grads=g_ref[l])
+                dxl = O.backward_input_unit(cfg, O.ATTN, W, st, dxa)
+                dx = O.backward_input_unit(cfg, O.PRE_ATTN, W, st, dxl, d_resid=dxa, grads=g_ref[l])
+                O.backward_weight_unit(cfg, O.MLP, st, dy, g_ref[l])
+                O.backward_weight_unit(cfg, O.ATTN, st, dxa, g_ref[l])
+                dy = dx
+            assert rel_err(to_host(stg.grad_slot(first, mb)), dy) < tol
+        for l in range(first, last + 1):
+            for k, r in g_ref[l].items():
+                assert rel_err(to_host(stg.g_dev[l][k]), r) < TOL[layers[l].dtype], (l, k)
