@@ -141,7 +141,29 @@ def stage_bench(ctx, args, torch, stp, synth):
     stg = StageOnDevice(ctx, layers, n_mb, seed=0, chain_break=cb)
     stg.load_inputs()
     L = len(layers)
-    if args.pattern:
+    sched = None
+    if args.schedule:
+        # one device's program of the p-device schedule (Section 4.2), the stage split into its two chunks
+        from paper_2510_27257_amd import schedule as S
+        p_, m_, d_ = (int(x) for x in args.schedule.split(","))
+        fl0 = unit_flops(layers[0])
+        tt = S.Times(TF=fl0["F"], TB=fl0["B"], TW=fl0["W"], TAR=0.0)      # relative block lengths: the flop counts
+        progs = S.build(p_, m_)
+        S.simulate(p_, progs, tt)
+        n_mb = m_
+        first1 = cb.index(1) if cb and 1 in cb else L // 2
+        if cb is None:
+            cb = [0] * (L + 1)
+            cb[first1] = 1
+        stg = StageOnDevice(ctx, layers, n_mb, seed=0, chain_break=cb)
+        stg.load_inputs()
+        step_lists = S.braid_steps(progs[d_], L, first1)
+        seq_name = f"program of device {d_} of {p_} ({m_} microbatches) from the schedule generator"
+        mt = S.metrics(p_, progs, tt)[d_]
+        sched = {"p": p_, "m": m_, "device": d_, "blocks": len(progs[d_]),
+                 "simulated_peak_activations": mt["peak_activation"], "table1_peak_activations": 3 * p_,
+                 "plain_forward_blocks": sum(1 for b in progs[d_] if b.f and not b.b and not b.w)}
+    elif args.pattern:
         from paper_2510_27257_amd.stage import two_chunk_sequence
         first1 = cb.index(1) if cb and 1 in cb else L // 2          # chunk 1 starts at the chain break
         step_lists = two_chunk_sequence(L, first1, n_mb, args.pattern)
@@ -220,7 +242,7 @@ def stage_bench(ctx, args, torch, stp, synth):
                    "sequence": seq_name, "peak_layer_stashes_in_flight": peak, "flops_per_step": flops},
         "braid": {"makespan_ms": ms_braided, "serialized_ms": ms_serial, "sum_isolated_ms": sum_iso,
                   "makespan_over_sum_isolated": ms_braided / sum_iso},
-        "offload": offload}))
+        "offload": offload, "schedule": sched}))
 
 
 def main():
@@ -237,6 +259,9 @@ def main():
     ap.add_argument("--stage-warmup", type=int, default=1,
                     help="with --stage: forward passes in flight before the first backward pass (1 = memory-efficient "
                          "warm-up, more = throughput-efficient warm-up)")
+    ap.add_argument("--schedule", default=None, metavar="P,M,D",
+                    help="with --stage: replay the program of device D of the P-device, M-microbatch schedule "
+                         "(the stage is split into two model chunks)")
     ap.add_argument("--pattern", type=int, choices=[1, 2], default=None,
                     help="with --stage: treat the stage as two model chunks and pair forward and backward units of "
                          "the same chunk (2) or of different chunks (1)")

@@ -1,0 +1,171 @@
+"""Host-side checks of the schedule generator and simulator (Section 4.2; Table 1)."""
+import ctypes as C
+import itertools
+
+import pytest
+
+import paper_2510_27257_amd as stp
+from paper_2510_27257_amd import schedule as S, synth
+from paper_2510_27257_amd.binding import Op, OP_F, OP_B, OP_W, OP_BW
+
+CASES = [(1, 3), (1, 8), (2, 6), (2, 8), (2, 13), (3, 9), (3, 16), (4, 12), (4, 24), (6, 20), (8, 24), (8, 40)]
+TIMES = [S.Times(1.0, 1.0, 0.6, 0.25), S.Times(1.0, 2.0, 1.0, 0.5), S.Times(3.0, 3.5, 2.5, 0.0), S.Times(1.0, 1.3, 1.1, 1.0)]
+
+
+@pytest.mark.parametrize("p,m", CASES)
+def test_every_part_runs_exactly_once_on_its_device(p, m):
+    for d, prog in enumerate(S.build(p, m)):
+        fs = [b.f for b in prog if b.f]
+        bs = [b.b for b in prog if b.b]
+        ws = [x for b in prog for x in b.w]
+        want = sorted(itertools.product((0, 1), range(m)))
+        assert sorted(fs) == want and sorted(bs) == want and sorted(ws) == want
+        # microbatches of a chunk go through in order, in both directions
+        for c in (0, 1):
+            assert [i for (cc, i) in fs if cc == c] == list(range(m))
+            assert [i for (cc, i) in bs if cc == c] == list(range(m))
+        # a W never precedes its B
+        seen = set()
+        for b in prog:
+            if b.b:
+                seen.add(b.b)
+            assert all(x in seen for x in b.w)
+
+
+def check_dependencies(p, progs, t):
+    """Independent of the simulator's bookkeeping: every start respects the results it needs."""
+    V = 2 * p
+    f_done, b_done, pos = {}, {}, {}
+    for d, prog in enumerate(progs):
+        prev_end = 0.0
+        for blk in prog:
+            assert blk.start >= prev_end - 1e-9
+            dur = (t.TF if blk.f else 0) + (t.TB if blk.b else 0) + len(blk.w) * t.TW
+            alone = (blk.f is None) != (blk.b is None) and not blk.w
+            assert abs(blk.end - blk.start - dur - (t.TAR if alone else 0)) < 1e-9
+            prev_end = blk.end
+            if blk.f and blk.b:
+                out = blk.start + t.TF + t.TB
+            elif blk.f:
+                out = blk.start + t.TF + (t.TAR if alone else 0)
+            else:
+                out = blk.start + t.TB + (t.TAR if alone else 0)
+            if blk.f:
+                f_done[(S.vstage(p, d, blk.f[0]), blk.f[1])] = out
+            if blk.b:
+                b_done[(S.vstage(p, d, blk.b[0]), blk.b[1])] = out
+    for d, prog in enumerate(progs):
+        for blk in prog:
+            if blk.f:
+                v, i = S.vstage(p, d, blk.f[0]), blk.f[1]
+                if v > 0:
+                    assert blk.start >= f_done[(v - 1, i)] - 1e-9
+            if blk.b:
+                v, j = S.vstage(p, d, blk.b[0]), blk.b[1]
+                assert blk.start >= f_done[(v, j)] - 1e-9
+                if v < V - 1:
+                    assert blk.start >= b_done[(v + 1, j)] - 1e-9
+            for x in blk.w:
+                if x != blk.b:
+                    assert blk.start >= b_done[(S.vstage(p, d, x[0]), x[1])] - 1e-9
+
+
+@pytest.mark.parametrize("p,m", CASES)
+@pytest.mark.parametrize("t", TIMES)
+def test_simulated_programs_respect_every_dependency(p, m, t):
+    progs = S.build(p, m)
+    T = S.simulate(p, progs, t)
+    check_dependencies(p, progs, t)
+    assert abs(T - max(b.end for pr in progs for b in pr)) < 1e-9
+    # same blocks after W blocks floated into waits
+    for d, prog in enumerate(progs):
+        assert sorted(x for b in prog for x in b.w) == sorted(itertools.product((0, 1), range(m)))
+
+
+@pytest.mark.parametrize("p,m", CASES)
+@pytest.mark.parametrize("t", TIMES)
+def test_table1_tp_bubble_and_peak_activation_memory(p, m, t):
+    """Table 1, row of the proposed schedule: non-overlapped TP communication (2p+1) T_AR on every device, peak
+    activation memory 3p M_a (device 0; device d holds 3p - d), and the start-up part of the PP bubble."""
+    progs = S.build(p, m)
+    S.simulate(p, progs, t)
+    ms = S.metrics(p, progs, t)
+    ref = S.table1(p, t)
+    for d, x in enumerate(ms):
+        assert abs(x["tp_bubble"] - ref["tp_bubble"]) < 1e-9
+        assert x["peak_activation"] == 3 * p - d
+        assert abs(x["start_idle"] - d * (t.TF + t.TAR)) < 1e-9
+        assert x["peak_with_w_stash"] >= x["peak_activation"]
+    assert ms[0]["peak_activation"] == ref["peak_activation"]
+    # every device waits the same total time, and never less than Table 1's (approximate) PP bubble
+    assert max(x["pp_bubble"] for x in ms) - min(x["pp_bubble"] for x in ms) < 1e-6
+    assert ms[0]["pp_bubble"] >= ref["pp_bubble"] - 1e-9
+
+
+def test_simulator_on_a_case_worked_by_hand():
+    """One device (p = 1: virtual stages 0 and 1), three microbatches, T_F = 1, T_B = 2, T_W = 1, T_AR = 0.5: the
+    2p+1 = 3 warm-up forward passes are the only blocks with an exposed all-reduce, and a lone device never
+    waits, so the makespan is all the work plus three all-reduces."""
+    t = S.Times(1.0, 2.0, 1.0, 0.5)
+    progs = S.build(1, 3)
+    names = [b.name() for b in progs[0]]
+    assert names[:3] == ["F0.0", "F1.0", "F0.1"]
+    T = S.simulate(1, progs, t)
+    # one device never waits for another: the makespan is the sum of its blocks
+    plain = sum(1 for b in progs[0] if (b.f is None) != (b.b is None) and not b.w)
+    assert plain == 3
+    assert abs(T - (2 * 3 * (1.0 + 2.0 + 1.0) + 3 * 0.5)) < 1e-9
+    assert S.metrics(1, progs, t)[0]["pp_bubble"] < 1e-9
+
+
+def test_two_devices_first_blocks_by_hand():
+    """p = 2, unit times, no all-reduce: device 1 starts one forward later; device 0's first chunk-1 forward can
+    start when microbatch 0 has passed virtual stages 1 and 2 on device 1 (t = 3), its first backward follows."""
+    t = S.Times(1.0, 1.0, 1.0, 0.0)
+    progs = S.build(2, 6)
+    S.simulate(2, progs, t)
+    d0, d1 = progs
+    assert [b.name() for b in d0[:6]] == ["F0.0", "F0.1", "F0.2", "F1.0", "F0.3", "F1.1&B1.0"]
+    assert [b.start for b in d0[:6]] == [0.0, 1.0, 2.0, 3.0, 4.0, 5.0]
+    assert [b.name() for b in d1[:5]] == ["F0.0", "F1.0", "F0.1", "F1.1", "F0.2"]
+    assert [b.start for b in d1[:5]] == [1.0, 2.0, 3.0, 4.0, 5.0]
+    # the last device never separates W in the warm-up; device 0 does, once (p - d - 1 = 1), and uses it at once
+    assert d0[6].name() == "F0.4&W1.0"
+    assert d1[5].name() == "F1.2&BW1.0"
+
+
+def test_too_few_microbatches_are_refused():
+    with pytest.raises(ValueError):
+        S.device_program(4, 11, 0)
+    with pytest.raises(ValueError):
+        S.device_program(2, 8, 2)
+
+
+def _stage(n_layers, n_mb, chain_break):
+    descs = (stp.LayerDesc * n_layers)(*[stp.make_desc(synth.WORKLOADS["tiny"]) for _ in range(n_layers)])
+    cb = (C.c_int32 * (n_layers + 1))(*chain_break)
+    return stp.Stage(n_layers=n_layers, n_microbatches=n_mb, desc=descs, chain_break=cb), descs, cb
+
+
+@pytest.mark.parametrize("p,m", [(1, 4), (2, 7), (3, 9), (4, 13)])
+def test_the_library_accepts_every_device_program(p, m):
+    """A device's program as braid steps over a two-chunk stage passes the library's own validator."""
+    t = S.Times(1.0, 1.2, 0.8, 0.3)
+    progs = S.build(p, m)
+    S.simulate(p, progs, t)
+    L, first1 = 3, 2
+    st, *_keep = _stage(L, m, [0, 0, 1, 0])
+    for d in range(p):
+        steps = S.braid_steps(progs[d], L, first1)
+        assert len(steps) == len(progs[d])
+        n_ops = 0
+        for step in steps:
+            arr = (Op * len(step))(*step)
+            bad = C.c_size_t()
+            assert stp.lib().stp_validate_ops(C.byref(st), arr, len(step), C.byref(bad)) == 0, (d, bad.value)
+            n_ops += len(step)
+        # 4 F units, 4 B units and 2 W units per layer and microbatch; a BW op stands for a B and a W
+        f = sum(1 for s in steps for o in s if o.kind == OP_F)
+        b = sum(1 for s in steps for o in s if o.kind in (OP_B, OP_BW))
+        w = sum(1 for s in steps for o in s if o.kind == OP_W or (o.kind == OP_BW and o.unit in (1, 3)))
+        assert (f, b, w) == (4 * L * m, 4 * L * m, 2 * L * m)
