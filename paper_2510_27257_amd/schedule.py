@@ -19,8 +19,8 @@ alternates chunk-1 and chunk-0 blocks):
               In-flight activations reach 3p-d: Table 1's peak of 3p on device 0.
   steady      F&BW of chunk 1, F&BW of chunk 0, W separation off, while chunk-0 forwards remain.
   degraded    chunk-0 forwards exhausted: full backward of chunk 0, F&B of chunk 1 with W separated and stored.
-  cool-down   the remaining backward passes, each with the oldest stored W riding along (hides its all-reduce);
-              stored W blocks left over float into waits that are long enough for them.
+  cool-down   the remaining backward passes as full backward passes (their own W hides the all-reduce); the W
+              blocks stored in the degraded phase float into waits that are long enough for them.
 It needs m >= 3p microbatches (the paper assumes p << m).
 """
 from __future__ import annotations
@@ -101,11 +101,7 @@ def device_program(p: int, m: int, d: int) -> List[Block]:
                 stored.append(bb)
         elif have_b and (c == 1 or b[0] < b[1]):      # "V" order: chunk 0 of a microbatch after its chunk 1
             bb = Bk(c)
-            if stored:
-                prog.append(Block(b=bb, w=(stored.pop(0),)))
-                stored.append(bb)
-            else:
-                prog.append(Block(b=bb, w=(bb,)))
+            prog.append(Block(b=bb, w=(bb,)))
         elif have_f:
             w = (stored.pop(0),) if stored else ()
             prog.append(Block(f=F(c), w=w))
