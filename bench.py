@@ -24,7 +24,7 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak (256 CU x 4096 
 # HBM-side bytes per launch of the dominant kernel on its four shapes, from the two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors calibrated on a 1 GiB copy) summarised in
 # profiles/gemm_bf16_fwd_layout_gpt7b_tp8.txt; counters cannot be read from inside this process.
-GEMM_FWD_TRAFFIC_BYTES = 206.9e6
+GEMM_FWD_TRAFFIC_BYTES = 177.9e6
 
 
 def unit_flops(wl):
@@ -382,7 +382,7 @@ def main():
         },
         "braid": {"makespan_ms": ms_braided, "serialized_ms": ms_serial, "sum_isolated_ms": ms_F + ms_B + ms_W,
                   "makespan_over_sum_isolated": ms_braided / (ms_F + ms_B + ms_W)},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel<BM, BN, A k-contiguous, B row-contiguous, store> (forward layout; 256x256 and 128x256 tiles as picked per shape)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel<BM, BN, A k-contiguous, B row-contiguous, store> (forward layout; tile as picked per shape: 192x256 for all four when the GEMM has the GPU to itself)",
                      "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "avg_launch_ms": gemm_avg_ms,
                      "flops_per_launch": gemm_flops_per_launch,

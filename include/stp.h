@@ -279,9 +279,9 @@ typedef struct {
   const void *resid; int32_t ldr; float resid_scale; /* [M,N] added as resid*resid_scale, or NULL */
   int32_t epilogue;        /* 0 none; 1: C = v and C2 = gelu(v); 2: C = v * gelu'(aux) */
   void *C2; const void *aux; int32_t ld2;
-  int32_t tile_m, tile_n;  /* 0, 0: the library picks the workgroup tile from the shape.  Otherwise both
-                            * 128 or 256 (bf16 with K a multiple of 32 only): forces that tile, for
-                            * tuning and tests; any other value is STP_EINVAL */
+  int32_t tile_m, tile_n;  /* 0, 0: the library picks the workgroup tile from the shape.  Otherwise each
+                            * 128 or 256, or 192 x 256 with a_trans = 0 (bf16 with K a multiple of 32
+                            * only): forces that tile, for tuning and tests; anything else is STP_EINVAL */
 } stp_gemm_args;
 int stp_gemm(stp_ctx *ctx, const stp_gemm_args *args, void *hip_stream);
 

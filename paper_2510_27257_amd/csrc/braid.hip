@@ -166,6 +166,7 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
   for (size_t i = 0; i < bsz; i++) ev_of[i] = -1;
   int ev_used = 0;
   rc = STP_OK;
+  ctx->concurrent = serial ? 0 : 1;
 
   for (size_t i = 0; i < n_ops && rc == STP_OK; i++) {
     const stp_op &o = ops[i];
@@ -238,6 +239,7 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
     }
   }
   free(ev_of);
+  ctx->concurrent = 0;
   if (rc != STP_OK) return rc;
   if (!serial) {
     for (int i = 0; i < 3; i++) {

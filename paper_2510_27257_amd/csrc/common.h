@@ -33,6 +33,9 @@ struct stp_ctx {
   // (a stream wait refers to the record that precedes it, so the ring may wrap)
   hipEvent_t ev_copy[16];
   int ev_copy_made, ev_copy_next;
+  // set by stp_braid_step while it issues a step on distinct streams: kernels launched then share the GPU
+  // with the other streams' kernels, which changes the best GEMM tile
+  int concurrent;
 };
 
 static inline int stp_fail(stp_ctx *ctx, int status, const char *fmt, const char *a = "", long b = 0, long c = 0) {

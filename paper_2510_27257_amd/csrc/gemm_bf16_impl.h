@@ -347,15 +347,22 @@ constexpr int DSTAGES = 4;
 
 template <int ROWS, bool KC, int NWAVES>
 struct DmaOp {
-  static_assert(ROWS % (16 * NWAVES) == 0, "each wave issues a whole number of 1 KB loads per K-tile");
-  static constexpr int NINST = ROWS / 16 / NWAVES;       // wave instructions per wave per K-tile
+  static_assert(ROWS % 16 == 0, "a tile is a whole number of 1 KB pieces per K-tile");
+  static_assert(KC || (ROWS / 8) % 16 == 0, "the chunk permutation of a row-contiguous tile works on blocks of 16 chunks");
+  static constexpr int PIECES = ROWS / 16;                               // 1 KB pieces (wave instructions) per K-tile
+  static constexpr int NINST = (PIECES + NWAVES - 1) / NWAVES;           // issue slots per wave per K-tile
+  static constexpr bool EVEN = PIECES % NWAVES == 0;                     // every slot of every wave has a piece
   static constexpr int bytes = ROWS * DK * 2;
   static constexpr int CPR = ROWS / 8;                   // 16-byte chunks per k-row (row-contiguous operand)
   static constexpr int LDS_OPS_PER_FRAG = KC ? 1 : 2;
+  // piece that slot j of wave `wave` loads; pieces >= PIECES do not exist (the slot then loads piece 0 again,
+  // into a dump area: every wave issues the same number of loads per K-tile, which the vmcnt waits rely on)
+  static __device__ __forceinline__ int piece(int j, int wave) { return wave + NWAVES * j; }
   // byte offset (from the operand base, K-tile 0) of the chunk that lane `lane` of this wave's j-th
   // instruction must fetch
   static __device__ __forceinline__ unsigned chunk_offset(int j, int wave, int lane, int ld, int row0, int row_lim) {
-    const int p = (wave * NINST + j) * 64 + lane;
+    const int pc = piece(j, wave);
+    const int p = (pc < PIECES ? pc : 0) * 64 + lane;
     if (KC) {
       const int r = p >> 2, c = (p & 3) ^ ((r >> 2) & 3);
       const int row = min(row0 + r, row_lim - 1);
@@ -456,11 +463,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(c
   do {                                                                                                           \
     const int kt_ = min((ktile), KT - 1);                                                                        \
     char *st_ = smem_raw + (stage) * STAGE_BYTES;                                                                \
-    if ((q) < OA::NINST)                                                                                         \
-      dma_load16(ra, st_ + (wave * OA::NINST + (q)) * 1024, offa[(q) < OA::NINST ? (q) : 0], kt_ * stepa);       \
-    else                                                                                                         \
-      dma_load16(rb, st_ + OA::bytes + (wave * OB::NINST + (q) - OA::NINST) * 1024,                              \
-                 offb[(q) >= OA::NINST ? (q) - OA::NINST : 0], kt_ * stepb);                                     \
+    if ((q) < OA::NINST) {                                                                                       \
+      const int pc_ = OA::piece((q), wave);                                                                      \
+      char *dst_ = (OA::EVEN || pc_ < OA::PIECES) ? st_ + pc_ * 1024 : smem_raw + NSTG * STAGE_BYTES;            \
+      dma_load16(ra, dst_, offa[(q) < OA::NINST ? (q) : 0], kt_ * stepa);                                        \
+    } else {                                                                                                     \
+      const int pc_ = OB::piece((q) - OA::NINST, wave);                                                          \
+      char *dst_ = (OB::EVEN || pc_ < OB::PIECES) ? st_ + OA::bytes + pc_ * 1024 : smem_raw + NSTG * STAGE_BYTES; \
+      dma_load16(rb, dst_, offb[(q) >= OA::NINST ? (q) - OA::NINST : 0], kt_ * stepb);                           \
+    }                                                                                                            \
   } while (0)
   // prologue: tiles 0 .. NSTG-2 and the first LF loads of tile NSTG-1
 #pragma unroll
@@ -532,7 +543,7 @@ inline long operand_bytes(bool kc, long rows, long K, long ld) {
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTG, bool A_KC, bool B_KC, int EPI>
 int launch_dma(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t s) {
-  constexpr size_t smem = (size_t)NSTG * (BM + BN) * DK * 2;
+  constexpr size_t smem = (size_t)NSTG * (BM + BN) * DK * 2 + 1024;      // stages, then the dump area of unused load slots
   static_assert(smem <= 160 * 1024 && smem >= (size_t)WAVES_M * WAVES_N * 32 * (BN / WAVES_N + 8) * sizeof(float), "LDS budget");
   auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, NSTG, A_KC, B_KC, EPI>;
   static bool attr_set = false;
@@ -576,10 +587,16 @@ int launch_cfg(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t 
 // (a partly filled chip leaves each workgroup more L2 and fabric bandwidth) and t_fixed the prologue +
 // epilogue of a tile.  Against measured times of the layer's GEMM shapes the estimate is within
 // 6 % on average and picks the fastest tile or one within 1 % of it.
+// The 192 x 256 tile exists for 6144-token activations: 32 tile rows x (N / 256) columns fill the 256 CUs in
+// whole rounds where the 256 x 256 tile leaves a quarter to a half of them idle; alone on the GPU it is the
+// fastest tile for seven of the layer's eight token-major shapes (3-12 %).  When other streams run beside
+// the GEMM (the braided block) those idle CUs are not idle, a GEMM spread over all of them only takes longer
+// per tile, and the braided step was measured 1-2 % slower with it: with `shared_gpu` it is not considered.
 struct TileChoice { int bm, bn; };
-inline TileChoice pick_tile(long M, long N, long K, bool a_kc, bool b_kc) {
-  struct Cfg { int bm, bn, per_cu; double t_ktile[4]; };   // t_ktile index: 2 * a_kc + b_kc
-  static const Cfg cfgs[4] = {{256, 256, 1, {0.761, 0.766, 0.756, 0.766}},
+inline TileChoice pick_tile(long M, long N, long K, bool a_kc, bool b_kc, bool shared_gpu) {
+  struct Cfg { int bm, bn, per_cu; double t_ktile[4]; };   // t_ktile index: 2 * a_kc + b_kc; 0 = layout not built
+  static const Cfg cfgs[5] = {{256, 256, 1, {0.761, 0.766, 0.756, 0.766}},
+                              {192, 256, 1, {0.0, 0.0, 0.567, 0.617}},
                               {128, 256, 1, {0.432, 0.467, 0.428, 0.492}},
                               {256, 128, 1, {0.449, 0.451, 0.517, 0.496}},
                               {128, 128, 2, {0.240, 0.278, 0.251, 0.285}}};
@@ -587,6 +604,8 @@ inline TileChoice pick_tile(long M, long N, long K, bool a_kc, bool b_kc) {
   TileChoice best{256, 256};
   double best_t = 1e30;
   for (const Cfg &c : cfgs) {
+    if (c.t_ktile[2 * a_kc + b_kc] == 0.0) continue;
+    if (c.bm == 192 && shared_gpu) continue;
     const long tiles = ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
     const long slots = 256L * c.per_cu;
     const long full = tiles / slots, rem = tiles % slots;
@@ -607,8 +626,12 @@ template <bool A_KC, bool B_KC, int EPI>
 int launch_tile(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t s) {
   const bool dma_ok = a->K % DK == 0 && operand_bytes(A_KC, a->M, a->K, a->lda) > 0 && operand_bytes(B_KC, a->N, a->K, a->ldb) > 0;
   if (!dma_ok) return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI>(ctx, a, ep, s);
-  TileChoice c = pick_tile(a->M, a->N, a->K, A_KC, B_KC);
+  TileChoice c = pick_tile(a->M, a->N, a->K, A_KC, B_KC, ctx && ctx->concurrent);
   if (a->tile_m) c = TileChoice{a->tile_m, a->tile_n};
+  if constexpr (A_KC) {
+    // 192 rows: 6144 tokens are 32 such tiles, and 32 x (N / 256) fills the 256 compute units in whole rounds
+    if (c.bm == 192 && c.bn == 256) return launch_dma<192, 256, 2, 4, DSTAGES, A_KC, B_KC, EPI>(ctx, a, ep, s);
+  }
   if (c.bm == 256 && c.bn == 128) return launch_dma<256, 128, 2, 4, DSTAGES, A_KC, B_KC, EPI>(ctx, a, ep, s);
   if (c.bm == 128 && c.bn == 256) return launch_dma<128, 256, 2, 4, DSTAGES, A_KC, B_KC, EPI>(ctx, a, ep, s);
   if (c.bm == 128 && c.bn == 128) return launch_dma<128, 128, 2, 4, DSTAGES, A_KC, B_KC, EPI>(ctx, a, ep, s);

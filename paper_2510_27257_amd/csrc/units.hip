@@ -159,9 +159,12 @@ extern "C" int stp_gemm(stp_ctx *ctx, const stp_gemm_args *g, void *hip_stream) 
   if (g->epilogue == 2 && (!g->aux || g->ld2 < g->N)) return stp_fail(ctx, STP_EINVAL, "stp_gemm: epilogue 2 needs aux/ld2%s");
   if (g->epilogue && g->c_f32_accum) return stp_fail(ctx, STP_EINVAL, "stp_gemm: epilogue with fp32 accumulation%s");
   if (g->tile_m || g->tile_n) {
-    const bool ok = (g->tile_m == 128 || g->tile_m == 256) && (g->tile_n == 128 || g->tile_n == 256) && g->dtype == STP_BF16 &&
-                    g->K % 32 == 0;
-    if (!ok) return stp_fail(ctx, STP_EINVAL, "stp_gemm: tile_m / tile_n must both be 0, or 128 or 256 for bf16 with K %% 32 == 0%s");
+    const bool square = (g->tile_m == 128 || g->tile_m == 256) && (g->tile_n == 128 || g->tile_n == 256);
+    const bool wide = g->tile_m == 192 && g->tile_n == 256 && !g->a_trans;      // needs a k-contiguous A
+    const bool ok = (square || wide) && g->dtype == STP_BF16 && g->K % 32 == 0;
+    if (!ok)
+      return stp_fail(ctx, STP_EINVAL, "stp_gemm: tile_m / tile_n must both be 0, or 128 or 256 each, or 192 x 256 with a_trans = 0, "
+                                       "for bf16 with K %% 32 == 0%s");
   }
   if (g->M == 0 || g->N == 0) return STP_OK;
   hipStream_t s = (hipStream_t)hip_stream;

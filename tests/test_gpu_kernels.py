@@ -70,8 +70,31 @@ def test_gemm_forced_tiles(ctx, tile, a_trans, b_trans, M, N, K):
     assert rel_err(to_host(Cd), A.astype(np.float64) @ B.astype(np.float64)) < 4e-3
 
 
+@pytest.mark.parametrize("b_trans", [0, 1])
+@pytest.mark.parametrize("M,N,K", [(520, 776, 160), (264, 136, 32), (1288, 520, 352), (192, 256, 64), (1928, 264, 96)])
+def test_gemm_192_row_tile(ctx, b_trans, M, N, K):
+    """The 192 x 256 tile (k-contiguous A only): 12 one-KB pieces of A per K-tile for 8 waves, so half of the
+    waves have an unused load slot; ragged last tile rows (M = 520: 136 of 192; M = 1928: 8 of 192).  Same
+    bits as the 256 x 256 tile: the accumulation order over K does not depend on the tile."""
+    rng = np.random.default_rng(M + N + K + 1)
+    A = q(rng.standard_normal((M, K), dtype=np.float32), "bf16")
+    B = q(rng.standard_normal((K, N), dtype=np.float32) * 0.05, "bf16")
+    Ad = to_dev(A, "bf16")
+    Bd = to_dev(np.ascontiguousarray(B.T) if b_trans else B, "bf16")
+    out = {}
+    for tile in ((192, 256), (256, 256)):
+        Cd = torch.zeros((M, N), dtype=Ad.dtype, device="cuda")
+        ctx.gemm(stp.GemmArgs(dtype=stp.BF16, M=M, N=N, K=K, A=Ad.data_ptr(), lda=K, B=Bd.data_ptr(),
+                              ldb=K if b_trans else N, b_trans=b_trans, C=Cd.data_ptr(), ldc=N, bias_scale=1.0,
+                              resid_scale=1.0, tile_m=tile[0], tile_n=tile[1]))
+        torch.cuda.synchronize()
+        out[tile] = Cd
+    assert rel_err(to_host(out[(192, 256)]), A.astype(np.float64) @ B.astype(np.float64)) < 4e-3
+    assert torch.equal(out[(192, 256)], out[(256, 256)])
+
+
 @pytest.mark.parametrize("dtype,tile", [("bf16", (0, 0)), ("f32", (0, 0)), ("bf16", (256, 256)), ("bf16", (128, 128)),
-                                        ("bf16", (256, 128)), ("bf16", (128, 256))])
+                                        ("bf16", (256, 128)), ("bf16", (128, 256)), ("bf16", (192, 256))])
 def test_gemm_epilogues(ctx, dtype, tile):
     M, N, K = (392, 456, 136) if tile == (0, 0) else (392, 456, 160)
     rng = np.random.default_rng(5)
@@ -133,6 +156,7 @@ def test_gemm_rejects_bad_arguments(ctx):
     for bad, status in [(dict(M=63), 2), (dict(A=None), 1), (dict(A=x.data_ptr() + 2), 3), (dict(lda=32), 2),
                         (dict(dtype=7), 1), (dict(epilogue=1), 1), (dict(tile_m=64, tile_n=128), 1),
                         (dict(tile_m=128, tile_n=0), 1), (dict(K=40, lda=64, tile_m=128, tile_n=128), 1),
+                        (dict(tile_m=192, tile_n=128), 1), (dict(tile_m=192, tile_n=256, a_trans=1), 1),
                         (dict(dtype=stp.F32, tile_m=128, tile_n=128), 1)]:
         with pytest.raises(stp.StpError) as e:
             ctx.gemm(stp.GemmArgs(**(ok | bad)))
