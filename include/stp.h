@@ -25,6 +25,10 @@
  *     at the caller's synchronisation;
  *   - the library owns only the context (events, small tables) and uses the
  *     caller-supplied workspace; it never allocates device memory;
+ *   - a context is for one host thread at a time (it carries the last error
+ *     text, the braid's bookkeeping and the event ring of the offload calls),
+ *     and a process uses the library on one device: kernel attributes that the
+ *     launchers set once per process are set on the device current then;
  *   - the four points per layer where a TP All-Reduce would fall (after Attn
  *     and MLP in forward, after MLP-B and Attn-B in backward; Section 3) are
  *     boundaries: unit outputs there are this rank's PARTIAL and the caller
