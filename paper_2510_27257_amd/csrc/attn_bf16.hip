@@ -132,20 +132,26 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
   // ---- direct-to-LDS loads of this wave: instruction I = wave * NLD + j covers tile rows I*RPI .. +RPI-1
   const __amdgpu_buffer_rsrc_t rs =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(bbase), 0, (int)min((size_t)seq * ld * 2, (size_t)0x7fffffff), 0x00020000);
-  int ld_row[NLD];
-  unsigned ld_kcol[NLD], ld_vcol[NLD];          // byte offset within a [3a] row of the chunk this lane fetches
+  // lane's byte offset = min(row offset, last row's) + column offset; the row offset is this lane's row within the
+  // wave's first instruction (a register) plus a wave-uniform part (step, instruction), so a load costs three
+  // vector instructions and no multiplication, and its LDS target is computed on the scalar unit
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);     // same value, known to be wave-uniform
+  const unsigned row_bytes = (unsigned)ld * 2u, max_rowoff = (unsigned)(seq - 1) * row_bytes;
+  const unsigned ld_rowoff0 = (unsigned)(wave * NLD * RPI + lane / CPR) * row_bytes;
+  unsigned ld_kcol[NLD], ld_vcol[NLD];          // byte offset within a qkv row of the chunk this lane fetches
 #pragma unroll
   for (int j = 0; j < NLD; j++) {
     const int row = (wave * NLD + j) * RPI + lane / CPR, slot = lane % CPR;
-    ld_row[j] = row;
     ld_kcol[j] = (unsigned)(kcol + (slot ^ ((row / RPB) & (CPR - 1))) * 8) * 2u;
     ld_vcol[j] = (unsigned)(vcol + (slot ^ (4 * ((row & 3) / RPB))) * 8) * 2u;
   }
-  // load j (0 .. NLD-1) of the K or V tile of local step k, into ring slot k & 1
+  // load j (0 .. NLD-1) of the K or V tile of local step k, into ring slot k & 1; rows past the end of the
+  // sequence read its last row
   auto issue_one = [&](int k, bool is_v, int j) {
-    char *dst = smem_raw + (is_v ? 2 * TILE : 0) + (k & 1) * TILE + (wave * NLD + j) * 1024;
-    const int grow = min((s_begin + k) * KSTEP + ld_row[j], seq - 1);
-    dma_load16(rs, dst, (unsigned)grow * (unsigned)(ld * 2) + (is_v ? ld_vcol[j] : ld_kcol[j]), 0);
+    char *dst = smem_raw + (is_v ? 2 * TILE : 0) + (k & 1) * TILE + (wave_s * NLD + j) * 1024;
+    const unsigned uni = (unsigned)((s_begin + k) * KSTEP + j * RPI) * row_bytes;
+    const unsigned rowoff = min(ld_rowoff0 + uni, max_rowoff);
+    dma_load16(rs, dst, rowoff + (is_v ? ld_vcol[j] : ld_kcol[j]), 0);
   };
   auto issue_tile = [&](int k, bool is_v) {
 #pragma unroll

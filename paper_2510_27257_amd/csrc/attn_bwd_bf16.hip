@@ -60,11 +60,15 @@ __device__ __forceinline__ void dma_tile(__amdgpu_buffer_rsrc_t rs, char *tile, 
   using G = BG<D>;
   constexpr int N = ROWS / G::RPI / 8;
   static_assert(N >= 1, "tile too small for 8 waves");
+  // byte offset = min(uniform part + lane's row part, last row) + lane's column part: the lane parts do not
+  // change from step to step, so a load costs an add, a min and an add; the LDS target is wave-uniform
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned uni = (unsigned)row0 * ld_bytes, last = (unsigned)(seq - 1) * ld_bytes;
 #pragma unroll
   for (int j = 0; j < N; j++) {
     const int row = (wave * N + j) * G::RPI + lane / G::CPR, slot = lane % G::CPR;
-    const int grow = min(row0 + row, seq - 1);
-    dma_load16(rs, tile + (wave * N + j) * 1024, (unsigned)grow * ld_bytes + col_bytes + ((slot ^ G::swz(row)) * 16), 0);
+    const unsigned row_part = (unsigned)row * ld_bytes, col_part = col_bytes + ((slot ^ G::swz(row)) * 16);
+    dma_load16(rs, tile + (wave_s * N + j) * 1024, min(uni + row_part, last) + col_part, 0);
   }
 }
 
