@@ -423,6 +423,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(c
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // same value, known wave-uniform: LDS targets of the loads stay scalar
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   int tm, tn;
   map_tile(tiles_m, tiles_n, tm, tn);
@@ -464,11 +465,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(c
     const int kt_ = min((ktile), KT - 1);                                                                        \
     char *st_ = smem_raw + (stage) * STAGE_BYTES;                                                                \
     if ((q) < OA::NINST) {                                                                                       \
-      const int pc_ = OA::piece((q), wave);                                                                      \
+      const int pc_ = OA::piece((q), wave_s);                                                                    \
       char *dst_ = (OA::EVEN || pc_ < OA::PIECES) ? st_ + pc_ * 1024 : smem_raw + NSTG * STAGE_BYTES;            \
       dma_load16(ra, dst_, offa[(q) < OA::NINST ? (q) : 0], kt_ * stepa);                                        \
     } else {                                                                                                     \
-      const int pc_ = OB::piece((q) - OA::NINST, wave);                                                          \
+      const int pc_ = OB::piece((q) - OA::NINST, wave_s);                                                        \
       char *dst_ = (OB::EVEN || pc_ < OB::PIECES) ? st_ + OA::bytes + pc_ * 1024 : smem_raw + NSTG * STAGE_BYTES; \
       dma_load16(rb, dst_, offb[(q) >= OA::NINST ? (q) - OA::NINST : 0], kt_ * stepb);                           \
     }                                                                                                            \
