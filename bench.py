@@ -148,7 +148,7 @@ def stage_bench(ctx, args, torch, stp, synth):
         p_, m_, d_ = (int(x) for x in args.schedule.split(","))
         fl0 = unit_flops(layers[0])
         tt = S.Times(TF=fl0["F"], TB=fl0["B"], TW=fl0["W"], TAR=0.0)      # relative block lengths: the flop counts
-        progs = S.build(p_, m_)
+        progs = S.build(p_, m_, steady_w_tail=args.schedule_w_tail)
         S.simulate(p_, progs, tt)
         n_mb = m_
         first1 = cb.index(1) if cb and 1 in cb else L // 2
@@ -160,7 +160,8 @@ def stage_bench(ctx, args, torch, stp, synth):
         step_lists = S.braid_steps(progs[d_], L, first1)
         seq_name = f"program of device {d_} of {p_} ({m_} microbatches) from the schedule generator"
         mt = S.metrics(p_, progs, tt)[d_]
-        sched = {"p": p_, "m": m_, "device": d_, "blocks": len(progs[d_]),
+        sched = {"p": p_, "m": m_, "device": d_, "blocks": len(progs[d_]), "steady_w_tail": args.schedule_w_tail,
+                 "simulated_peak_with_w_stashes": mt["peak_with_w_stash"],
                  "simulated_peak_activations": mt["peak_activation"], "table1_peak_activations": 3 * p_,
                  "plain_forward_blocks": sum(1 for b in progs[d_] if b.f and not b.b and not b.w)}
     elif args.pattern:
@@ -259,6 +260,8 @@ def main():
     ap.add_argument("--stage-warmup", type=int, default=1,
                     help="with --stage: forward passes in flight before the first backward pass (1 = memory-efficient "
                          "warm-up, more = throughput-efficient warm-up)")
+    ap.add_argument("--schedule-w-tail", type=int, default=0,
+                    help="with --schedule: the last N braids of the steady phase store their W (Section 4.2)")
     ap.add_argument("--schedule", default=None, metavar="P,M,D",
                     help="with --stage: replay the program of device D of the P-device, M-microbatch schedule "
                          "(the stage is split into two model chunks)")

@@ -17,7 +17,10 @@ alternates chunk-1 and chunk-0 blocks):
   warm-up 2   until the first chunk-0 backward arrives (p-d-1 rounds; none on the last device): F&B of chunk 1
               with W separated, so that the gradient moves on at once, then F of chunk 0 & the separated W.
               In-flight activations reach 3p-d: Table 1's peak of 3p on device 0.
-  steady      F&BW of chunk 1, F&BW of chunk 0, W separation off, while chunk-0 forwards remain.
+  steady      F&BW of chunk 1, F&BW of chunk 0, W separation off, while chunk-0 forwards remain.  Optionally the
+              last `steady_w_tail` braids of the phase separate and store their W as well (Section 4.2 allows
+              separation in the steady phase at the price of the stash it keeps alive until the final steps, which
+              is what the offload is for): more stored W to fill the waits of the cool-down phase.
   degraded    chunk-0 forwards exhausted: full backward of chunk 0, F&B of chunk 1 with W separated and stored.
   cool-down   the remaining backward passes as full backward passes (their own W hides the all-reduce); the W
               blocks stored in the degraded phase float into waits that are long enough for them.
@@ -63,7 +66,7 @@ def vstage(p: int, d: int, chunk: int) -> int:
     return d if chunk == 0 else 2 * p - 1 - d
 
 
-def device_program(p: int, m: int, d: int) -> List[Block]:
+def device_program(p: int, m: int, d: int, steady_w_tail: int = 0) -> List[Block]:
     """The block list of device d for p devices and m microbatches (see the module docstring)."""
     if p < 1 or not 0 <= d < p:
         raise ValueError("need 0 <= d < p")
@@ -94,7 +97,8 @@ def device_program(p: int, m: int, d: int) -> List[Block]:
             prog.append(Block(f=F(0), w=w))
             w2_left -= 1
         elif have_f and have_b and f[c] > b[c]:
-            separate = (c == 1 and w2_left > 0) or not steady
+            left = 2 * (m - f[0]) - (1 if c == 0 else 0)     # steady braids still to come, this one included
+            separate = (c == 1 and w2_left > 0) or not steady or left <= steady_w_tail
             bb = Bk(c)
             prog.append(Block(f=F(c), b=bb, w=() if separate else (bb,)))
             if separate:
@@ -110,8 +114,8 @@ def device_program(p: int, m: int, d: int) -> List[Block]:
     return prog
 
 
-def build(p: int, m: int) -> List[List[Block]]:
-    return [device_program(p, m, d) for d in range(p)]
+def build(p: int, m: int, steady_w_tail: int = 0) -> List[List[Block]]:
+    return [device_program(p, m, d, steady_w_tail) for d in range(p)]
 
 
 def block_time(blk: Block, t: Times) -> Tuple[float, float]:

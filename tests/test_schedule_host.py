@@ -134,6 +134,33 @@ def test_two_devices_first_blocks_by_hand():
     assert d1[5].name() == "F1.2&BW1.0"
 
 
+@pytest.mark.parametrize("p,m", [(2, 8), (3, 16), (4, 16), (4, 24), (8, 40)])
+@pytest.mark.parametrize("t", TIMES)
+def test_weight_separation_late_in_the_steady_phase(p, m, t):
+    """Section 4.2: separation in the steady phase trades stash memory for bubbles.  Storing the W of the last
+    braids of the phase leaves every part in place once, breaks no dependency, keeps Table 1's TP bubble and peak
+    activation memory, never lengthens the step, and holds more W stashes."""
+    base = S.build(p, m)
+    T0 = S.simulate(p, base, t)
+    m0 = S.metrics(p, base, t)
+    for tail in (1, p, 2 * p):
+        progs = S.build(p, m, steady_w_tail=tail)
+        for d, prog in enumerate(progs):
+            want = sorted(itertools.product((0, 1), range(m)))
+            assert sorted(b.f for b in prog if b.f) == want and sorted(b.b for b in prog if b.b) == want
+            assert sorted(x for b in prog for x in b.w) == want
+        T = S.simulate(p, progs, t)
+        check_dependencies(p, progs, t)
+        ms = S.metrics(p, progs, t)
+        ref = S.table1(p, t)
+        for d, x in enumerate(ms):
+            assert abs(x["tp_bubble"] - ref["tp_bubble"]) < 1e-9
+            assert x["peak_activation"] == 3 * p - d
+            assert x["peak_with_w_stash"] >= m0[d]["peak_with_w_stash"]
+        assert T <= T0 + 1e-9
+        assert ms[0]["pp_bubble"] >= ref["pp_bubble"] - 1e-9
+
+
 def test_too_few_microbatches_are_refused():
     with pytest.raises(ValueError):
         S.device_program(4, 11, 0)
