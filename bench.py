@@ -345,8 +345,9 @@ def main():
             ctx.clock_probe(probe_out, 8.0, stream=s_probe)
     torch.cuda.synchronize()
     cyc, ticks = (int(v) for v in probe_out.tolist())
-    wall_khz = torch.cuda.get_device_properties(0).clock_rate if False else 100000   # wall clock: 100 MHz on gfx950
+    wall_khz = 100000            # the constant-rate counter the probe reads beside the shader clock: 100 MHz on gfx950
     sustained_mhz = cyc / (ticks / wall_khz) / 1e3 if ticks else None
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
 
     # ---- the same op list on one stream, and the isolated units ----------------------
     ms_serial = time_steps(lambda: ctx.braid_step(stg.stage, arr, s0, s0, s0), args.steps, args.warmup, torch)
@@ -377,7 +378,8 @@ def main():
         "mfma_util_frac_of_bf16_peak": total_flops / (ms_braided * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
         "sustained_shader_clock_mhz": sustained_mhz,
         "mfma_util_frac_at_sustained_clock": (total_flops / (ms_braided * 1e-3) / 1e12 /
-                                              (256 * 4096 * sustained_mhz * 1e6 / 1e12)) if sustained_mhz else None,
+                                              (n_cu * 4096 * sustained_mhz * 1e6 / 1e12)) if sustained_mhz else None,
+        "compute_units": n_cu,
         "units": {
             "F": {"ms": ms_F, "tflops": fl["F"] / (ms_F * 1e-3) / 1e12},
             "B": {"ms": ms_B, "tflops": fl["B"] / (ms_B * 1e-3) / 1e12},
