@@ -236,6 +236,14 @@ int stp_braid_step(stp_ctx *ctx, const stp_stage *stage, const stp_op *ops, size
 int stp_validate_ops(const stp_stage *stage, const stp_op *ops, size_t n_ops, size_t *bad_index);
 /* Forget which B units earlier steps have run (start of a new iteration). */
 int stp_braid_reset(stp_ctx *ctx);
+/* The next stp_braid_step does not wait for the step before it: for a caller that has ordered the three
+ * streams itself since then (a device synchronisation, say).
+ * Stream capture: stp_braid_step only enqueues kernels, event records and event waits (no allocation, no
+ * memset, no synchronisation), but recording three-stream steps into a HIP graph is NOT supported: the one
+ * attempt (capture begun on s_fwd, the other two streams forked from it and joined to it by events, steps
+ * detached before and after) crashed the host process inside the runtime when the capture ended, before
+ * any replay, and the cause is not known. */
+int stp_braid_detach(stp_ctx *ctx);
 
 /* ---- activation offload and reload (Section 4.2, last paragraph; Section 4.3) --------------------
  * The schedule keeps some stashed activations for a long time: those of a microbatch whose weight

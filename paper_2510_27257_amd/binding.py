@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = [
     "stp_create", "stp_destroy", "stp_last_error", "stp_status_str", "stp_check_desc", "stp_stash_bytes",
     "stp_stash_field", "stp_workspace_bytes", "stp_set_workspace", "stp_forward_unit",
     "stp_backward_input_unit", "stp_backward_weight_unit", "stp_braid_step", "stp_validate_ops",
-    "stp_braid_reset", "stp_gemm", "stp_norm_forward", "stp_norm_backward", "stp_attention_forward",
+    "stp_braid_reset", "stp_braid_detach", "stp_gemm", "stp_norm_forward", "stp_norm_backward", "stp_attention_forward",
     "stp_attention_backward", "stp_gelu_forward", "stp_gelu_backward", "stp_swiglu_forward",
     "stp_swiglu_backward", "stp_rope", "stp_colsum", "stp_clock_probe",
     "stp_offload_bytes", "stp_stash_offload", "stp_stash_reload",
@@ -127,6 +127,7 @@ def lib() -> C.CDLL:
     L.stp_braid_step.argtypes = [vp, P(Stage), P(Op), sz, vp, vp, vp, vp, vp]
     L.stp_validate_ops.argtypes = [P(Stage), P(Op), sz, P(sz)]
     L.stp_braid_reset.argtypes = [vp]
+    L.stp_braid_detach.argtypes = [vp]
     L.stp_gemm.argtypes = [vp, P(GemmArgs), vp]
     L.stp_norm_forward.argtypes = [vp, C.c_int, C.c_int, i32, i32, f32, vp, vp, vp, vp, vp, vp]
     L.stp_norm_backward.argtypes = [vp, C.c_int, C.c_int, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp]
@@ -278,6 +279,9 @@ class Context:
 
     def braid_reset(self):
         self.check(self._lib.stp_braid_reset(self._h), "stp_braid_reset")
+
+    def braid_detach(self):
+        self.check(self._lib.stp_braid_detach(self._h), "stp_braid_detach")
 
     # ---- kernels -------------------------------------------------------------
     def gemm(self, args: GemmArgs, stream=None):

@@ -127,6 +127,12 @@ extern "C" int stp_braid_reset(stp_ctx *ctx) {
   return STP_OK;
 }
 
+extern "C" int stp_braid_detach(stp_ctx *ctx) {
+  if (!ctx) return STP_EINVAL;
+  ctx->ev_next = 0;
+  return STP_OK;
+}
+
 extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *ops, size_t n_ops, void *s_fwd,
                               void *s_bwd, void *s_wgrad, stp_boundary_fn cb, void *user) {
   if (!ctx) return STP_EINVAL;
