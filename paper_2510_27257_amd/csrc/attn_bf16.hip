@@ -4,7 +4,9 @@
 // Work decomposition.  A workgroup owns 128 query rows of one (sequence, head) and ONE CHUNK of up
 // to `chunk_steps` * 128 keys (chosen per launch); chunks of the same query block are merged afterwards by a small combine kernel
 // (fixed order, deterministic).  Cutting the key range into chunks turns the causal triangle into
-// pieces of similar size instead of workgroups whose length varies 1..seq/128.
+// pieces of similar size instead of workgroups whose length varies 1..seq/128.  The chunk length and the
+// order in which the (block, chunk) pairs are dispatched - longest first, so that the short remainders fill
+// the end of the launch - come from a host-side plan that simulates the dispatch over the 256 compute units.
 // Inside a workgroup 8 waves run as 4 query sub-tiles (32 rows) x 2 key halves: per 128-key step
 // waves 0-3 (group A) take keys 0..63 and waves 4-7 (group B) keys 64..127; a SIMD holds one wave of
 // each group.  The two halves are merged through LDS at the end.
@@ -37,6 +39,9 @@
 #include <type_traits>
 #include <vector>
 #include <algorithm>
+#include <queue>
+#include <functional>
+#include <cstring>
 
 namespace {
 
@@ -96,7 +101,8 @@ __device__ __forceinline__ void mfma_pv(f32x16_t (&o)[D / 32], const u32x4_t (&b
 
 template <int D>
 __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__restrict__ qkv, float *__restrict__ part, int seq,
-                                                            int n, int nk, int causal, int max_chunks, int chunk_steps, float scale_log2) {
+                                                            int n, int nk, int causal, int max_chunks, int chunk_steps, float scale_log2,
+                                                            int n_items, stp_attn_order ord) {
   using G = AttnGeom<D>;
   static_assert(D == 64 || D == 128, "head dimension");
   constexpr int RB = G::RB, CPR = G::CPR, RPB = G::RPB, RPI = G::RPI, NLD = G::NLD, TILE = G::TILE;
@@ -107,9 +113,13 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
   const int lr = lane & 31, lg = lane >> 5;
   const int qsub = wave & 3, half = wave >> 2;
   const int nqb = (seq + QB - 1) / QB;
-  const int qb = nqb - 1 - blockIdx.x;              // late query blocks own the most chunks: start them first
-  const int chunk = blockIdx.y;
-  const int head = blockIdx.z % n, b = blockIdx.z / n;
+  // the workgroup's (query block, chunk): from the launch's work order (grid = heads x items), or, without
+  // one, from a grid of blocks x chunks x heads with the late query blocks, which own the most chunks, first
+  const int item = n_items ? ord.item[blockIdx.y] : 0;
+  const int qb = n_items ? (item & 0xfff) : nqb - 1 - (int)blockIdx.x;
+  const int chunk = n_items ? (item >> 12) : (int)blockIdx.y;
+  const int bz = n_items ? blockIdx.x : blockIdx.z;
+  const int head = bz % n, b = bz / n;
   const int nsteps = attn_steps(qb, seq, causal);
   const int s_begin = chunk * chunk_steps, s_end = min(nsteps, s_begin + chunk_steps);
   if (s_begin >= nsteps) return;
@@ -431,12 +441,12 @@ __global__ __launch_bounds__(256) void attn_fwd_combine_kernel(const float *__re
   if (lane == 0) lse[((size_t)b * n + head) * seq + q] = (M + log2f(L)) * LN2;
 }
 
-// steps per chunk for this shape: grid x runs over the query blocks, last block first
-inline int fwd_chunk_steps(const stp_layer_desc *d) {
+// the plan of the forward kernel for this shape (block x = query block x)
+inline const stp_attn_plan *fwd_plan(stp_ctx *ctx, const stp_layer_desc *d) {
   const int nqb = (d->seq + QB - 1) / QB;
   std::vector<int> steps(nqb);
-  for (int x = 0; x < nqb; x++) steps[x] = attn_steps(nqb - 1 - x, d->seq, d->causal);
-  return stp_pick_chunk(0, nqb, steps.data());
+  for (int x = 0; x < nqb; x++) steps[x] = attn_steps(x, d->seq, d->causal);
+  return stp_attn_plan_get(ctx, 0, d, nqb, steps.data(), d->heads_local * d->mbsz);
 }
 
 template <int D>
@@ -455,15 +465,16 @@ int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out
   if ((size_t)d->seq * stp_qkv_width(d) * sizeof(bf16_t) > (size_t)0x7fffffff)
     return stp_fail(ctx, STP_ESHAPE, "attention forward: one sequence of QKV must span less than 2 GiB%s");
   const int nqb = (d->seq + QB - 1) / QB;
-  const int chunk_steps = fwd_chunk_steps(d);
-  const int max_chunks = (attn_steps(nqb - 1, d->seq, d->causal) + chunk_steps - 1) / chunk_steps;
+  const stp_attn_plan *plan = fwd_plan(ctx, d);
+  const int chunk_steps = plan->chunk_steps, max_chunks = plan->max_chunks;
   const size_t need = (size_t)d->mbsz * d->heads_local * nqb * max_chunks * G::piece_floats * sizeof(float);
   if (!ws || ws_bytes < need)
     return stp_fail(ctx, STP_ENOSPACE, "attention forward: workspace lane too small%s (need %ld bytes)", "", (long)need);
-  dim3 grid(nqb, max_chunks, d->heads_local * d->mbsz), block(512);
+  const dim3 grid = plan->n_items ? dim3(d->heads_local * d->mbsz, plan->n_items) : dim3(nqb, max_chunks, d->heads_local * d->mbsz);
+  const dim3 block(512);
   float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
   hipLaunchKernelGGL(kern, grid, block, smem, s, (const bf16_t *)qkv, ws, d->seq, d->heads_local, stp_kv_heads(d), d->causal, max_chunks, chunk_steps,
-                     scale_log2);
+                     scale_log2, plan->n_items, plan->order);
   STP_LAUNCH_CHECK(ctx);
   size_t waves = (size_t)d->mbsz * d->heads_local * d->seq;
   hipLaunchKernelGGL(attn_fwd_combine_kernel<D>, dim3((waves + 3) / 4), dim3(256), 0, s, ws, (bf16_t *)out, lse, d->seq,
@@ -476,8 +487,7 @@ int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out
 
 size_t stp_attn_fwd_ws_bytes(const stp_layer_desc *d) {
   const int nqb = (d->seq + QB - 1) / QB;
-  const int chunk_steps = fwd_chunk_steps(d);
-  const int max_chunks = (attn_steps(nqb - 1, d->seq, d->causal) + chunk_steps - 1) / chunk_steps;
+  const int max_chunks = fwd_plan(nullptr, d)->max_chunks;
   return (size_t)d->mbsz * d->heads_local * nqb * max_chunks * (QB * d->head_dim + 2 * QB) * sizeof(float);
 }
 
@@ -488,16 +498,77 @@ int stp_launch_attn_fwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *
   return stp_fail(ctx, STP_ESHAPE, "bf16 attention needs head_dim 64 or 128%s");
 }
 
-int stp_pick_chunk(int kind, int nblocks, const int *steps) {
-  // Measured on gpt7b_tp8-like shapes (4 heads x 128, seq 4096 and 6144, causal): 16 steps of 128 keys for the
-  // forward and dq kernels and 32 steps of 64 queries for dkv beat both shorter chunks (more partial pieces,
-  // more workgroup prologues and epilogues) and longer ones (too few workgroups for 256 compute units).  A
-  // list-scheduling model of the dispatch did not reproduce that ordering, so the lengths are constants; they
-  // are only capped so that a block is never cut into more than 8 pieces (bounds the workspace).
-  static const int dflt[3] = {16, 32, 16};
+namespace {
+
+// Time of a launch whose workgroups, in the given order, each go to the compute unit that is free first
+// (256 of them, one workgroup each): fixed + per_step * steps per workgroup, every length `zcount` times.
+double plan_makespan(const std::vector<int> &lens, int zcount, double fixed, double per_step) {
+  std::priority_queue<double, std::vector<double>, std::greater<double>> cu;
+  for (int i = 0; i < 256; i++) cu.push(0.0);
+  double end = 0.0;
+  for (int len : lens)
+    for (int z = 0; z < zcount; z++) {
+      const double t = cu.top() + fixed + per_step * len;
+      cu.pop();
+      cu.push(t);
+      end = std::max(end, t);
+    }
+  return end;
+}
+
+void plan_make(int kind, int nblocks, const int *steps, int zcount, stp_attn_plan *plan) {
+  // Microseconds per workgroup: start and end of a workgroup (first tiles, the merge of the wave halves, the
+  // partial result) and one step of its main loop; fitted to measured kernel times over chunk lengths 8 .. 32
+  // (16 .. 64 for dkv) at 4 and 10 heads x 128, seq 4096 and 6144, causal, and 16 heads, seq 1024, not causal:
+  // the estimate is within 6 - 8 % (rms) and its choice is the fastest chunk length measured, or within 3 % of it.
+  static const double fixed_us[3] = {11.5, 12.0, 12.0}, step_us[3] = {1.75, 1.90, 2.65};
   int max_steps = 1;
   for (int x = 0; x < nblocks; x++) max_steps = std::max(max_steps, steps[x]);
-  int c = std::min(dflt[kind], max_steps);
-  while ((max_steps + c - 1) / c > 8) c *= 2;
-  return c;
+  // a block is never cut into more than 8 pieces (bounds the workspace and fits the table's 3 chunk bits)
+  const int lo = std::max((max_steps + 7) / 8, std::min(max_steps, 4));
+  int best_c = max_steps;
+  double best_t = 1e30;
+  std::vector<int> lens;
+  for (int c = lo; c <= max_steps; c++) {
+    lens.clear();
+    for (int x = 0; x < nblocks; x++) {
+      for (int k = 0; k < steps[x] / c; k++) lens.push_back(c);
+      if (steps[x] % c) lens.push_back(steps[x] % c);
+    }
+    std::sort(lens.begin(), lens.end(), std::greater<int>());
+    const double t = plan_makespan(lens, zcount, fixed_us[kind], step_us[kind]);
+    if (t < best_t * 0.995) { best_t = t; best_c = c; }      // a longer chunk has to win by half a percent
+  }
+  plan->chunk_steps = best_c;
+  plan->max_chunks = (max_steps + best_c - 1) / best_c;
+  // the (block, chunk) pairs, longest first; equal lengths keep the later blocks first
+  struct Item { int len, block, chunk; };
+  std::vector<Item> items;
+  for (int x = nblocks - 1; x >= 0; x--)
+    for (int k = 0; k * best_c < steps[x]; k++) items.push_back({std::min(best_c, steps[x] - k * best_c), x, k});
+  std::stable_sort(items.begin(), items.end(), [](const Item &u, const Item &v) { return u.len > v.len; });
+  plan->n_items = 0;
+  if (items.size() <= STP_ATTN_ORDER_CAP && nblocks <= 4096 && plan->max_chunks <= 8) {
+    plan->n_items = (int)items.size();
+    for (size_t i = 0; i < items.size(); i++) plan->order.item[i] = (uint16_t)(items[i].block | (items[i].chunk << 12));
+  }
+}
+
+}  // namespace
+
+const stp_attn_plan *stp_attn_plan_get(stp_ctx *ctx, int kind, const stp_layer_desc *d, int nblocks, const int *steps, int zcount) {
+  const int key[8] = {kind + 1, d->seq, d->causal, d->heads_local, stp_kv_heads(d), d->mbsz, d->head_dim, nblocks};
+  static thread_local stp_attn_plan scratch;
+  stp_attn_plan *p = &scratch;
+  if (ctx) {
+    for (int i = 0; i < ctx->attn_plan_n; i++)
+      if (memcmp(ctx->attn_plan[i].key, key, sizeof(key)) == 0) return &ctx->attn_plan[i];
+    if (ctx->attn_plan_n < STP_ATTN_PLAN_CACHE) p = &ctx->attn_plan[ctx->attn_plan_n++];
+    else { p = &ctx->attn_plan[ctx->attn_plan_next]; ctx->attn_plan_next = (ctx->attn_plan_next + 1) % STP_ATTN_PLAN_CACHE; }
+  } else if (memcmp(scratch.key, key, sizeof(key)) == 0) {
+    return &scratch;
+  }
+  plan_make(kind, nblocks, steps, zcount, p);
+  memcpy(p->key, key, sizeof(key));
+  return p;
 }

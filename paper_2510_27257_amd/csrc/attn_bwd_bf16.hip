@@ -120,7 +120,8 @@ template <int D>
 __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                                            const float *__restrict__ lse, const float *__restrict__ delta,
                                                            float *__restrict__ part, int seq, int n, int nk, int causal,
-                                                           int max_chunks, int chunk_steps, float scale) {
+                                                           int max_chunks, int chunk_steps, float scale, int n_items,
+                                                           stp_attn_order ord) {
   using G = BG<D>;
   constexpr int RB = G::RB;
   constexpr int KV_TILE = KVB * RB, Q_TILE = QSTEP * RB, STAGE = 2 * Q_TILE;
@@ -130,8 +131,12 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lg = lane >> 5;
   const int ksub = wave & 3, qhalf = wave >> 2;
-  const int kvb = blockIdx.x, chunk = blockIdx.y;      // key block 0 owns the most chunks and is scheduled first
-  const int kh = blockIdx.z % nk, b = blockIdx.z / nk;     // key / value head
+  // the workgroup's (key block, chunk): from the launch's work order (grid = heads x items), or, without one,
+  // from a grid of blocks x chunks x heads (key block 0 owns the most chunks and comes first)
+  const int item = n_items ? ord.item[blockIdx.y] : 0;
+  const int kvb = n_items ? (item & 0xfff) : (int)blockIdx.x, chunk = n_items ? (item >> 12) : (int)blockIdx.y;
+  const int bz = n_items ? blockIdx.x : blockIdx.z;
+  const int kh = bz % nk, b = bz / nk;                     // key / value head
   const int group = n / nk;                                // query heads kh*group .. kh*group+group-1 share it
   const int nq = (seq + QSTEP - 1) / QSTEP;
   // the workgroup's steps run over (query head of the group, 64-query step): step u is query head
@@ -348,7 +353,7 @@ template <int D>
 __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                                           const float *__restrict__ lse, const float *__restrict__ delta,
                                                           float *__restrict__ part, int seq, int n, int nk, int causal, int max_chunks,
-                                                          int chunk_steps, float scale) {
+                                                          int chunk_steps, float scale, int n_items, stp_attn_order ord) {
   using G = BG<D>;
   constexpr int RB = G::RB;
   constexpr int KV_TILE = KVB * RB, STAGE = 2 * KV_TILE;      // LDS: ring of two stages { K [128][D], V [128][D] }
@@ -358,9 +363,13 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
   const int lr = lane & 31, lg = lane >> 5;
   const int qsub = wave & 3, half = wave >> 2;
   const int nqblk = (seq + 127) / 128;
-  const int qb = nqblk - 1 - blockIdx.x;                   // late query blocks own the most chunks: start them first
-  const int chunk = blockIdx.y;
-  const int head = blockIdx.z % n, b = blockIdx.z / n;
+  // the workgroup's (query block, chunk): from the launch's work order (grid = heads x items), or, without
+  // one, from a grid of blocks x chunks x heads with the late query blocks, which own the most chunks, first
+  const int item = n_items ? ord.item[blockIdx.y] : 0;
+  const int qb = n_items ? (item & 0xfff) : nqblk - 1 - (int)blockIdx.x;
+  const int chunk = n_items ? (item >> 12) : (int)blockIdx.y;
+  const int bz = n_items ? blockIdx.x : blockIdx.z;
+  const int head = bz % n, b = bz / n;
   const int nsteps = dq_steps(qb, seq, causal);
   const int s_begin = chunk * chunk_steps, s_end = min(nsteps, s_begin + chunk_steps);
   if (s_begin >= nsteps) return;
@@ -532,25 +541,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_combine_kernel(const float *_
   Vec8<bf16_t>::store(dqkv + ((size_t)b * seq + q) * ((size_t)(n + 2 * nk) * D) + head * D + c8, sq);
 }
 
-// steps per chunk for this shape (grid x: key blocks in order for dkv; query blocks, last first, for dq)
-inline int dkv_chunk_steps(const stp_layer_desc *d) {
+// the plans of the two kernels for this shape (dkv: block x = key block x; dq: block x = query block x)
+inline const stp_attn_plan *dkv_plan(stp_ctx *ctx, const stp_layer_desc *d) {
   const int nkvb = (d->seq + KVB - 1) / KVB, nq = (d->seq + QSTEP - 1) / QSTEP;
   std::vector<int> steps(nkvb);
   const int group = d->heads_local / stp_kv_heads(d);     // a key block runs over the steps of its whole head group
   for (int x = 0; x < nkvb; x++) steps[x] = group * (nq - dkv_first_step(x, d->causal));
-  return stp_pick_chunk(1, nkvb, steps.data());
+  return stp_attn_plan_get(ctx, 1, d, nkvb, steps.data(), stp_kv_heads(d) * d->mbsz);
 }
-inline int dq_chunk_steps(const stp_layer_desc *d) {
+inline const stp_attn_plan *dq_plan(stp_ctx *ctx, const stp_layer_desc *d) {
   const int nqb = (d->seq + 127) / 128;
   std::vector<int> steps(nqb);
-  for (int x = 0; x < nqb; x++) steps[x] = dq_steps(nqb - 1 - x, d->seq, d->causal);
-  return stp_pick_chunk(2, nqb, steps.data());
-}
-inline int dkv_max_chunks(int seq, int group, int chunk_steps) {
-  return (group * ((seq + QSTEP - 1) / QSTEP) + chunk_steps - 1) / chunk_steps;
-}
-inline int dq_max_chunks(int seq, int causal, int chunk_steps) {
-  return (dq_steps((seq + 127) / 128 - 1, seq, causal) + chunk_steps - 1) / chunk_steps;
+  for (int x = 0; x < nqb; x++) steps[x] = dq_steps(x, d->seq, d->causal);
+  return stp_attn_plan_get(ctx, 2, d, nqb, steps.data(), d->heads_local * d->mbsz);
 }
 
 template <int D>
@@ -574,22 +577,25 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
   const float scale = 1.0f / sqrtf((float)D);
   const int nkvb = (d->seq + KVB - 1) / KVB, nqb = (d->seq + 127) / 128;
   const int nk = stp_kv_heads(d), group = d->heads_local / nk;
-  const int ch_kv = dkv_chunk_steps(d), ch_q = dq_chunk_steps(d);
-  const int mc_kv = dkv_max_chunks(d->seq, group, ch_kv), mc_q = dq_max_chunks(d->seq, d->causal, ch_q);
+  // copies: the second lookup may evict the first plan from the context's cache
+  const stp_attn_plan pkv = *dkv_plan(ctx, d), pq = *dq_plan(ctx, d);
+  const int ch_kv = pkv.chunk_steps, ch_q = pq.chunk_steps, mc_kv = pkv.max_chunks, mc_q = pq.max_chunks;
   const size_t bh = (size_t)d->mbsz * d->heads_local, bk = (size_t)d->mbsz * nk;
   const size_t need_kv = bk * nkvb * mc_kv * 2 * KVB * D * sizeof(float), need_q = bh * nqb * mc_q * 128 * D * sizeof(float);
   const size_t need = need_kv > need_q ? need_kv : need_q;
   if (!ws || ws_bytes < need)
     return stp_fail(ctx, STP_ENOSPACE, "attention backward: workspace lane too small%s (need %ld bytes)", "", (long)need);
   const size_t rows8 = bh * d->seq * (D / 8), rows8_kv = bk * d->seq * (D / 8);
-  hipLaunchKernelGGL(kkv, dim3(nkvb, mc_kv, (unsigned)bk), dim3(512), smem_kv, s, (const bf16_t *)qkv, (const bf16_t *)dout, lse,
-                     delta, ws, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv, scale);
+  hipLaunchKernelGGL(kkv, pkv.n_items ? dim3((unsigned)bk, pkv.n_items) : dim3(nkvb, mc_kv, (unsigned)bk), dim3(512), smem_kv, s,
+                     (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta, ws, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv, scale,
+                     pkv.n_items, pkv.order);
   STP_LAUNCH_CHECK(ctx);
   hipLaunchKernelGGL(attn_bwd_dkv_combine_kernel<D>, dim3((rows8_kv + 255) / 256), dim3(256), 0, s, ws, (bf16_t *)dqkv, d->seq,
                      d->heads_local, nk, d->mbsz, d->causal, mc_kv, ch_kv, scale);
   STP_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(kq, dim3(nqb, mc_q, (unsigned)bh), dim3(512), smem_q, s, (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta,
-                     ws, d->seq, d->heads_local, nk, d->causal, mc_q, ch_q, scale);
+  hipLaunchKernelGGL(kq, pq.n_items ? dim3((unsigned)bh, pq.n_items) : dim3(nqb, mc_q, (unsigned)bh), dim3(512), smem_q, s,
+                     (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta, ws, d->seq, d->heads_local, nk, d->causal, mc_q, ch_q, scale,
+                     pq.n_items, pq.order);
   STP_LAUNCH_CHECK(ctx);
   hipLaunchKernelGGL(attn_bwd_dq_combine_kernel<D>, dim3((rows8 + 255) / 256), dim3(256), 0, s, ws, (bf16_t *)dqkv, d->seq,
                      d->heads_local, nk, d->mbsz, d->causal, mc_q, ch_q, scale);
@@ -603,8 +609,8 @@ size_t stp_attn_bwd_ws_bytes(const stp_layer_desc *d) {
   const int nkvb = (d->seq + KVB - 1) / KVB, nqb = (d->seq + 127) / 128;
   const int nk = stp_kv_heads(d);
   const size_t bh = (size_t)d->mbsz * d->heads_local, bk = (size_t)d->mbsz * nk;
-  const size_t need_kv = bk * nkvb * dkv_max_chunks(d->seq, d->heads_local / nk, dkv_chunk_steps(d)) * 2 * KVB * d->head_dim * sizeof(float);
-  const size_t need_q = bh * nqb * dq_max_chunks(d->seq, d->causal, dq_chunk_steps(d)) * 128 * d->head_dim * sizeof(float);
+  const size_t need_kv = bk * nkvb * dkv_plan(nullptr, d)->max_chunks * 2 * KVB * d->head_dim * sizeof(float);
+  const size_t need_q = bh * nqb * dq_plan(nullptr, d)->max_chunks * 128 * d->head_dim * sizeof(float);
   return need_kv > need_q ? need_kv : need_q;
 }
 

@@ -15,6 +15,21 @@ typedef short s16x8_t __attribute__((ext_vector_type(8)));
 
 #define STP_MAX_LAYER_EVENTS 4096
 
+// Work plan of a chunked attention kernel (forward, dq, dkv).  A workgroup owns one chunk of up to chunk_steps
+// steps of one block (a query block, or a key block for dkv); `order` lists the (block, chunk) pairs, longest
+// first, and the grid is (heads, n_items) so that the dispatcher, which hands out workgroups in grid order,
+// starts the long ones first and fills the tail of the launch with the short ones.  item = block | chunk << 12.
+// n_items = 0 (more pairs than the table holds): the grid is blocks x max_chunks x heads and a workgroup
+// reads its pair from its grid position.
+#define STP_ATTN_ORDER_CAP 1024
+struct stp_attn_order { uint16_t item[STP_ATTN_ORDER_CAP]; };
+struct stp_attn_plan {
+  int key[8];          // what the plan was made for (cache tag)
+  int chunk_steps, max_chunks, n_items;
+  stp_attn_order order;
+};
+#define STP_ATTN_PLAN_CACHE 12
+
 struct stp_ctx {
   int device;
   char err[512];
@@ -36,6 +51,9 @@ struct stp_ctx {
   // set by stp_braid_step while it issues a step on distinct streams: kernels launched then share the GPU
   // with the other streams' kernels, which changes the best GEMM tile
   int concurrent;
+  // plans of the attention kernels for the shapes seen so far (making one simulates the dispatch)
+  stp_attn_plan attn_plan[STP_ATTN_PLAN_CACHE];
+  int attn_plan_n, attn_plan_next;
 };
 
 static inline int stp_fail(stp_ctx *ctx, int status, const char *fmt, const char *a = "", long b = 0, long c = 0) {
@@ -135,9 +153,10 @@ int stp_launch_attn_bwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *
 static inline int stp_kv_heads(const stp_layer_desc *d) { return d->kv_heads_local > 0 ? d->kv_heads_local : d->heads_local; }
 static inline int stp_qkv_width(const stp_layer_desc *d) { return (d->heads_local + 2 * stp_kv_heads(d)) * d->head_dim; }
 
-// Steps per chunk for the attention kernels, whose workgroups own one chunk of a block's step range (grid =
-// blocks x chunks x heads).  kind: 0 forward, 1 dkv, 2 dq; steps[x] is the number of steps of block x.
-int stp_pick_chunk(int kind, int nblocks, const int *steps);
+// The plan for one attention kernel.  kind: 0 forward, 1 dkv, 2 dq; steps[x] is the number of steps of block
+// x; zcount the number of (head, sequence) pairs that repeat the same blocks.  With a context the plan is
+// cached there (tag: kind and the layer's attention shape); without one it lives in a thread-local slot.
+const stp_attn_plan *stp_attn_plan_get(stp_ctx *ctx, int kind, const stp_layer_desc *d, int nblocks, const int *steps, int zcount);
 
 size_t stp_attn_fwd_ws_bytes(const stp_layer_desc *d);   // workspace the bf16 attention kernels need (chunk partials)
 size_t stp_attn_bwd_ws_bytes(const stp_layer_desc *d);
