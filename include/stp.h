@@ -305,6 +305,17 @@ int stp_norm_backward(stp_ctx *ctx, int dtype, int norm, int32_t T, int32_t h, c
                       const void *gamma, const float *stats, const void *dy, const void *d_resid,
                       void *dx, float *dgamma, float *dbeta, int lane, void *hip_stream);
 
+/* The work plan of one of the chunked bf16 attention kernels for a layer shape (host only, no GPU needed).
+ * kind 0: forward, blocks of 128 queries, steps of 128 keys; 1: dK / dV, blocks of 128 keys, steps of 64
+ * queries (over every query head of the key head's group); 2: dQ, blocks of 128 queries, steps of 128 keys.
+ * A workgroup runs one chunk of at most *chunk_steps consecutive steps of one block; a block has at most
+ * *max_chunks chunks (never more than 8), which is what sizes the workspace.  items[0 .. *n_items) are the
+ * (block, chunk) pairs in the order the workgroups are dispatched, longest first, as block | chunk << 12;
+ * *n_items = 0 means more pairs than the kernel's table holds (1024) and a blocks x chunks grid.  items may
+ * be NULL; STP_ENOSPACE if items_cap < *n_items; STP_EUNSUPPORTED for fp32 (those kernels are not chunked). */
+int stp_attention_plan(const stp_layer_desc *desc, int kind, int32_t *chunk_steps, int32_t *max_chunks, int32_t *n_items,
+                       uint16_t *items, size_t items_cap);
+
 /* Attention core of one rank: qkv is [T, (n + 2 n_kv) d] (n Q heads | n_kv K heads | n_kv V heads; n_kv = n
  * unless desc->kv_heads_local is set), ctx [T, n d], lse fp32 [mbsz,n,seq].  The bf16 kernels cut the key
  * range into chunks whose fp32 partials live in workspace lane `lane` (0..2), and address a sequence's QKV

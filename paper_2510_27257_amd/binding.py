@@ -12,6 +12,7 @@ __all__ = [
     "PRE_ATTN", "ATTN", "PRE_MLP", "MLP", "OP_F", "OP_B", "OP_W", "OP_BW", "F32", "BF16",
     "NORM_LN", "NORM_RMS", "ACT_GELU", "ACT_SWIGLU", "STASH_FIELDS", "STATUS",
     "OFFLOAD_W_ATTN", "OFFLOAD_W_MLP", "OFFLOAD_FWD", "offload_bytes",
+    "ATTN_FWD", "ATTN_DKV", "ATTN_DQ", "attention_plan",
 ]
 
 PRE_ATTN, ATTN, PRE_MLP, MLP = 0, 1, 2, 3
@@ -29,7 +30,7 @@ EXPORTED_SYMBOLS = [
     "stp_create", "stp_destroy", "stp_last_error", "stp_status_str", "stp_check_desc", "stp_stash_bytes",
     "stp_stash_field", "stp_workspace_bytes", "stp_set_workspace", "stp_forward_unit",
     "stp_backward_input_unit", "stp_backward_weight_unit", "stp_braid_step", "stp_validate_ops",
-    "stp_braid_reset", "stp_braid_detach", "stp_gemm", "stp_norm_forward", "stp_norm_backward", "stp_attention_forward",
+    "stp_braid_reset", "stp_braid_detach", "stp_attention_plan", "stp_gemm", "stp_norm_forward", "stp_norm_backward", "stp_attention_forward",
     "stp_attention_backward", "stp_gelu_forward", "stp_gelu_backward", "stp_swiglu_forward",
     "stp_swiglu_backward", "stp_rope", "stp_colsum", "stp_clock_probe",
     "stp_offload_bytes", "stp_stash_offload", "stp_stash_reload",
@@ -128,6 +129,7 @@ def lib() -> C.CDLL:
     L.stp_validate_ops.argtypes = [P(Stage), P(Op), sz, P(sz)]
     L.stp_braid_reset.argtypes = [vp]
     L.stp_braid_detach.argtypes = [vp]
+    L.stp_attention_plan.argtypes = [P(LayerDesc), C.c_int, P(i32), P(i32), P(i32), P(C.c_uint16), sz]
     L.stp_gemm.argtypes = [vp, P(GemmArgs), vp]
     L.stp_norm_forward.argtypes = [vp, C.c_int, C.c_int, i32, i32, f32, vp, vp, vp, vp, vp, vp]
     L.stp_norm_backward.argtypes = [vp, C.c_int, C.c_int, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp]
@@ -188,6 +190,19 @@ def offload_bytes(desc: "LayerDesc", which: int, alpha: float) -> int:
     if rc != 0:
         raise StpError(rc, "stp_offload_bytes")
     return n.value
+
+
+ATTN_FWD, ATTN_DKV, ATTN_DQ = 0, 1, 2
+
+
+def attention_plan(desc: "LayerDesc", kind: int):
+    """(chunk_steps, max_chunks, [(block, chunk), ...] in dispatch order) of a chunked attention kernel (no GPU needed)."""
+    cs, mc, n = C.c_int32(), C.c_int32(), C.c_int32()
+    items = (C.c_uint16 * 1024)()
+    rc = lib().stp_attention_plan(C.byref(desc), kind, C.byref(cs), C.byref(mc), C.byref(n), items, 1024)
+    if rc != 0:
+        raise StpError(rc, "stp_attention_plan")
+    return cs.value, mc.value, [(items[i] & 0xfff, items[i] >> 12) for i in range(n.value)]
 
 
 class Context:

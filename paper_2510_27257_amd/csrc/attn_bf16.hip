@@ -485,6 +485,10 @@ int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out
 
 }  // namespace
 
+const stp_attn_plan *stp_attn_plan_for(stp_ctx *ctx, const stp_layer_desc *d, int kind) {
+  return kind == 0 ? fwd_plan(ctx, d) : stp_attn_bwd_plan_for(ctx, d, kind);
+}
+
 size_t stp_attn_fwd_ws_bytes(const stp_layer_desc *d) {
   const int nqb = (d->seq + QB - 1) / QB;
   const int max_chunks = fwd_plan(nullptr, d)->max_chunks;
@@ -529,7 +533,8 @@ void plan_make(int kind, int nblocks, const int *steps, int zcount, stp_attn_pla
   int best_c = max_steps;
   double best_t = 1e30;
   std::vector<int> lens;
-  for (int c = lo; c <= max_steps; c++) {
+  const int stride = std::max(1, (max_steps - lo) / 48);      // at most about 48 candidates
+  for (int c = lo; c <= max_steps; c += stride) {
     lens.clear();
     for (int x = 0; x < nblocks; x++) {
       for (int k = 0; k < steps[x] / c; k++) lens.push_back(c);
@@ -558,7 +563,8 @@ void plan_make(int kind, int nblocks, const int *steps, int zcount, stp_attn_pla
 
 const stp_attn_plan *stp_attn_plan_get(stp_ctx *ctx, int kind, const stp_layer_desc *d, int nblocks, const int *steps, int zcount) {
   const int key[8] = {kind + 1, d->seq, d->causal, d->heads_local, stp_kv_heads(d), d->mbsz, d->head_dim, nblocks};
-  static thread_local stp_attn_plan scratch;
+  static thread_local stp_attn_plan scratch_of_kind[3];
+  stp_attn_plan &scratch = scratch_of_kind[kind];
   stp_attn_plan *p = &scratch;
   if (ctx) {
     for (int i = 0; i < ctx->attn_plan_n; i++)

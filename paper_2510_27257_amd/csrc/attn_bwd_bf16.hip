@@ -605,6 +605,10 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
 
 }  // namespace
 
+const stp_attn_plan *stp_attn_bwd_plan_for(stp_ctx *ctx, const stp_layer_desc *d, int kind) {
+  return kind == 1 ? dkv_plan(ctx, d) : dq_plan(ctx, d);
+}
+
 size_t stp_attn_bwd_ws_bytes(const stp_layer_desc *d) {
   const int nkvb = (d->seq + KVB - 1) / KVB, nqb = (d->seq + 127) / 128;
   const int nk = stp_kv_heads(d);

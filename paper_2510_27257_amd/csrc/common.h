@@ -157,6 +157,9 @@ static inline int stp_qkv_width(const stp_layer_desc *d) { return (d->heads_loca
 // x; zcount the number of (head, sequence) pairs that repeat the same blocks.  With a context the plan is
 // cached there (tag: kind and the layer's attention shape); without one it lives in a thread-local slot.
 const stp_attn_plan *stp_attn_plan_get(stp_ctx *ctx, int kind, const stp_layer_desc *d, int nblocks, const int *steps, int zcount);
+// the plan of one kernel for a layer shape (kind as above); bf16 shapes only
+const stp_attn_plan *stp_attn_plan_for(stp_ctx *ctx, const stp_layer_desc *d, int kind);
+const stp_attn_plan *stp_attn_bwd_plan_for(stp_ctx *ctx, const stp_layer_desc *d, int kind);
 
 size_t stp_attn_fwd_ws_bytes(const stp_layer_desc *d);   // workspace the bf16 attention kernels need (chunk partials)
 size_t stp_attn_bwd_ws_bytes(const stp_layer_desc *d);

@@ -132,6 +132,23 @@ extern "C" int stp_workspace_bytes(const stp_layer_desc *d, size_t *bytes) {
   return STP_OK;
 }
 
+extern "C" int stp_attention_plan(const stp_layer_desc *d, int kind, int32_t *chunk_steps, int32_t *max_chunks, int32_t *n_items,
+                                  uint16_t *items, size_t items_cap) {
+  int rc = stp_check_desc(d);
+  if (rc != STP_OK) return rc;
+  if (kind < 0 || kind > 2 || !chunk_steps || !max_chunks || !n_items) return STP_EINVAL;
+  if (d->dtype != STP_BF16) return STP_EUNSUPPORTED;      // the fp32 attention kernels are not chunked
+  const stp_attn_plan *p = stp_attn_plan_for(nullptr, d, kind);
+  *chunk_steps = p->chunk_steps;
+  *max_chunks = p->max_chunks;
+  *n_items = p->n_items;
+  if (items) {
+    if (items_cap < (size_t)p->n_items) return STP_ENOSPACE;
+    for (int i = 0; i < p->n_items; i++) items[i] = p->order.item[i];
+  }
+  return STP_OK;
+}
+
 extern "C" int stp_set_workspace(stp_ctx *ctx, void *p, size_t bytes) {
   if (!ctx) return STP_EINVAL;
   if (p && !stp_aligned16(p)) return stp_fail(ctx, STP_EALIGN, "stp_set_workspace: pointer must be 16-byte aligned%s");
