@@ -507,8 +507,12 @@ namespace {
 // Time of a launch whose workgroups, in the given order, each go to the compute unit that is free first
 // (256 of them, one workgroup each): fixed + per_step * steps per workgroup, every length `zcount` times.
 double plan_makespan(const std::vector<int> &lens, int zcount, double fixed, double per_step) {
+  // many (head, sequence) pairs: 16 of them on a proportionally smaller machine give the same picture
+  // and keep the planning time bounded
+  int cus = 256;
+  if (zcount > 16) { cus = std::max(1, 256 * 16 / zcount); zcount = 16; }
   std::priority_queue<double, std::vector<double>, std::greater<double>> cu;
-  for (int i = 0; i < 256; i++) cu.push(0.0);
+  for (int i = 0; i < cus; i++) cu.push(0.0);
   double end = 0.0;
   for (int len : lens)
     for (int z = 0; z < zcount; z++) {
