@@ -5,11 +5,11 @@
 //     P = exp(S - L),  S = Q K^T / sqrt(d)  (causal: key > query masked)
 //     dV = P^T dO,  dP = dO V^T,  dS = P o (dP - delta),  dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d)
 // Two kernels, both deterministic (no atomics):
-//   * dkv: a workgroup owns 128 keys and one CHUNK of up to 32 steps of 64 queries; 8 waves = 4 key sub-tiles
+//   * dkv: a workgroup owns 128 keys and one CHUNK of steps of 64 queries; 8 waves = 4 key sub-tiles
 //     (32 keys) x 2 halves of each 64-query step.  S and dP are formed with the keys as MFMA columns,
 //     so the accumulator layout of P / dS is already the B-operand layout of dV^T += dO^T P and
 //     dK^T += Q^T dS.  dO^T / Q^T fragments come from the [q][d] tiles through the transposing LDS read.
-//   * dq: a workgroup owns 128 queries and one chunk of up to 16 steps of 128 keys; 8 waves = 4 query sub-tiles
+//   * dq: a workgroup owns 128 queries and one chunk of steps of 128 keys; 8 waves = 4 query sub-tiles
 //     x 2 halves of each 128-key step, with the transposed tiles S^T = K Q^T, dP^T = V dO^T (queries
 //     as MFMA columns: L and delta are per-lane scalars) and dQ^T += K^T dS^T.
 // Grouped-query attention: a key / value head serves n / nk query heads.  dq only changes its tile addresses;
@@ -17,7 +17,7 @@
 // collect the whole group in a fixed order.
 // In both, the two wave halves are summed through LDS, every chunk writes an fp32 partial, and a
 // small combine kernel adds the chunks in a fixed order.  Chunking balances the causal triangle over
-// the 256 compute units; the 8-wave layout puts two waves on every SIMD so one wave's exponentials
+// the 256 compute units (chunk length and dispatch order, longest first, come from the host-side plan); the 8-wave layout puts two waves on every SIMD so one wave's exponentials
 // overlap the other's MFMAs.  S and dP are formed twice (7 matrix products executed for the 5 the
 // method needs): the price of bit-reproducible gradients without atomics.
 // Tiles go global -> LDS directly (buffer_load ... lds) and sit there once, unpadded ([row][D]); the
