@@ -73,6 +73,31 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, 
 // adds them up in a fixed order (deterministic, no float atomics).
 // chunk c of a thread covers elements (c*256 + tid)*8 .. +7
 // ======================================================================
+// Eight elements as loaded, unconverted: what a thread keeps of the NEXT row while it works on the current one.
+template <typename T> struct Raw8;
+template <> struct Raw8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float *p) {
+    a = *reinterpret_cast<const float4 *>(p);
+    b = *reinterpret_cast<const float4 *>(p + 4);
+  }
+  __device__ __forceinline__ void get(float (&v)[8]) const {
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+};
+template <> struct Raw8<bf16_t> {
+  uint4 u;
+  __device__ __forceinline__ void load(const bf16_t *p) { u = *reinterpret_cast<const uint4 *>(p); }
+  __device__ __forceinline__ void get(float (&v)[8]) const {
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      v[2 * i] = __uint_as_float(w[i] << 16);
+      v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+
 template <typename T, int NORM, int NCH>
 __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, const T *__restrict__ gamma,
                                                        const float *__restrict__ stats, const T *__restrict__ dy,
@@ -88,9 +113,28 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, 
     for (int i = 0; i < 8; i++) { gam[c][i] = 0.f; acc_g[c][i] = 0.f; acc_b[c][i] = 0.f; }
     if (col < h) Vec8<T>::load(gamma + col, gam[c]);
   }
+  // A row is one load latency, a reduction over the group and a store; a group works through its rows one
+  // after the other, so the loads of the next row are issued before the current row is touched.
+  Raw8<T> nx[NCH], nd[NCH], nr[NCH];
+  float nmean = 0.f, nrstd = 0.f;
+  auto fetch = [&](int row) {
+    nmean = stats[2 * (size_t)row];
+    nrstd = stats[2 * (size_t)row + 1];
+    const size_t off = (size_t)row * h;
+#pragma unroll
+    for (int c = 0; c < NCH; c++) {
+      int col = (c * 256 + tid) * 8;
+      if (col < h) {
+        nx[c].load(x + off + col);
+        nd[c].load(dy + off + col);
+        if (dres) nr[c].load(dres + off + col);
+      }
+    }
+  };
+  if ((int)blockIdx.x < rows) fetch(blockIdx.x);
   int it = 0;
   for (int row = blockIdx.x; row < rows; row += gridDim.x, it++) {
-    const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
+    const float mean = nmean, rstd = nrstd;
     const size_t off = (size_t)row * h;
     float xh[NCH][8], g[NCH][8], rs[NCH][8];
     float s1 = 0.f, s2 = 0.f;
@@ -99,9 +143,9 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, 
       int col = (c * 256 + tid) * 8;
       if (col < h) {
         float xv[8], dv[8];
-        Vec8<T>::load(x + off + col, xv);
-        Vec8<T>::load(dy + off + col, dv);
-        if (dres) Vec8<T>::load(dres + off + col, rs[c]);   // in flight with the other two, used after the row reduction
+        nx[c].get(xv);
+        nd[c].get(dv);
+        if (dres) nr[c].get(rs[c]);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
           xh[c][i] = (xv[i] - mean) * rstd;
@@ -113,6 +157,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, 
         }
       }
     }
+    if (row + (int)gridDim.x < rows) fetch(row + gridDim.x);
     s1 = wave_sum(s1);
     s2 = wave_sum(s2);
     if (lane == 0) { red[it & 1][wv][0] = s1; red[it & 1][wv][1] = s2; }
