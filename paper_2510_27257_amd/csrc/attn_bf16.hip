@@ -502,6 +502,13 @@ int stp_launch_attn_fwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *
   return stp_fail(ctx, STP_ESHAPE, "bf16 attention needs head_dim 64 or 128%s");
 }
 
+// Cost of a workgroup of the chunked kernels in microseconds (index: 0 forward, 1 dkv, 2 dq): start and end of a
+// workgroup (first tiles, the merge of the wave halves, the partial result) and one step of its main loop; fitted
+// to measured kernel times over chunk lengths 8 .. 32 (16 .. 64 for dkv) at 4 and 10 heads x 128, seq 4096 and
+// 6144, causal, and 16 heads, seq 1024, not causal: the estimate is within 6 - 8 % (rms) and its choice is the
+// fastest chunk length measured, or within 3 % of it.
+static const double kFixedUs[3] = {11.5, 12.0, 12.0}, kStepUs[3] = {1.75, 1.90, 2.65};
+
 namespace {
 
 // Time of a launch whose workgroups, in the given order, each go to the compute unit that is free first
@@ -525,11 +532,7 @@ double plan_makespan(const std::vector<int> &lens, int zcount, double fixed, dou
 }
 
 void plan_make(int kind, int nblocks, const int *steps, int zcount, stp_attn_plan *plan) {
-  // Microseconds per workgroup: start and end of a workgroup (first tiles, the merge of the wave halves, the
-  // partial result) and one step of its main loop; fitted to measured kernel times over chunk lengths 8 .. 32
-  // (16 .. 64 for dkv) at 4 and 10 heads x 128, seq 4096 and 6144, causal, and 16 heads, seq 1024, not causal:
-  // the estimate is within 6 - 8 % (rms) and its choice is the fastest chunk length measured, or within 3 % of it.
-  static const double fixed_us[3] = {11.5, 12.0, 12.0}, step_us[3] = {1.75, 1.90, 2.65};
+  const double *fixed_us = kFixedUs, *step_us = kStepUs;
   int max_steps = 1;
   for (int x = 0; x < nblocks; x++) max_steps = std::max(max_steps, steps[x]);
   // a block is never cut into more than 8 pieces (bounds the workspace and fits the table's 3 chunk bits)
@@ -565,20 +568,29 @@ void plan_make(int kind, int nblocks, const int *steps, int zcount, stp_attn_pla
 
 }  // namespace
 
-const stp_attn_plan *stp_attn_plan_get(stp_ctx *ctx, int kind, const stp_layer_desc *d, int nblocks, const int *steps, int zcount) {
-  const int key[8] = {kind + 1, d->seq, d->causal, d->heads_local, stp_kv_heads(d), d->mbsz, d->head_dim, nblocks};
-  static thread_local stp_attn_plan scratch_of_kind[3];
-  stp_attn_plan &scratch = scratch_of_kind[kind];
-  stp_attn_plan *p = &scratch;
+double stp_attn_item_cost(int kind, int len) { return kFixedUs[kind] + kStepUs[kind] * len; }
+
+stp_attn_plan *stp_attn_plan_slot(stp_ctx *ctx, const int key[8], bool *hit) {
+  static thread_local stp_attn_plan scratch_of_kind[4];
+  stp_attn_plan *p = &scratch_of_kind[(key[0] - 1) & 3];
+  *hit = false;
   if (ctx) {
     for (int i = 0; i < ctx->attn_plan_n; i++)
-      if (memcmp(ctx->attn_plan[i].key, key, sizeof(key)) == 0) return &ctx->attn_plan[i];
+      if (memcmp(ctx->attn_plan[i].key, key, 8 * sizeof(int)) == 0) { *hit = true; return &ctx->attn_plan[i]; }
     if (ctx->attn_plan_n < STP_ATTN_PLAN_CACHE) p = &ctx->attn_plan[ctx->attn_plan_n++];
     else { p = &ctx->attn_plan[ctx->attn_plan_next]; ctx->attn_plan_next = (ctx->attn_plan_next + 1) % STP_ATTN_PLAN_CACHE; }
-  } else if (memcmp(scratch.key, key, sizeof(key)) == 0) {
-    return &scratch;
+  } else if (memcmp(p->key, key, 8 * sizeof(int)) == 0) {
+    *hit = true;
+    return p;
   }
-  plan_make(kind, nblocks, steps, zcount, p);
-  memcpy(p->key, key, sizeof(key));
+  memcpy(p->key, key, 8 * sizeof(int));
+  return p;
+}
+
+const stp_attn_plan *stp_attn_plan_get(stp_ctx *ctx, int kind, const stp_layer_desc *d, int nblocks, const int *steps, int zcount) {
+  const int key[8] = {kind + 1, d->seq, d->causal, d->heads_local, stp_kv_heads(d), d->mbsz, d->head_dim, nblocks};
+  bool hit;
+  stp_attn_plan *p = stp_attn_plan_slot(ctx, key, &hit);
+  if (!hit) plan_make(kind, nblocks, steps, zcount, p);
   return p;
 }

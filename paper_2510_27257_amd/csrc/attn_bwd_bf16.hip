@@ -30,6 +30,7 @@
 #include "lds_dma.h"
 #include <type_traits>
 #include <vector>
+#include <algorithm>
 
 int stp_launch_rowdot(stp_ctx *ctx, const stp_layer_desc *d, const void *a, const void *b, float *delta, hipStream_t s);
 
@@ -117,11 +118,10 @@ __host__ __device__ inline int dq_steps(int qb, int seq, int causal) {
 // ring of { lse [64], delta [64] } (fp32).
 // ---------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
-                                                           const float *__restrict__ lse, const float *__restrict__ delta,
-                                                           float *__restrict__ part, int seq, int n, int nk, int causal,
-                                                           int max_chunks, int chunk_steps, float scale, int n_items,
-                                                           stp_attn_order ord) {
+__device__ __forceinline__ void dkv_body(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
+                                         const float *__restrict__ lse, const float *__restrict__ delta,
+                                         float *__restrict__ part, int seq, int n, int nk, int causal, int max_chunks,
+                                         int chunk_steps, float scale, int kvb, int chunk, int bz) {
   using G = BG<D>;
   constexpr int RB = G::RB;
   constexpr int KV_TILE = KVB * RB, Q_TILE = QSTEP * RB, STAGE = 2 * Q_TILE;
@@ -131,11 +131,6 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lg = lane >> 5;
   const int ksub = wave & 3, qhalf = wave >> 2;
-  // the workgroup's (key block, chunk): from the launch's work order (grid = heads x items), or, without one,
-  // from a grid of blocks x chunks x heads (key block 0 owns the most chunks and comes first)
-  const int item = n_items ? ord.item[blockIdx.y] : 0;
-  const int kvb = n_items ? (item & 0xfff) : (int)blockIdx.x, chunk = n_items ? (item >> 12) : (int)blockIdx.y;
-  const int bz = n_items ? blockIdx.x : blockIdx.z;
   const int kh = bz % nk, b = bz / nk;                     // key / value head
   const int group = n / nk;                                // query heads kh*group .. kh*group+group-1 share it
   const int nq = (seq + QSTEP - 1) / QSTEP;
@@ -316,6 +311,20 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restr
   }
 }
 
+// One workgroup per (key block, chunk): from the launch's work order (grid = heads x items), or, without one,
+// from a grid of blocks x chunks x heads (key block 0 owns the most chunks and comes first).
+template <int D>
+__global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
+                                                           const float *__restrict__ lse, const float *__restrict__ delta,
+                                                           float *__restrict__ part, int seq, int n, int nk, int causal,
+                                                           int max_chunks, int chunk_steps, float scale, int n_items,
+                                                           stp_attn_order ord) {
+  const int item = n_items ? ord.item[blockIdx.y] : 0;
+  const int kvb = n_items ? (item & 0xfff) : (int)blockIdx.x, chunk = n_items ? (item >> 12) : (int)blockIdx.y;
+  const int bz = n_items ? blockIdx.x : blockIdx.z;
+  dkv_body<D>(qkv, dout, lse, delta, part, seq, n, nk, causal, max_chunks, chunk_steps, scale, kvb, chunk, bz);
+}
+
 // dK = scale * sum_c, dV = sum_c over the chunks of a key block (fixed order).  One thread per 8 columns of a key row.
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ dqkv,
@@ -350,10 +359,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_combine_kernel(const float *
 // dQ partials.  piece layout: dQ [128][D] fp32 (unscaled)
 // ---------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
-                                                          const float *__restrict__ lse, const float *__restrict__ delta,
-                                                          float *__restrict__ part, int seq, int n, int nk, int causal, int max_chunks,
-                                                          int chunk_steps, float scale, int n_items, stp_attn_order ord) {
+__device__ __forceinline__ void dq_body(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
+                                        const float *__restrict__ lse, const float *__restrict__ delta,
+                                        float *__restrict__ part, int seq, int n, int nk, int causal, int max_chunks,
+                                        int chunk_steps, float scale, int qb, int chunk, int bz) {
   using G = BG<D>;
   constexpr int RB = G::RB;
   constexpr int KV_TILE = KVB * RB, STAGE = 2 * KV_TILE;      // LDS: ring of two stages { K [128][D], V [128][D] }
@@ -363,12 +372,6 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
   const int lr = lane & 31, lg = lane >> 5;
   const int qsub = wave & 3, half = wave >> 2;
   const int nqblk = (seq + 127) / 128;
-  // the workgroup's (query block, chunk): from the launch's work order (grid = heads x items), or, without
-  // one, from a grid of blocks x chunks x heads with the late query blocks, which own the most chunks, first
-  const int item = n_items ? ord.item[blockIdx.y] : 0;
-  const int qb = n_items ? (item & 0xfff) : nqblk - 1 - (int)blockIdx.x;
-  const int chunk = n_items ? (item >> 12) : (int)blockIdx.y;
-  const int bz = n_items ? blockIdx.x : blockIdx.z;
   const int head = bz % n, b = bz / n;
   const int nsteps = dq_steps(qb, seq, causal);
   const int s_begin = chunk * chunk_steps, s_end = min(nsteps, s_begin + chunk_steps);
@@ -515,6 +518,36 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
   }
 }
 
+// One workgroup per (query block, chunk): from the launch's work order (grid = heads x items), or, without
+// one, from a grid of blocks x chunks x heads with the late query blocks, which own the most chunks, first.
+template <int D>
+__global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
+                                                          const float *__restrict__ lse, const float *__restrict__ delta,
+                                                          float *__restrict__ part, int seq, int n, int nk, int causal, int max_chunks,
+                                                          int chunk_steps, float scale, int n_items, stp_attn_order ord) {
+  const int nqblk = (seq + 127) / 128;
+  const int item = n_items ? ord.item[blockIdx.y] : 0;
+  const int qb = n_items ? (item & 0xfff) : nqblk - 1 - (int)blockIdx.x;
+  const int chunk = n_items ? (item >> 12) : (int)blockIdx.y;
+  const int bz = n_items ? blockIdx.x : blockIdx.z;
+  dq_body<D>(qkv, dout, lse, delta, part, seq, n, nk, causal, max_chunks, chunk_steps, scale, qb, chunk, bz);
+}
+
+// Both kernels in one launch (same number of query and key / value heads): a work item is a dkv or a dq
+// (block, chunk) pair, item = block | chunk << 12 | (1 << 15 for dq), sorted by estimated time, longest first.
+// The two kinds fill each other's idle compute units: their workgroups are few and of unequal length.
+template <int D>
+__global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
+                                                             const float *__restrict__ lse, const float *__restrict__ delta,
+                                                             float *__restrict__ part_kv, float *__restrict__ part_q, int seq, int n,
+                                                             int nk, int causal, int mc_kv, int ch_kv, int mc_q, int ch_q, float scale,
+                                                             stp_attn_order ord) {
+  const int item = ord.item[blockIdx.y];
+  const int block = item & 0xfff, chunk = (item >> 12) & 7, bz = blockIdx.x;
+  if (item & 0x8000) dq_body<D>(qkv, dout, lse, delta, part_q, seq, n, nk, causal, mc_q, ch_q, scale, block, chunk, bz);
+  else dkv_body<D>(qkv, dout, lse, delta, part_kv, seq, n, nk, causal, mc_kv, ch_kv, scale, block, chunk, bz);
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dq_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ dqkv,
                                                                   int seq, int n, int nk, int mbsz, int causal, int max_chunks,
@@ -556,48 +589,89 @@ inline const stp_attn_plan *dq_plan(stp_ctx *ctx, const stp_layer_desc *d) {
   return stp_attn_plan_get(ctx, 2, d, nqb, steps.data(), d->heads_local * d->mbsz);
 }
 
+// The merged work order of the fused launch: the (block, chunk) pairs of both kernels, sorted by the plan's
+// estimate of their time, longest first (ties keep dkv before dq and each kernel's own order).
+const stp_attn_plan *fused_plan(stp_ctx *ctx, const stp_layer_desc *d, const stp_attn_plan &pkv, const stp_attn_plan &pq) {
+  const int key[8] = {4, d->seq, d->causal, d->heads_local, stp_kv_heads(d), d->mbsz, d->head_dim, 0};
+  bool hit;
+  stp_attn_plan *p = stp_attn_plan_slot(ctx, key, &hit);
+  if (hit) return p;
+  const int nq = (d->seq + QSTEP - 1) / QSTEP, group = d->heads_local / stp_kv_heads(d);
+  struct Item { double cost; uint16_t item; };
+  std::vector<Item> items;
+  for (int i = 0; i < pkv.n_items; i++) {
+    const int x = pkv.order.item[i] & 0xfff, k = pkv.order.item[i] >> 12;
+    const int steps = group * (nq - dkv_first_step(x, d->causal));
+    items.push_back({stp_attn_item_cost(1, std::min(pkv.chunk_steps, steps - k * pkv.chunk_steps)), pkv.order.item[i]});
+  }
+  for (int i = 0; i < pq.n_items; i++) {
+    const int x = pq.order.item[i] & 0xfff, k = pq.order.item[i] >> 12;
+    const int steps = dq_steps(x, d->seq, d->causal);
+    items.push_back({stp_attn_item_cost(2, std::min(pq.chunk_steps, steps - k * pq.chunk_steps)), (uint16_t)(pq.order.item[i] | 0x8000)});
+  }
+  std::stable_sort(items.begin(), items.end(), [](const Item &u, const Item &v) { return u.cost > v.cost; });
+  p->chunk_steps = 0;
+  p->max_chunks = 0;
+  p->n_items = (int)items.size();
+  for (size_t i = 0; i < items.size(); i++) p->order.item[i] = items[i].item;
+  return p;
+}
+
 template <int D>
 int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const float *lse, const void *dout, const float *delta,
                void *dqkv, float *ws, size_t ws_bytes, hipStream_t s) {
   using G = BG<D>;
   constexpr size_t smem_kv = (size_t)(2 * KVB + 4 * QSTEP) * G::RB + 2 * 512;   // K, V, ring of {Q, dO}, ring of {lse, delta}
   constexpr size_t smem_q = (size_t)4 * KVB * G::RB;                              // ring of {K, V}
+  constexpr size_t smem_f = smem_kv > smem_q ? smem_kv : smem_q;
   static_assert(smem_kv <= 160 * 1024 && smem_kv >= (size_t)4 * D * 64 * sizeof(float), "dkv LDS budget");
   static_assert(smem_q <= 160 * 1024 && smem_q >= (size_t)4 * (D / 2) * 64 * sizeof(float), "dq LDS budget");
   if ((size_t)d->seq * stp_qkv_width(d) * sizeof(bf16_t) > (size_t)0x7fffffff)
     return stp_fail(ctx, STP_ESHAPE, "attention backward: one sequence of QKV must span less than 2 GiB%s");
   auto kkv = attn_bwd_dkv_kernel<D>;
   auto kq = attn_bwd_dq_kernel<D>;
+  auto kf = attn_bwd_fused_kernel<D>;
   static bool attr_set = false;
   if (!attr_set) {
     STP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kkv), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_kv));
     STP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kq), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_q));
+    STP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kf), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_f));
     attr_set = true;
   }
   const float scale = 1.0f / sqrtf((float)D);
   const int nkvb = (d->seq + KVB - 1) / KVB, nqb = (d->seq + 127) / 128;
-  const int nk = stp_kv_heads(d), group = d->heads_local / nk;
-  // copies: the second lookup may evict the first plan from the context's cache
+  const int nk = stp_kv_heads(d);
+  // copies: a later lookup may evict an earlier plan from the context's cache
   const stp_attn_plan pkv = *dkv_plan(ctx, d), pq = *dq_plan(ctx, d);
   const int ch_kv = pkv.chunk_steps, ch_q = pq.chunk_steps, mc_kv = pkv.max_chunks, mc_q = pq.max_chunks;
   const size_t bh = (size_t)d->mbsz * d->heads_local, bk = (size_t)d->mbsz * nk;
-  const size_t need_kv = bk * nkvb * mc_kv * 2 * KVB * D * sizeof(float), need_q = bh * nqb * mc_q * 128 * D * sizeof(float);
-  const size_t need = need_kv > need_q ? need_kv : need_q;
+  // the partials of the two kernels lie one behind the other: with equal head counts both run in one launch
+  const size_t need_kv = stp_align_up(bk * nkvb * mc_kv * 2 * KVB * D * sizeof(float), 256), need_q = bh * nqb * mc_q * 128 * D * sizeof(float);
+  const size_t need = need_kv + need_q;
   if (!ws || ws_bytes < need)
     return stp_fail(ctx, STP_ENOSPACE, "attention backward: workspace lane too small%s (need %ld bytes)", "", (long)need);
+  float *ws_kv = ws, *ws_q = ws + need_kv / sizeof(float);
   const size_t rows8 = bh * d->seq * (D / 8), rows8_kv = bk * d->seq * (D / 8);
-  hipLaunchKernelGGL(kkv, pkv.n_items ? dim3((unsigned)bk, pkv.n_items) : dim3(nkvb, mc_kv, (unsigned)bk), dim3(512), smem_kv, s,
-                     (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta, ws, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv, scale,
-                     pkv.n_items, pkv.order);
-  STP_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(attn_bwd_dkv_combine_kernel<D>, dim3((rows8_kv + 255) / 256), dim3(256), 0, s, ws, (bf16_t *)dqkv, d->seq,
+  const bool fused = bk == bh && pkv.n_items && pq.n_items && pkv.n_items + pq.n_items <= STP_ATTN_ORDER_CAP;
+  if (fused) {
+    const stp_attn_plan *pf = fused_plan(ctx, d, pkv, pq);
+    hipLaunchKernelGGL(kf, dim3((unsigned)bh, pf->n_items), dim3(512), smem_f, s, (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta,
+                       ws_kv, ws_q, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv, mc_q, ch_q, scale, pf->order);
+    STP_LAUNCH_CHECK(ctx);
+  } else {
+    hipLaunchKernelGGL(kkv, pkv.n_items ? dim3((unsigned)bk, pkv.n_items) : dim3(nkvb, mc_kv, (unsigned)bk), dim3(512), smem_kv, s,
+                       (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta, ws_kv, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv,
+                       scale, pkv.n_items, pkv.order);
+    STP_LAUNCH_CHECK(ctx);
+    hipLaunchKernelGGL(kq, pq.n_items ? dim3((unsigned)bh, pq.n_items) : dim3(nqb, mc_q, (unsigned)bh), dim3(512), smem_q, s,
+                       (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta, ws_q, d->seq, d->heads_local, nk, d->causal, mc_q, ch_q, scale,
+                       pq.n_items, pq.order);
+    STP_LAUNCH_CHECK(ctx);
+  }
+  hipLaunchKernelGGL(attn_bwd_dkv_combine_kernel<D>, dim3((rows8_kv + 255) / 256), dim3(256), 0, s, ws_kv, (bf16_t *)dqkv, d->seq,
                      d->heads_local, nk, d->mbsz, d->causal, mc_kv, ch_kv, scale);
   STP_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(kq, pq.n_items ? dim3((unsigned)bh, pq.n_items) : dim3(nqb, mc_q, (unsigned)bh), dim3(512), smem_q, s,
-                     (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta, ws, d->seq, d->heads_local, nk, d->causal, mc_q, ch_q, scale,
-                     pq.n_items, pq.order);
-  STP_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(attn_bwd_dq_combine_kernel<D>, dim3((rows8 + 255) / 256), dim3(256), 0, s, ws, (bf16_t *)dqkv, d->seq,
+  hipLaunchKernelGGL(attn_bwd_dq_combine_kernel<D>, dim3((rows8 + 255) / 256), dim3(256), 0, s, ws_q, (bf16_t *)dqkv, d->seq,
                      d->heads_local, nk, d->mbsz, d->causal, mc_q, ch_q, scale);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
@@ -613,9 +687,9 @@ size_t stp_attn_bwd_ws_bytes(const stp_layer_desc *d) {
   const int nkvb = (d->seq + KVB - 1) / KVB, nqb = (d->seq + 127) / 128;
   const int nk = stp_kv_heads(d);
   const size_t bh = (size_t)d->mbsz * d->heads_local, bk = (size_t)d->mbsz * nk;
-  const size_t need_kv = bk * nkvb * dkv_plan(nullptr, d)->max_chunks * 2 * KVB * d->head_dim * sizeof(float);
+  const size_t need_kv = stp_align_up(bk * nkvb * dkv_plan(nullptr, d)->max_chunks * 2 * KVB * d->head_dim * sizeof(float), 256);
   const size_t need_q = bh * nqb * dq_plan(nullptr, d)->max_chunks * 128 * d->head_dim * sizeof(float);
-  return need_kv > need_q ? need_kv : need_q;
+  return need_kv + need_q;
 }
 
 int stp_launch_attn_bwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const void *out, const float *lse,

@@ -157,6 +157,10 @@ static inline int stp_qkv_width(const stp_layer_desc *d) { return (d->heads_loca
 // x; zcount the number of (head, sequence) pairs that repeat the same blocks.  With a context the plan is
 // cached there (tag: kind and the layer's attention shape); without one it lives in a thread-local slot.
 const stp_attn_plan *stp_attn_plan_get(stp_ctx *ctx, int kind, const stp_layer_desc *d, int nblocks, const int *steps, int zcount);
+// the context's (or, without one, the thread's) cache slot for a plan with this tag; *hit says whether it is filled
+stp_attn_plan *stp_attn_plan_slot(stp_ctx *ctx, const int key[8], bool *hit);
+// the plan's estimate of a workgroup's time in microseconds: `len` steps of a kernel of this kind
+double stp_attn_item_cost(int kind, int len);
 // the plan of one kernel for a layer shape (kind as above); bf16 shapes only
 const stp_attn_plan *stp_attn_plan_for(stp_ctx *ctx, const stp_layer_desc *d, int kind);
 const stp_attn_plan *stp_attn_bwd_plan_for(stp_ctx *ctx, const stp_layer_desc *d, int kind);
