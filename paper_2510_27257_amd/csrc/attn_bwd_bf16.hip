@@ -4,7 +4,8 @@
 // Given Q, K, V, the forward's log-sum-exp L and delta = rowsum(dO o O):
 //     P = exp(S - L),  S = Q K^T / sqrt(d)  (causal: key > query masked)
 //     dV = P^T dO,  dP = dO V^T,  dS = P o (dP - delta),  dQ = dS K / sqrt(d),  dK = dS^T Q / sqrt(d)
-// Two kernels, both deterministic (no atomics):
+// Two kernel bodies, both deterministic (no atomics), run by one launch when the query and key / value head
+// counts are equal (their workgroups then fill each other's idle compute units) and by two launches otherwise:
 //   * dkv: a workgroup owns 128 keys and one CHUNK of steps of 64 queries; 8 waves = 4 key sub-tiles
 //     (32 keys) x 2 halves of each 64-query step.  S and dP are formed with the keys as MFMA columns,
 //     so the accumulator layout of P / dS is already the B-operand layout of dV^T += dO^T P and
