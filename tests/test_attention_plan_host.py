@@ -95,3 +95,28 @@ def test_plan_rejects_bad_arguments():
     assert L.stp_attention_plan(C.byref(desc), 0, C.byref(a), C.byref(b), C.byref(n), small, 4) == 4      # STP_ENOSPACE
     f32 = stp.make_desc(WORKLOADS["tiny"])
     assert L.stp_attention_plan(C.byref(f32), 0, C.byref(a), C.byref(b), C.byref(n), None, 0) == 6        # STP_EUNSUPPORTED
+
+
+def test_plan_invariants_on_random_shapes():
+    """Seeded random shapes (sequence length, head counts, grouping, causal or not): the same invariants."""
+    import random
+    rng = random.Random(20251027)
+    for _ in range(60):
+        seq = rng.choice([8, 64, 72, 128, 136, 1000, 2048, 4096, 5000, 12288]) if rng.random() < 0.6 else 8 * rng.randint(1, 2500)
+        nk = rng.choice([1, 2, 4, 8])
+        group = rng.choice([1, 1, 2, 5])
+        heads = nk * group
+        wl = Workload("r", 512, heads, rng.choice([64, 128]), 512, seq, 8, causal=rng.random() < 0.7, kv_heads=nk if group > 1 else 0)
+        desc = stp.make_desc(wl, mbsz=rng.choice([1, 1, 2]))
+        for kind in (stp.ATTN_FWD, stp.ATTN_DKV, stp.ATTN_DQ):
+            c, max_chunks, items = stp.attention_plan(desc, kind)
+            steps = steps_of(wl, kind)
+            assert c >= 1 and 1 <= max_chunks <= 8, (seq, heads, nk, kind)
+            assert max_chunks == max((s + c - 1) // c for s in steps)
+            want = {(x, k) for x, s in enumerate(steps) for k in range((s + c - 1) // c)}
+            if len(want) > 1024:
+                assert items == []
+                continue
+            assert len(items) == len(want) and set(items) == want
+            lens = [min(c, steps[x] - k * c) for x, k in items]
+            assert lens == sorted(lens, reverse=True) and sum(lens) == sum(steps)
