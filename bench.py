@@ -365,7 +365,8 @@ def main():
     hbm = hbm_leg(ctx, wl, torch, stp)
 
     result = {
-        "metric": "braided F/B/W TFLOP/s + MFMA util, 7B layer TP=8 shard, seq 6144, 1 GPU",
+        "metric": ("braided F/B/W TFLOP/s + MFMA util, 7B layer TP=8 shard, seq 6144, 1 GPU" if args.workload == "gpt7b_tp8"
+                   else f"braided F/B/W TFLOP/s + MFMA util, workload {args.workload}, 1 GPU"),
         "value": total_flops / (ms_braided * 1e-3) / 1e12,
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
