@@ -229,7 +229,12 @@ int stp_backward_weight_unit(stp_ctx *ctx, const stp_layer_desc *desc, int unit,
  * BW ops to microbatches j < i (Appendix A) unless the list has no F op; units
  * of one direction appear in dependence order; a W op needs its B in this list
  * or in an earlier step.  Passing the same stream three times serialises the
- * step (used to check braided == sequential bit for bit). */
+ * step (used to check braided == sequential bit for bit).
+ * STP_ESHAPE: two consecutive layers with no chain break between them differ in
+ * tokens (seq * mbsz), hidden or dtype (the first writes into the second's input
+ * slot).  STP_EUNSUPPORTED: one of the streams is being captured into a HIP graph.
+ * Every host-side condition of the list is checked before the first launch; B
+ * units count as run (for later W ops) only when the whole step was issued. */
 int stp_braid_step(stp_ctx *ctx, const stp_stage *stage, const stp_op *ops, size_t n_ops,
                    void *s_fwd, void *s_bwd, void *s_wgrad, stp_boundary_fn cb, void *user);
 /* Validation alone (host only, no GPU needed); *bad_index gets the offending op. */
@@ -238,11 +243,9 @@ int stp_validate_ops(const stp_stage *stage, const stp_op *ops, size_t n_ops, si
 int stp_braid_reset(stp_ctx *ctx);
 /* The next stp_braid_step does not wait for the step before it: for a caller that has ordered the three
  * streams itself since then (a device synchronisation, say).
- * Stream capture: stp_braid_step only enqueues kernels, event records and event waits (no allocation, no
- * memset, no synchronisation), but recording three-stream steps into a HIP graph is NOT supported: the one
- * attempt (capture begun on s_fwd, the other two streams forked from it and joined to it by events, steps
- * detached before and after) crashed the host process inside the runtime when the capture ended, before
- * any replay, and the cause is not known. */
+ * Stream capture: recording three-stream steps into a HIP graph is NOT supported (the one attempt crashed the
+ * host process inside the runtime when the capture ended, and the cause is not known); stp_braid_step returns
+ * STP_EUNSUPPORTED when any of its streams is capturing. */
 int stp_braid_detach(stp_ctx *ctx);
 
 /* ---- activation offload and reload (Section 4.2, last paragraph; Section 4.3) --------------------

@@ -265,6 +265,8 @@ class Context:
         import torch
         need = max(self.workspace_bytes(d) for d in descs)
         if self._ws is None or self._ws.numel() < need:
+            # kernels already enqueued on any stream may still use the old block (and its lane offsets)
+            torch.cuda.synchronize()
             self.set_workspace(torch.empty(need, dtype=torch.uint8, device="cuda"))
 
     # ---- units ---------------------------------------------------------------

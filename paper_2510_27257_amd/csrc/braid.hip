@@ -40,6 +40,13 @@ int validate(const stp_stage *st, const stp_op *ops, size_t n, const uint8_t *b_
   if (!st || (!ops && n)) return STP_EINVAL;
   if (st->n_layers < 1 || st->n_microbatches < 1 || !st->desc) return STP_EINVAL;
   const int L = st->n_layers, MB = st->n_microbatches;
+  // a layer's output is written straight into the next layer's input slot (and the gradient the other way):
+  // the two descriptions must agree on the extent and type of that slot unless a chain break separates them
+  for (int l = 0; l + 1 < L; l++) {
+    if (st->chain_break && st->chain_break[l + 1]) continue;
+    const stp_layer_desc &a = st->desc[l], &b = st->desc[l + 1];
+    if ((long)a.seq * a.mbsz != (long)b.seq * b.mbsz || a.hidden != b.hidden || a.dtype != b.dtype) return STP_ESHAPE;
+  }
   int f_mb = -1;
   Cursor fcur = {0, 0, false};
   Cursor *bcur = (Cursor *)calloc(MB, sizeof(Cursor));
@@ -155,10 +162,29 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
     if (rc != STP_OK) return stp_fail(ctx, rc, "stp_braid_step: layer description rejected%s (layer %ld)", "", (long)l);
   }
   if (n_ops == 0) return STP_OK;
+  // every host-side condition of the whole list is checked before the first launch: a step is issued whole or not at all
+  for (size_t i = 0; i < n_ops; i++) {
+    const stp_op &o = ops[i];
+    if (!st->stash[(size_t)o.layer * MB + o.microbatch].base)
+      return stp_fail(ctx, STP_EINVAL, "stp_braid_step: null stash%s (op %ld)", "", (long)i);
+    const bool tail = o.layer + 1 < L && st->chain_break && st->chain_break[o.layer + 1];
+    if (tail && (!st->tail_act || !st->tail_grad))
+      return stp_fail(ctx, STP_EINVAL, "stp_braid_step: chain break without tail slots%s (op %ld)", "", (long)i);
+  }
 
   hipStream_t sF = (hipStream_t)s_fwd, sB = (hipStream_t)s_bwd, sW = (hipStream_t)s_wgrad;
   const bool serial = (sF == sB) && (sB == sW);
   hipStream_t streams[3] = {sF, sB, sW};
+  // Recording braid steps into a HIP graph is not supported (see stp.h): refuse a capturing stream with a status.
+  for (int i = 0; i < 3; i++) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(streams[i], &cs) != hipSuccess) {
+      (void)hipGetLastError();
+      return stp_fail(ctx, STP_EHIP, "stp_braid_step: hipStreamIsCapturing failed%s");
+    }
+    if (cs != hipStreamCaptureStatusNone)
+      return stp_fail(ctx, STP_EUNSUPPORTED, "stp_braid_step: a stream is being captured into a HIP graph; that is not supported%s");
+  }
   rc = ensure_events(ctx, (int)n_ops);
   if (rc != STP_OK) return rc;
   // join with the previous step: its stashes and gradients may be read by any stream now
@@ -168,7 +194,8 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
         if (streams[i] != streams[j]) STP_HIP(ctx, hipStreamWaitEvent(streams[i], ctx->ev_step[j], 0));
   }
   int *ev_of = (int *)malloc(sizeof(int) * bsz);
-  if (!ev_of) return stp_fail(ctx, STP_ENOSPACE, "out of host memory%s");
+  uint8_t *b_now = (uint8_t *)calloc(bsz, 1);      // B units issued by this step; committed to the context when the step is whole
+  if (!ev_of || !b_now) { free(ev_of); free(b_now); return stp_fail(ctx, STP_ENOSPACE, "out of host memory%s"); }
   for (size_t i = 0; i < bsz; i++) ev_of[i] = -1;
   int ev_used = 0;
   rc = STP_OK;
@@ -180,14 +207,12 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
     const stp_weights *w = &st->w[o.layer];
     stp_wgrads *g = &st->g[o.layer];
     const stp_stash *stash = &st->stash[(size_t)o.layer * MB + o.microbatch];
-    if (!stash->base) { rc = stp_fail(ctx, STP_EINVAL, "stp_braid_step: null stash%s"); break; }
     size_t off[STP_ST_NFIELDS], nbytes;
     for (int f = 0; f < STP_ST_NFIELDS; f++) stp_stash_field(d, f, &off[f], &nbytes);
     char *sb = (char *)stash->base;
     void *x = st->act[(size_t)o.layer * MB + o.microbatch];
     // a layer that ends a chain in the middle of the stage has its own output / upstream-gradient slots
     const bool tail = o.layer + 1 < L && st->chain_break && st->chain_break[o.layer + 1];
-    if (tail && (!st->tail_act || !st->tail_grad)) { rc = stp_fail(ctx, STP_EINVAL, "stp_braid_step: chain break without tail slots%s"); break; }
     void *x_out = tail ? st->tail_act[(size_t)o.layer * MB + o.microbatch] : st->act[(size_t)(o.layer + 1) * MB + o.microbatch];
     void *dx = st->grad[(size_t)o.layer * MB + o.microbatch];
     void *dx_out = tail ? st->tail_grad[(size_t)o.layer * MB + o.microbatch] : st->grad[(size_t)(o.layer + 1) * MB + o.microbatch];
@@ -227,7 +252,7 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
       }
       if (rc != STP_OK) break;
       if (has_w) {
-        ctx->b_done[slot] = 1;
+        b_now[slot] = 1;
         if (!serial && sW != sB) {
           hipError_t e = hipEventRecord(ctx->ev_pool[ev_used], sB);
           if (e != hipSuccess) { rc = stp_fail(ctx, STP_EHIP, "hipEventRecord failed: %s", hipGetErrorString(e)); break; }
@@ -246,12 +271,17 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
   }
   free(ev_of);
   ctx->concurrent = 0;
-  if (rc != STP_OK) return rc;
+  // The end-of-step events are recorded on the error path too: whatever part of the step was enqueued, the next
+  // step still joins all three streams.  The B units count as done only when the whole step was issued.
   if (!serial) {
     for (int i = 0; i < 3; i++) {
-      STP_HIP(ctx, hipEventRecord(ctx->ev_step[i], streams[i]));
+      const hipError_t e = hipEventRecord(ctx->ev_step[i], streams[i]);
+      if (e != hipSuccess && rc == STP_OK) rc = stp_fail(ctx, STP_EHIP, "hipEventRecord failed: %s", hipGetErrorString(e));
     }
   }
   ctx->ev_next = 1;
-  return STP_OK;
+  if (rc == STP_OK)
+    for (size_t i = 0; i < bsz; i++) ctx->b_done[i] |= b_now[i];
+  free(b_now);
+  return rc;
 }

@@ -121,6 +121,29 @@ def test_validator_chain_breaks():
     assert _validate(st, [Op(OP_B, PRE_ATTN, 2, 0), Op(OP_B, MLP, 0, 0)])[0] == 5
 
 
+def test_validator_rejects_chained_layers_of_different_extent():
+    """A layer writes its output into the next layer's input slot, so without a chain break the two layer
+    descriptions must agree in tokens, hidden size and element type (the ViT -> LM junction of a heterogeneous
+    stage needs a chain break)."""
+    ESHAPE = 2
+    small, big = stp.make_desc(synth.WORKLOADS["tiny"]), stp.make_desc(synth.WORKLOADS["tiny"])
+    big.hidden, big.heads_local = 512, 8
+    ops = [Op(OP_F, PRE_ATTN, 0, 0)]
+    for field, value in [("hidden", 512), ("seq", 256), ("dtype", stp.BF16)]:
+        other = stp.make_desc(synth.WORKLOADS["tiny"])
+        setattr(other, field, value)
+        descs = (stp.LayerDesc * 2)(small, other)
+        st = stp.Stage(n_layers=2, n_microbatches=1, desc=descs)
+        assert _validate(st, ops)[0] == ESHAPE, field
+        cb = (C.c_int32 * 3)(0, 1, 0)
+        st = stp.Stage(n_layers=2, n_microbatches=1, desc=descs, chain_break=cb)
+        assert _validate(st, ops)[0] == 0, field
+    # the same tokens split differently over seq and mbsz chain fine
+    other = stp.make_desc(synth.WORKLOADS["tiny"], mbsz=2, seq=64)
+    descs = (stp.LayerDesc * 2)(small, other)
+    assert _validate(stp.Stage(n_layers=2, n_microbatches=1, desc=descs), ops)[0] == 0
+
+
 # ---- op-list variants: warm-up depth (Appendix A) and the two pairing patterns of Section 4.1 -------------
 def _census(steps):
     """How often each (kind-of-work, unit, layer, microbatch) is issued; BW counts as a B and a W."""
