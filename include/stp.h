@@ -341,7 +341,15 @@ int stp_rope(stp_ctx *ctx, const stp_layer_desc *desc, void *qkv, int inverse, v
 /* out[N] += scale * sum over rows of x[T,N]  (bias gradients). */
 int stp_colsum(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const void *x, float scale, float *out,
                int lane, void *hip_stream);
-
+/* The same column sum for callers that cannot allocate device memory or supply a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the stage-1 partials go to a fixed
+ * 4 MiB array inside the library's device image instead of a workspace lane, so the call needs no
+ * stp_set_workspace and performs no allocation.  Limit: ceil(T / 64) * N <= 1048576 (STP_ENOSPACE beyond it;
+ * [6144, 4096] bf16 uses 393216).  Same kernels, same bits as stp_colsum.  Every call on one GPU shares that
+ * GPU's array: calls that may overlap on one GPU (different streams) race; calls on one stream do not.
+ * Nothing needs clearing between calls: the first kernel writes every partial the second one reads. */
+int stp_colsum_noalloc(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const void *x, float scale, float *out,
+                       void *hip_stream);
 
 /* Measurement aid: enqueues a one-wave kernel that spins for `milliseconds` of wall-clock time and
  * writes {shader-clock cycles elapsed, wall-clock ticks elapsed} to device_out2[0..1] (int64; the wall

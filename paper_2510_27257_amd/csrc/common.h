@@ -170,6 +170,8 @@ size_t stp_attn_bwd_ws_bytes(const stp_layer_desc *d);
 int stp_launch_attn_fwd_generic(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out, float *lse, hipStream_t s);
 int stp_launch_attn_bwd_generic(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const void *out, const float *lse,
                                 const void *dout, float *delta, void *dqkv, hipStream_t s);
+// device address of the fixed scratch array of stp_colsum_noalloc on `device` (the current device); a lookup, no allocation
+int stp_noalloc_init(stp_ctx *ctx, int device);
 // workspace lane: a third of the caller's workspace
 static inline char *stp_ws_lane(stp_ctx *ctx, int lane, size_t *bytes) {
   size_t third = (ctx->ws_bytes / 3) & ~(size_t)255;

@@ -528,6 +528,55 @@ extern "C" int stp_colsum(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const v
   return STP_OK;
 }
 
+// ======================================================================
+// Column sum without the caller's workspace, for callers that cannot allocate device memory or hand a
+// workspace over (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+// the stage-1 partials live in a fixed array in the library's device image.  Each GPU the library runs on
+// holds its own copy of the array at its own address; the address is looked up once per device.
+// ======================================================================
+#define STP_NOALLOC_SCRATCH_FLOATS (1u << 20)            // 4 MiB: ceil(T / 64) * N partial sums at most
+#define STP_NOALLOC_MAX_DEVICES 16
+static __device__ __align__(256) float scratch[STP_NOALLOC_SCRATCH_FLOATS];
+static float *g_scratch_ptr[STP_NOALLOC_MAX_DEVICES];    // device address of `scratch` per device; the array's name is no address on the host
+
+// Looks up the device address of the scratch array on `device` (which must be the current device).
+int stp_noalloc_init(stp_ctx *ctx, int device) {
+  if (device < 0 || device >= STP_NOALLOC_MAX_DEVICES) return stp_fail(ctx, STP_EINVAL, "stp_colsum_noalloc: device index out of range%s");
+  if (g_scratch_ptr[device]) return STP_OK;
+  float *p = nullptr;
+  STP_HIP(ctx, hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)));
+  if (!p) return stp_fail(ctx, STP_EHIP, "stp_colsum_noalloc: no device address for the scratch array%s");
+  g_scratch_ptr[device] = p;
+  return STP_OK;
+}
+
+extern "C" int stp_colsum_noalloc(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const void *x, float scale, float *out,
+                                  void *hip_stream) {
+  if (!ctx) return STP_EINVAL;
+  if (!x || !out) return stp_fail(ctx, STP_EINVAL, "stp_colsum_noalloc: null pointer%s");
+  if (T < 0 || N <= 0 || N % 8) return stp_fail(ctx, STP_ESHAPE, "stp_colsum_noalloc: N must be a multiple of 8%s");
+  if (!stp_aligned16(x)) return stp_fail(ctx, STP_EALIGN, "stp_colsum_noalloc: x must be 16-byte aligned%s");
+  if (dtype != STP_BF16 && dtype != STP_F32) return stp_fail(ctx, STP_EINVAL, "stp_colsum_noalloc: bad dtype%s");
+  if (T == 0) return STP_OK;
+  const int slabs = (T + 63) / 64;
+  if ((size_t)slabs * N > (size_t)STP_NOALLOC_SCRATCH_FLOATS)
+    return stp_fail(ctx, STP_ENOSPACE, "stp_colsum_noalloc: ceil(T / 64) * N%s = %ld exceeds the fixed scratch of %ld partial sums", "",
+                    (long)slabs * N, (long)STP_NOALLOC_SCRATCH_FLOATS);
+  int rc = stp_noalloc_init(ctx, ctx->device);   // a lookup; done at stp_create, repeated here only if that one failed
+  if (rc != STP_OK) return rc;
+  float *partial = g_scratch_ptr[ctx->device];
+  hipStream_t s = (hipStream_t)hip_stream;
+  // stage 1 writes every partial that stage 2 reads (slabs x N), so what an earlier call left behind is never seen
+  dim3 grid((N / 8 + 31) / 32, slabs), block(256);
+  if (dtype == STP_BF16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)x, T, N, partial);
+  else hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float *)x, T, N, partial);
+  STP_LAUNCH_CHECK(ctx);
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3((N + 63) / 64), dim3(256), 0, s, partial, slabs, (size_t)N, N, scale, out, 0x7fffffff,
+                     nullptr);
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+
 #define EW_CHECK(name, cond_null)                                                                          \
   if (!ctx) return STP_EINVAL;                                                                             \
   if (cond_null) return stp_fail(ctx, STP_EINVAL, name ": null pointer%s");                                \

@@ -32,6 +32,8 @@ extern "C" int stp_create(stp_ctx **out, int device) {
   if (!c) return STP_ENOSPACE;
   memset(c, 0, sizeof(*c));
   c->device = device;
+  (void)stp_noalloc_init(c, device);   // best effort here; stp_colsum_noalloc repeats the lookup and reports its failure
+  c->err[0] = 0;
   *out = c;
   return STP_OK;
 }
