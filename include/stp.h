@@ -209,6 +209,11 @@ int stp_forward_unit(stp_ctx *ctx, const stp_layer_desc *desc, int unit, const s
  *                                                 norm gain/bias grads += into wg (may be NULL)
  *   ATTN    : dy = dX_attn                     -> dx = partial of dX_ln; stash DQKV
  *   PRE_ATTN: x_in = X, dy = dX_ln (reduced), d_resid = dX_attn -> dx = dX
+ * Of `wg` the Pre-* units use the four norm entries and ONE bias entry: d_resid is the upstream gradient of
+ * the MLP (PRE_MLP) / Attn (PRE_ATTN) unit above, so (1/t) of its column sum is that unit's row-parallel bias
+ * gradient; the unit reads d_resid anyway and adds it into wg->b_fc2 (PRE_MLP) / wg->b_o (PRE_ATTN) when that
+ * entry is non-NULL and the layer has biases.  The W unit adds the same quantity when ITS table holds the
+ * entry: hand each accumulator to exactly one of the two (stp_braid_step gives b_fc2 / b_o to the Pre-* units).
  */
 int stp_backward_input_unit(stp_ctx *ctx, const stp_layer_desc *desc, int unit, const stp_weights *w,
                             const stp_stash *stash, const void *x_in, const void *dy,
@@ -303,10 +308,12 @@ int stp_gemm(stp_ctx *ctx, const stp_gemm_args *args, void *hip_stream);
 /* Normalisation of the Pre-* units.  stats is fp32 [T,2] (mean, rstd); RMSNorm stores (0, rstd). */
 int stp_norm_forward(stp_ctx *ctx, int dtype, int norm, int32_t T, int32_t h, float eps, const void *x,
                      const void *gamma, const void *beta, void *y, float *stats, void *hip_stream);
-/* dx = norm_bwd(dy) + d_resid (d_resid may be NULL); dgamma/dbeta (may be NULL) are += . */
+/* dx = norm_bwd(dy) + d_resid (d_resid may be NULL); dgamma/dbeta (may be NULL) are += .
+ * d_resid_sum (may be NULL; needs d_resid): [h] fp32, += d_resid_sum_scale * (sum over the T rows of d_resid). */
 int stp_norm_backward(stp_ctx *ctx, int dtype, int norm, int32_t T, int32_t h, const void *x,
                       const void *gamma, const float *stats, const void *dy, const void *d_resid,
-                      void *dx, float *dgamma, float *dbeta, int lane, void *hip_stream);
+                      void *dx, float *dgamma, float *dbeta, float *d_resid_sum, float d_resid_sum_scale,
+                      int lane, void *hip_stream);
 
 /* The work plan of one of the chunked bf16 attention kernels for a layer shape (host only, no GPU needed).
  * kind 0: forward, blocks of 128 queries, steps of 128 keys; 1: dK / dV, blocks of 128 keys, steps of 64
@@ -345,7 +352,7 @@ int stp_colsum(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const void *x, flo
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): the stage-1 partials go to a fixed
  * 4 MiB array inside the library's device image instead of a workspace lane, so the call needs no
  * stp_set_workspace and performs no allocation.  Limit: ceil(T / 64) * N <= 1048576 (STP_ENOSPACE beyond it;
- * [6144, 4096] bf16 uses 393216).  Same kernels, same bits as stp_colsum.  Every call on one GPU shares that
+ * [6144, 4096] uses 393216).  Same kernels, same bits as stp_colsum.  Every call on one GPU shares that
  * GPU's array: calls that may overlap on one GPU (different streams) race; calls on one stream do not.
  * Nothing needs clearing between calls: the first kernel writes every partial the second one reads. */
 int stp_colsum_noalloc(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const void *x, float scale, float *out,

@@ -132,7 +132,7 @@ def lib() -> C.CDLL:
     L.stp_attention_plan.argtypes = [P(LayerDesc), C.c_int, P(i32), P(i32), P(i32), P(C.c_uint16), sz]
     L.stp_gemm.argtypes = [vp, P(GemmArgs), vp]
     L.stp_norm_forward.argtypes = [vp, C.c_int, C.c_int, i32, i32, f32, vp, vp, vp, vp, vp, vp]
-    L.stp_norm_backward.argtypes = [vp, C.c_int, C.c_int, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp]
+    L.stp_norm_backward.argtypes = [vp, C.c_int, C.c_int, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, C.c_int, vp]
     L.stp_attention_forward.argtypes = [vp, P(LayerDesc), vp, vp, vp, C.c_int, vp]
     L.stp_attention_backward.argtypes = [vp, P(LayerDesc), vp, vp, vp, vp, vp, vp, C.c_int, vp]
     L.stp_gelu_forward.argtypes = [vp, C.c_int, sz, vp, vp, vp]
@@ -309,9 +309,11 @@ class Context:
         self.check(self._lib.stp_norm_forward(self._h, dtype, norm, T, h, eps, _ptr(x), _ptr(gamma), _ptr(beta),
                                               _ptr(y), _ptr(stats), _stream(stream)), "stp_norm_forward")
 
-    def norm_backward(self, dtype, norm, T, h, x, gamma, stats, dy, d_resid, dx, dgamma, dbeta, lane=0, stream=None):
+    def norm_backward(self, dtype, norm, T, h, x, gamma, stats, dy, d_resid, dx, dgamma, dbeta, lane=0, stream=None,
+                      d_resid_sum=None, d_resid_sum_scale=1.0):
         self.check(self._lib.stp_norm_backward(self._h, dtype, norm, T, h, _ptr(x), _ptr(gamma), _ptr(stats),
-                                               _ptr(dy), _ptr(d_resid), _ptr(dx), _ptr(dgamma), _ptr(dbeta), lane,
+                                               _ptr(dy), _ptr(d_resid), _ptr(dx), _ptr(dgamma), _ptr(dbeta),
+                                               _ptr(d_resid_sum), d_resid_sum_scale, lane,
                                                _stream(stream)), "stp_norm_backward")
 
     def attention_forward(self, desc, qkv, out, lse, lane=0, stream=None):

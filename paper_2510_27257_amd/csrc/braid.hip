@@ -206,6 +206,14 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
     const stp_layer_desc *d = &st->desc[o.layer];
     const stp_weights *w = &st->w[o.layer];
     stp_wgrads *g = &st->g[o.layer];
+    // Each accumulator goes to exactly one unit.  The bias gradients of the row-parallel linears (b_o, b_fc2: 1/t
+    // of the column sum of the unit's upstream gradient) ride in the norm backward of the Pre-* B unit below
+    // them, which reads that gradient anyway; the W units get a table without them.
+    stp_wgrads g_b, g_w = *g;
+    memset(&g_b, 0, sizeof(g_b));
+    g_b.norm1_g = g->norm1_g; g_b.norm1_b = g->norm1_b; g_b.norm2_g = g->norm2_g; g_b.norm2_b = g->norm2_b;
+    g_b.b_o = g->b_o; g_b.b_fc2 = g->b_fc2;
+    g_w.b_o = nullptr; g_w.b_fc2 = nullptr;
     const stp_stash *stash = &st->stash[(size_t)o.layer * MB + o.microbatch];
     size_t off[STP_ST_NFIELDS], nbytes;
     for (int f = 0; f < STP_ST_NFIELDS; f++) stp_stash_field(d, f, &off[f], &nbytes);
@@ -243,12 +251,12 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
           rc = stp_backward_input_unit(ctx, d, o.unit, w, stash, nullptr, dx_out, nullptr, dz, nullptr, 1, sB);
           if (rc == STP_OK && cb) cb(user, STP_AR_B_MLP, dz, act_bytes, o.layer, o.microbatch, sB);
           break;
-        case STP_PRE_MLP: rc = stp_backward_input_unit(ctx, d, o.unit, w, stash, x_attn, dz, dx_out, dx_attn, g, 1, sB); break;
+        case STP_PRE_MLP: rc = stp_backward_input_unit(ctx, d, o.unit, w, stash, x_attn, dz, dx_out, dx_attn, &g_b, 1, sB); break;
         case STP_ATTN:
           rc = stp_backward_input_unit(ctx, d, o.unit, w, stash, nullptr, dx_attn, nullptr, dx_ln, nullptr, 1, sB);
           if (rc == STP_OK && cb) cb(user, STP_AR_B_ATTN, dx_ln, act_bytes, o.layer, o.microbatch, sB);
           break;
-        case STP_PRE_ATTN: rc = stp_backward_input_unit(ctx, d, o.unit, w, stash, x, dx_ln, dx_attn, dx, g, 1, sB); break;
+        case STP_PRE_ATTN: rc = stp_backward_input_unit(ctx, d, o.unit, w, stash, x, dx_ln, dx_attn, dx, &g_b, 1, sB); break;
       }
       if (rc != STP_OK) break;
       if (has_w) {
@@ -266,7 +274,7 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
         if (e != hipSuccess) { rc = stp_fail(ctx, STP_EHIP, "hipStreamWaitEvent failed: %s", hipGetErrorString(e)); break; }
       }
       const void *dy = o.unit == STP_MLP ? dx_out : dx_attn;
-      rc = stp_backward_weight_unit(ctx, d, o.unit, stash, dy, g, 2, sW);
+      rc = stp_backward_weight_unit(ctx, d, o.unit, stash, dy, &g_w, 2, sW);
     }
   }
   free(ev_of);

@@ -122,15 +122,29 @@ __device__ __forceinline__ float other_half(float v) {
   return (threadIdx.x & 32) ? a : b;
 }
 
+// Sum / maximum over the 64 lanes of a wave, the result in every lane.  Within a row of 16 lanes by cross-lane
+// operand modifiers (quad permutes, then the half-row and row mirrors: no LDS round trips as a shuffle has),
+// then the four rows through scalar registers, (r0 + r1) + (r2 + r3).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float lane_f32(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_f32<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_f32<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_f32<0x141>(v);   // row_half_mirror
+  v += dpp_f32<0x140>(v);   // row_mirror
+  return (lane_f32(v, 0) + lane_f32(v, 16)) + (lane_f32(v, 32) + lane_f32(v, 48));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_f32<0xB1>(v));
+  v = fmaxf(v, dpp_f32<0x4E>(v));
+  v = fmaxf(v, dpp_f32<0x141>(v));
+  v = fmaxf(v, dpp_f32<0x140>(v));
+  return fmaxf(fmaxf(lane_f32(v, 0), lane_f32(v, 16)), fmaxf(lane_f32(v, 32), lane_f32(v, 48)));
 }
 
 // exact GELU x*Phi(x) and its derivative Phi(x) + x*phi(x)
@@ -139,6 +153,33 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
   float Phi = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
   float phi = 0.3989422804014327f * __expf(-0.5f * x * x);
   return Phi + x * phi;
+}
+// The same two for bf16 storage, where the rounding of the result (2^-9) hides an absolute error of 1e-7: the
+// normal distribution function from the rational-times-exponential approximation of erfc (Abramowitz & Stegun
+// 7.1.26, |error| < 1.5e-7 in erf), branch-free: 0.5 erfc(|x|/sqrt 2) = 0.5 t (a1 + t (a2 + ... )) exp(-x^2/2),
+// t = 1 / (1 + p |x| / sqrt 2); the lower tail is taken directly (no cancellation), the upper as 1 - tail.
+// `e` returns exp(-x^2/2), which the derivative needs as well.
+__device__ __forceinline__ float normal_cdf_fast(float x, float &e) {
+  const float ax = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(t, 1.061405429f, -1.453152027f);
+  p = fmaf(t, p, 1.421413741f);
+  p = fmaf(t, p, -0.284496736f);
+  p = fmaf(t, p, 0.254829592f);
+  e = __builtin_amdgcn_exp2f(ax * ax * -1.4426950408889634f);
+  const float q = 0.5f * p * t * e;
+  return x < 0.f ? q : 1.0f - q;
+}
+template <typename T> __device__ __forceinline__ float gelu_t(float x) {
+  if constexpr (sizeof(T) == 4) return gelu_f(x);
+  float e;
+  return x * normal_cdf_fast(x, e);
+}
+template <typename T> __device__ __forceinline__ float gelu_grad_t(float x) {
+  if constexpr (sizeof(T) == 4) return gelu_grad_f(x);
+  float e;
+  const float Phi = normal_cdf_fast(x, e);
+  return fmaf(x * 0.3989422804014327f, e, Phi);
 }
 __device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
 
@@ -172,6 +213,15 @@ int stp_launch_attn_bwd_generic(stp_ctx *ctx, const stp_layer_desc *d, const voi
                                 const void *dout, float *delta, void *dqkv, hipStream_t s);
 // device address of the fixed scratch array of stp_colsum_noalloc on `device` (the current device); a lookup, no allocation
 int stp_noalloc_init(stp_ctx *ctx, int device);
+// Launch geometry that also sizes the workspace.  Norm backward: 256-thread row groups that stride over the rows,
+// one partial per group.
+static inline int stp_norm_bwd_blocks(int rows, int h) {
+  (void)h;
+  return rows < 512 ? rows : 512;
+}
+// Column sum: stage-1 patches of STP_COLSUM_ROWS rows, one partial row each
+#define STP_COLSUM_ROWS 64
+static inline int stp_colsum_slabs(int rows) { return (rows + STP_COLSUM_ROWS - 1) / STP_COLSUM_ROWS; }
 // workspace lane: a third of the caller's workspace
 static inline char *stp_ws_lane(stp_ctx *ctx, int lane, size_t *bytes) {
   size_t third = (ctx->ws_bytes / 3) & ~(size_t)255;

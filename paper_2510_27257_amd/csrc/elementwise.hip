@@ -14,7 +14,7 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, 
                                                        const T *__restrict__ beta, T *__restrict__ y,
                                                        float *__restrict__ stats, int rows, int h, float eps) {
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (row >= rows) return;
   const T *xr = x + (size_t)row * h;
   float v[NCH][8];
@@ -71,6 +71,9 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, 
 // groups stride over rows and keep the gain/bias gradient partials of their
 // columns in registers; the partials go to the workspace and a second kernel
 // adds them up in a fixed order (deterministic, no float atomics).
+// With RSUM the column sums of the residual-path gradient are collected the same way: that gradient is read
+// here anyway, and (1/t) of its column sum is the bias gradient of the row-parallel linear layer of the
+// unit above (Eq. 1 adds b/t on every rank).  Partials of a group: [gain | bias | resid sum] (3h floats; 2h without RSUM).
 // chunk c of a thread covers elements (c*256 + tid)*8 .. +7
 // ======================================================================
 // Eight elements as loaded, unconverted: what a thread keeps of the NEXT row while it works on the current one.
@@ -98,19 +101,19 @@ template <> struct Raw8<bf16_t> {
   }
 };
 
-template <typename T, int NORM, int NCH>
+template <typename T, int NORM, int NCH, bool RSUM>
 __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, const T *__restrict__ gamma,
                                                        const float *__restrict__ stats, const T *__restrict__ dy,
                                                        const T *__restrict__ dres, T *__restrict__ dx,
                                                        float *__restrict__ partial, int rows, int h) {
   __shared__ float red[2][4][2];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  float gam[NCH][8], acc_g[NCH][8], acc_b[NCH][8];
+  float gam[NCH][8], acc_g[NCH][8], acc_b[NCH][8], acc_r[NCH][8];   // acc_r unused (and removed by the compiler) without RSUM
 #pragma unroll
   for (int c = 0; c < NCH; c++) {
     int col = (c * 256 + tid) * 8;
 #pragma unroll
-    for (int i = 0; i < 8; i++) { gam[c][i] = 0.f; acc_g[c][i] = 0.f; acc_b[c][i] = 0.f; }
+    for (int i = 0; i < 8; i++) { gam[c][i] = 0.f; acc_g[c][i] = 0.f; acc_b[c][i] = 0.f; acc_r[c][i] = 0.f; }
     if (col < h) Vec8<T>::load(gamma + col, gam[c]);
   }
   // A row is one load latency, a reduction over the group and a store; a group works through its rows one
@@ -148,6 +151,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, 
         if (dres) nr[c].get(rs[c]);
 #pragma unroll
         for (int i = 0; i < 8; i++) {
+          if (RSUM) acc_r[c][i] += rs[c][i];
           xh[c][i] = (xv[i] - mean) * rstd;
           acc_g[c][i] += dv[i] * xh[c][i];
           acc_b[c][i] += dv[i];
@@ -181,32 +185,36 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ x, 
     }
   }
   if (partial) {
-    float *pg = partial + (size_t)blockIdx.x * 2 * h;
+    float *pg = partial + (size_t)blockIdx.x * (RSUM ? 3 : 2) * h;
 #pragma unroll
     for (int c = 0; c < NCH; c++) {
       int col = (c * 256 + tid) * 8;
       if (col < h) {
         Vec8<float>::store(pg + col, acc_g[c]);
         Vec8<float>::store(pg + h + col, acc_b[c]);
+        if (RSUM) Vec8<float>::store(pg + 2 * h + col, acc_r[c]);
       }
     }
   }
 }
 
-// out[c] += scale * sum_{p < nparts} partial[p*stride + c], in a fixed order: a 256-thread group owns
-// 64 columns; thread (c, g) adds up rows g, g+4, g+8, ... (8 independent loads in flight), then the
-// four row-group sums are combined 0+1+2+3 through LDS.
-// Columns n_first .. n-1 go to out2 (its column 0 is column n_first): the gain and bias gradients of a norm,
-// whose partials lie side by side, are reduced by one launch.
+// Column c of the partials belongs to segment c / seg_w, column c % seg_w of that segment's output:
+//   out_k[c % seg_w] += scale_k * sum_{p < nparts} partial[p*stride + c]      (a NULL out_k skips the segment)
+// in a fixed order: a 256-thread group owns 64 columns; thread (c, g) adds up rows g, g+4, g+8, ... (8 independent
+// loads in flight), then the four row-group sums are combined 0+1+2+3 through LDS.  The gain, bias and
+// residual-sum partials of a norm lie side by side (three segments of h columns) and are reduced by one launch;
+// a plain column sum is one segment.
+struct ReduceOut { float *out[3]; float scale[3]; };
 __global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__restrict__ partial, int nparts,
-                                                            size_t stride, int n, float scale,
-                                                            float *__restrict__ out, int n_first = 0x7fffffff,
-                                                            float *__restrict__ out2 = nullptr) {
+                                                            size_t stride, int n, int seg_w, ReduceOut ro) {
   __shared__ float red[4][64];
   const int cl = threadIdx.x & 63, g = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl;
+  const int seg = c < n ? c / seg_w : 0;
+  float *const dst = seg == 0 ? ro.out[0] : (seg == 1 ? ro.out[1] : ro.out[2]);
+  const float scale = seg == 0 ? ro.scale[0] : (seg == 1 ? ro.scale[1] : ro.scale[2]);
   float s = 0.f;
-  if (c < n) {
+  if (c < n && dst) {
     int p = g;
     for (; p + 28 < nparts; p += 32) {
       float v[8];
@@ -219,41 +227,44 @@ __global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__rest
   }
   red[g][cl] = s;
   __syncthreads();
-  if (g == 0 && c < n) {
-    float *dst = c < n_first ? out + c : out2 + (c - n_first);
-    *dst += scale * (((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl]);
-  }
+  if (g == 0 && c < n && dst) dst[c - seg * seg_w] += scale * (((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl]);
 }
 
 // ======================================================================
-// Column sums (bias gradients), stage 1: a 256-thread group owns a 64-row x 256-column patch as
-// 8 row-lanes x 32 column chunks; every thread adds 8 rows (8 independent 16-byte loads in flight),
-// the 8 row-lanes are combined through LDS in a fixed order, and the patch sum goes to the
-// workspace; partial_reduce_kernel adds the patches of a column.
+// Column sums (bias gradients), stage 1: a 256-thread group owns a CS_ROWS-row x 256-column patch as
+// 8 row-lanes x 32 column chunks; every thread adds CS_ROWS / 8 rows in batches of 8 independent 16-byte
+// loads, the 8 row-lanes are combined through LDS in a fixed order, and the patch sum goes to the
+// workspace; partial_reduce_kernel adds the patches of a column.  (Taller patches were no faster at
+// [6144, 4096] and slower for narrower tensors, whose launch they leave with too few workgroups.)
 // ======================================================================
+constexpr int CS_ROWS = STP_COLSUM_ROWS;
+
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ x, int rows, int n,
                                                      float *__restrict__ partial) {
   __shared__ float red[8][32][9];
   const int cc = threadIdx.x & 31, rl = threadIdx.x >> 5;
   const int col = (blockIdx.x * 32 + cc) * 8;
-  const int r0 = blockIdx.y * 64;
+  const int r0 = blockIdx.y * CS_ROWS;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (col < n) {
-    float v[8][8];
 #pragma unroll
-    for (int u = 0; u < 8; u++) {
-      const int r = r0 + rl + 8 * u;
-      if (r < rows) Vec8<T>::load(x + (size_t)r * n + col, v[u]);
-      else {
+    for (int b = 0; b < CS_ROWS / 64; b++) {
+      float v[8][8];
 #pragma unroll
-        for (int i = 0; i < 8; i++) v[u][i] = 0.f;
+      for (int u = 0; u < 8; u++) {
+        const int r = r0 + 64 * b + rl + 8 * u;
+        if (r < rows) Vec8<T>::load(x + (size_t)r * n + col, v[u]);
+        else {
+#pragma unroll
+          for (int i = 0; i < 8; i++) v[u][i] = 0.f;
+        }
       }
+#pragma unroll
+      for (int u = 0; u < 8; u++)
+#pragma unroll
+        for (int i = 0; i < 8; i++) acc[i] += v[u][i];
     }
-#pragma unroll
-    for (int u = 0; u < 8; u++)
-#pragma unroll
-      for (int i = 0; i < 8; i++) acc[i] += v[u][i];
   }
 #pragma unroll
   for (int i = 0; i < 8; i++) red[rl][cc][i] = acc[i];
@@ -280,7 +291,7 @@ __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T *__restrict__ x, 
     float v[8];
     Vec8<T>::load(x + i * 8, v);
 #pragma unroll
-    for (int k = 0; k < 8; k++) v[k] = gelu_f(v[k]);
+    for (int k = 0; k < 8; k++) v[k] = gelu_t<T>(v[k]);
     Vec8<T>::store(y + i * 8, v);
   }
 }
@@ -292,7 +303,7 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T *__restrict__ x, 
     Vec8<T>::load(x + i * 8, v);
     Vec8<T>::load(dy + i * 8, d);
 #pragma unroll
-    for (int k = 0; k < 8; k++) d[k] *= gelu_grad_f(v[k]);
+    for (int k = 0; k < 8; k++) d[k] *= gelu_grad_t<T>(v[k]);
     Vec8<T>::store(dx + i * 8, d);
   }
 }
@@ -435,17 +446,19 @@ extern "C" int stp_norm_forward(stp_ctx *ctx, int dtype, int norm, int32_t T, in
   return stp_fail(ctx, STP_EINVAL, "stp_norm_forward: bad dtype%s");
 }
 
-static inline int norm_bwd_groups(int rows) { return rows < 512 ? rows : 512; }
-
 template <typename T>
 static int norm_bwd_dispatch(stp_ctx *ctx, int norm, int rows, int h, const void *x, const void *gamma,
                              const float *stats, const void *dy, const void *dres, void *dx, float *partial,
-                             int groups, hipStream_t s) {
-  dim3 grid(groups), block(256);
+                             bool rsum, hipStream_t s) {
+  dim3 grid(stp_norm_bwd_blocks(rows, h)), block(256);
   int nch = (h + 2047) / 2048;
-#define LAUNCH(NORM, NCH)                                                                               \
-  hipLaunchKernelGGL((norm_bwd_kernel<T, NORM, NCH>), grid, block, 0, s, (const T *)x, (const T *)gamma, \
-                     stats, (const T *)dy, (const T *)dres, (T *)dx, partial, rows, h)
+#define LAUNCH(NORM, NCH)                                                                                         \
+  do {                                                                                                            \
+    if (rsum) hipLaunchKernelGGL((norm_bwd_kernel<T, NORM, NCH, true>), grid, block, 0, s, (const T *)x,          \
+                                 (const T *)gamma, stats, (const T *)dy, (const T *)dres, (T *)dx, partial, rows, h); \
+    else hipLaunchKernelGGL((norm_bwd_kernel<T, NORM, NCH, false>), grid, block, 0, s, (const T *)x,              \
+                            (const T *)gamma, stats, (const T *)dy, (const T *)dres, (T *)dx, partial, rows, h);  \
+  } while (0)
 #define BY_NCH(NORM)                                   \
   if (nch <= 1) LAUNCH(NORM, 1);                       \
   else if (nch <= 2) LAUNCH(NORM, 2);                  \
@@ -460,7 +473,8 @@ static int norm_bwd_dispatch(stp_ctx *ctx, int norm, int rows, int h, const void
 
 extern "C" int stp_norm_backward(stp_ctx *ctx, int dtype, int norm, int32_t T, int32_t h, const void *x,
                                  const void *gamma, const float *stats, const void *dy, const void *d_resid,
-                                 void *dx, float *dgamma, float *dbeta, int lane, void *hip_stream) {
+                                 void *dx, float *dgamma, float *dbeta, float *d_resid_sum, float d_resid_sum_scale,
+                                 int lane, void *hip_stream) {
   if (!ctx) return STP_EINVAL;
   if (!x || !gamma || !stats || !dy || !dx) return stp_fail(ctx, STP_EINVAL, "stp_norm_backward: null pointer%s");
   if (T < 0 || h <= 0 || h % 8 || h > 8192) return stp_fail(ctx, STP_ESHAPE, "stp_norm_backward: h must be a multiple of 8, <= 8192%s");
@@ -470,35 +484,42 @@ extern "C" int stp_norm_backward(stp_ctx *ctx, int dtype, int norm, int32_t T, i
   if (norm != STP_NORM_LN && norm != STP_NORM_RMS) return stp_fail(ctx, STP_EINVAL, "stp_norm_backward: bad norm%s");
   if (lane < 0 || lane > 2) return stp_fail(ctx, STP_EINVAL, "stp_norm_backward: lane must be 0..2%s");
   if (dtype != STP_BF16 && dtype != STP_F32) return stp_fail(ctx, STP_EINVAL, "stp_norm_backward: bad dtype%s");
+  if (d_resid_sum && !d_resid) return stp_fail(ctx, STP_EINVAL, "stp_norm_backward: d_resid_sum without d_resid%s");
   if (T == 0) return STP_OK;
   hipStream_t s = (hipStream_t)hip_stream;
-  int groups = norm_bwd_groups(T);
+  const int blocks = stp_norm_bwd_blocks(T, h);
+  const bool rsum = d_resid_sum != nullptr;
+  const bool want_beta = dbeta && norm == STP_NORM_LN;
   float *partial = nullptr;
-  bool want = dgamma || dbeta;
-  if (want) {
+  if (dgamma || want_beta || rsum) {
     size_t lane_bytes;
     char *ws = stp_ws_lane(ctx, lane, &lane_bytes);
-    size_t need = (size_t)groups * 2 * h * sizeof(float);
+    size_t need = (size_t)blocks * (rsum ? 3 : 2) * h * sizeof(float);
     if (!ws || lane_bytes < need) return stp_fail(ctx, STP_ENOSPACE, "stp_norm_backward: workspace lane too small%s (need %ld bytes)", "", (long)need);
     partial = (float *)ws;
   }
-  int rc = dtype == STP_BF16 ? norm_bwd_dispatch<bf16_t>(ctx, norm, T, h, x, gamma, stats, dy, d_resid, dx, partial, groups, s)
-                             : norm_bwd_dispatch<float>(ctx, norm, T, h, x, gamma, stats, dy, d_resid, dx, partial, groups, s);
+  int rc = dtype == STP_BF16 ? norm_bwd_dispatch<bf16_t>(ctx, norm, T, h, x, gamma, stats, dy, d_resid, dx, partial, rsum, s)
+                             : norm_bwd_dispatch<float>(ctx, norm, T, h, x, gamma, stats, dy, d_resid, dx, partial, rsum, s);
   if (rc != STP_OK) return rc;
-  const bool want_beta = dbeta && norm == STP_NORM_LN;
-  if (dgamma && want_beta) {   // the partials of a row group lie side by side: [gain | bias]
-    hipLaunchKernelGGL(partial_reduce_kernel, dim3((2 * h + 63) / 64), dim3(256), 0, s, partial, groups, (size_t)2 * h, 2 * h, 1.0f,
-                       dgamma, h, dbeta);
-    STP_LAUNCH_CHECK(ctx);
-  } else if (dgamma) {
-    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 63) / 64), dim3(256), 0, s, partial, groups, (size_t)2 * h, h, 1.0f, dgamma,
-                       0x7fffffff, nullptr);
-    STP_LAUNCH_CHECK(ctx);
-  } else if (want_beta) {
-    hipLaunchKernelGGL(partial_reduce_kernel, dim3((h + 63) / 64), dim3(256), 0, s, partial + h, groups, (size_t)2 * h, h, 1.0f, dbeta,
-                       0x7fffffff, nullptr);
+  if (partial) {   // the partials of a row group lie side by side: [gain | bias | residual sum]
+    const int segs = rsum ? 3 : 2;
+    ReduceOut ro = {{dgamma, want_beta ? dbeta : nullptr, d_resid_sum}, {1.0f, 1.0f, d_resid_sum_scale}};
+    hipLaunchKernelGGL(partial_reduce_kernel, dim3((segs * h + 63) / 64), dim3(256), 0, s, partial, blocks, (size_t)segs * h, segs * h, h, ro);
     STP_LAUNCH_CHECK(ctx);
   }
+  return STP_OK;
+}
+
+// the two stages of a column sum with the partial sums at `partial` (slabs x N floats)
+static int colsum_launch(stp_ctx *ctx, int dtype, int T, int N, const void *x, float scale, float *out, float *partial, hipStream_t s) {
+  const int slabs = stp_colsum_slabs(T);
+  dim3 grid((N / 8 + 31) / 32, slabs), block(256);
+  if (dtype == STP_BF16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)x, T, N, partial);
+  else hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float *)x, T, N, partial);
+  STP_LAUNCH_CHECK(ctx);
+  ReduceOut ro = {{out, nullptr, nullptr}, {scale, 0.f, 0.f}};
+  hipLaunchKernelGGL(partial_reduce_kernel, dim3((N + 63) / 64), dim3(256), 0, s, partial, slabs, (size_t)N, N, N, ro);
+  STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }
 
@@ -511,21 +532,11 @@ extern "C" int stp_colsum(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const v
   if (lane < 0 || lane > 2) return stp_fail(ctx, STP_EINVAL, "stp_colsum: lane must be 0..2%s");
   if (dtype != STP_BF16 && dtype != STP_F32) return stp_fail(ctx, STP_EINVAL, "stp_colsum: bad dtype%s");
   if (T == 0) return STP_OK;
-  hipStream_t s = (hipStream_t)hip_stream;
-  int slabs = (T + 63) / 64;
   size_t lane_bytes;
   char *ws = stp_ws_lane(ctx, lane, &lane_bytes);
-  size_t need = (size_t)slabs * N * sizeof(float);
+  size_t need = (size_t)stp_colsum_slabs(T) * N * sizeof(float);
   if (!ws || lane_bytes < need) return stp_fail(ctx, STP_ENOSPACE, "stp_colsum: workspace lane too small%s (need %ld bytes)", "", (long)need);
-  float *partial = (float *)ws;
-  dim3 grid((N / 8 + 31) / 32, slabs), block(256);
-  if (dtype == STP_BF16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)x, T, N, partial);
-  else hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float *)x, T, N, partial);
-  STP_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(partial_reduce_kernel, dim3((N + 63) / 64), dim3(256), 0, s, partial, slabs, (size_t)N, N, scale, out, 0x7fffffff,
-                     nullptr);
-  STP_LAUNCH_CHECK(ctx);
-  return STP_OK;
+  return colsum_launch(ctx, dtype, T, N, x, scale, out, (float *)ws, (hipStream_t)hip_stream);
 }
 
 // ======================================================================
@@ -558,23 +569,14 @@ extern "C" int stp_colsum_noalloc(stp_ctx *ctx, int dtype, int32_t T, int32_t N,
   if (!stp_aligned16(x)) return stp_fail(ctx, STP_EALIGN, "stp_colsum_noalloc: x must be 16-byte aligned%s");
   if (dtype != STP_BF16 && dtype != STP_F32) return stp_fail(ctx, STP_EINVAL, "stp_colsum_noalloc: bad dtype%s");
   if (T == 0) return STP_OK;
-  const int slabs = (T + 63) / 64;
+  const int slabs = stp_colsum_slabs(T);
   if ((size_t)slabs * N > (size_t)STP_NOALLOC_SCRATCH_FLOATS)
     return stp_fail(ctx, STP_ENOSPACE, "stp_colsum_noalloc: ceil(T / 64) * N%s = %ld exceeds the fixed scratch of %ld partial sums", "",
                     (long)slabs * N, (long)STP_NOALLOC_SCRATCH_FLOATS);
   int rc = stp_noalloc_init(ctx, ctx->device);   // a lookup; done at stp_create, repeated here only if that one failed
   if (rc != STP_OK) return rc;
-  float *partial = g_scratch_ptr[ctx->device];
-  hipStream_t s = (hipStream_t)hip_stream;
   // stage 1 writes every partial that stage 2 reads (slabs x N), so what an earlier call left behind is never seen
-  dim3 grid((N / 8 + 31) / 32, slabs), block(256);
-  if (dtype == STP_BF16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)x, T, N, partial);
-  else hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float *)x, T, N, partial);
-  STP_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(partial_reduce_kernel, dim3((N + 63) / 64), dim3(256), 0, s, partial, slabs, (size_t)N, N, scale, out, 0x7fffffff,
-                     nullptr);
-  STP_LAUNCH_CHECK(ctx);
-  return STP_OK;
+  return colsum_launch(ctx, dtype, T, N, x, scale, out, g_scratch_ptr[ctx->device], (hipStream_t)hip_stream);
 }
 
 #define EW_CHECK(name, cond_null)                                                                          \

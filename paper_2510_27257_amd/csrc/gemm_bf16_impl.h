@@ -29,6 +29,7 @@
 #include "common.h"
 #include "lds_dma.h"
 #include <utility>
+#include <stdlib.h>
 
 namespace {
 
@@ -105,6 +106,9 @@ __device__ __forceinline__ bf16x8_t frag_load(const bf16_t *lds, int row, int kk
 }
 
 struct Epi {
+#ifdef STP_GEMM_TRACE
+  long long *trace;   // measurement build only: 4 wall-clock stamps per workgroup
+#endif
   void *C; int ldc; int c_f32_accum;
   const bf16_t *bias; float bias_scale;
   const bf16_t *resid; int ldr; float resid_scale;
@@ -215,7 +219,7 @@ __device__ __forceinline__ void store_tile(f32x16_t (&acc)[MI][NI], float *stage
           const bf16x8_t h8 = __builtin_bit_cast(bf16x8_t, raw);
 #pragma unroll
           for (int e = 0; e < 8; e++) {
-            if (AUX) val[e] *= gelu_grad_f((float)h8[e]);
+            if (AUX) val[e] *= gelu_grad_t<bf16_t>((float)h8[e]);
             else val[e] += (float)h8[e] * ep.resid_scale;
           }
         }
@@ -227,7 +231,7 @@ __device__ __forceinline__ void store_tile(f32x16_t (&acc)[MI][NI], float *stage
           if (EPI == EPI_GELU_DUAL) {
             float gv[8];
 #pragma unroll
-            for (int e = 0; e < 8; e++) gv[e] = gelu_f((float)o[e]);
+            for (int e = 0; e < 8; e++) gv[e] = gelu_t<bf16_t>((float)o[e]);
             Vec8<bf16_t>::store(ep.C2 + (size_t)row * ep.ld2 + col, gv);
           }
         }
@@ -419,10 +423,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(c
   constexpr int STAGE_BYTES = OA::bytes + OB::bytes;
   constexpr int LOADS_PER_TILE = OA::NINST + OB::NINST;
   constexpr int READS_PER_STEP = MI * OA::LDS_OPS_PER_FRAG + NI * OB::LDS_OPS_PER_FRAG;
-  static_assert(READS_PER_STEP <= 15, "lgkmcnt is a 4-bit counter");
+  // lgkmcnt is a 4-bit counter: with 16 reads per step the wait for "the previous step's reads" also waits for
+  // the first read of the step just issued (the reads of a wave complete in order)
+  constexpr int READS_WAIT = READS_PER_STEP < 15 ? READS_PER_STEP : 15;
+  static_assert(READS_PER_STEP <= 16, "one step's fragment reads must fit the lgkmcnt counter");
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#ifdef STP_GEMM_TRACE
+  const long long tr0 = wall_clock64();
+#endif
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // same value, known wave-uniform: LDS targets of the loads stay scalar
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   int tm, tn;
@@ -510,19 +520,22 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(c
   } while (0)
 
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSTG - 2) * LOADS_PER_TILE + LF) : "memory");
+#ifdef STP_GEMM_TRACE
+  const long long tr1 = wall_clock64();
+#endif
   STP_READ(0, fa0, fb0, 0);
 
   for (int kt = 0; kt < KT; kt++) {
     const int st = kt % NSTG;
     STP_READ(1, fa1, fb1, st);
-    lds_wait<READS_PER_STEP>();          // the reads of half 0 (issued one step ago) have returned
+    lds_wait<READS_WAIT>();              // the reads of half 0 (issued one step ago) have returned
     STP_MFMAS(fa0, fb0, LF, LS, kt + NSTG - 1, (kt + NSTG - 1) % NSTG);
     // tile kt+1 has landed once at most (NSTG-2) tiles' worth of this wave's loads remain in flight;
     // lgkmcnt(0): this wave's reads of stage st are complete, so after the barrier the stage is free
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NSTG - 2) * LOADS_PER_TILE) : "memory");
     __builtin_amdgcn_sched_barrier(0);
     STP_READ(0, fa0, fb0, (kt + 1) % NSTG);   // past the last tile this reads a stale stage; never used
-    lds_wait<READS_PER_STEP>();
+    lds_wait<READS_WAIT>();
     STP_MFMAS(fa1, fb1, 0, LF, kt + NSTG, st);
   }
 #undef STP_READ
@@ -532,8 +545,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(c
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
   lds_tie(fa0);
   lds_tie(fb0);
+#ifdef STP_GEMM_TRACE
+  const long long tr2 = wall_clock64();
+#endif
   store_tile<MI, NI, WN, EPI>(acc, reinterpret_cast<float *>(smem_raw) + wave * (32 * (WN + 8)), m0 + wm * WM, n0 + wn * WN, M, N,
                               ep, lane);
+#ifdef STP_GEMM_TRACE
+  if (ep.trace) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const long long tr3 = wall_clock64();
+    if (tid == 0) {
+      unsigned hw;
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(hw));
+      long long *t = ep.trace + (size_t)blockIdx.x * 5;
+      t[0] = tr0; t[1] = tr1; t[2] = tr2; t[3] = tr3; t[4] = hw;
+    }
+  }
+#endif
 }
 
 // extent in bytes of a K x rows operand as the kernel addresses it; 0 if it does not fit a 31-bit offset
@@ -642,6 +671,9 @@ int launch_tile(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t
 template <bool A_KC, bool B_KC>
 int launch_layout(stp_ctx *ctx, const stp_gemm_args *a, hipStream_t s) {
   Epi ep;
+#ifdef STP_GEMM_TRACE
+  ep.trace = getenv("STP_TRACE_PTR") ? (long long *)strtoull(getenv("STP_TRACE_PTR"), nullptr, 0) : nullptr;
+#endif
   ep.C = a->C; ep.ldc = a->ldc; ep.c_f32_accum = a->c_f32_accum;
   ep.bias = (const bf16_t *)a->bias; ep.bias_scale = a->bias_scale;
   ep.resid = (const bf16_t *)a->resid; ep.ldr = a->ldr; ep.resid_scale = a->resid_scale;

@@ -112,11 +112,10 @@ extern "C" int stp_stash_bytes(const stp_layer_desc *d, size_t *bytes) {
 static size_t ws_lane_bytes(const stp_layer_desc *d) {
   const size_t T = (size_t)d->seq * d->mbsz;
   const size_t h = d->hidden, a3 = (size_t)stp_qkv_width(d), ff = d->ffn_local;
-  size_t groups = T < 512 ? T : 512;
-  size_t norm = groups * 2 * h * sizeof(float);
+  size_t norm = (size_t)stp_norm_bwd_blocks((int)T, (int)h) * 3 * h * sizeof(float);   // [gain | bias | residual sum] per workgroup
   size_t widest = h > a3 ? h : a3;
   if (ff > widest) widest = ff;
-  size_t cs = ((T + 63) / 64) * widest * sizeof(float);
+  size_t cs = (size_t)stp_colsum_slabs((int)T) * widest * sizeof(float);
   size_t need = norm > cs ? norm : cs;
   if (d->dtype == STP_BF16) {
     size_t af = stp_attn_fwd_ws_bytes(d), ab = stp_attn_bwd_ws_bytes(d);
@@ -406,9 +405,13 @@ extern "C" int stp_backward_input_unit(stp_ctx *ctx, const stp_layer_desc *d, in
       RET_IF(need_ptr(ctx, gam, "norm gain"));
       float *dgam = wg ? (first ? wg->norm1_g : wg->norm2_g) : nullptr;
       float *dbet = wg ? (first ? wg->norm1_b : wg->norm2_b) : nullptr;
+      // The gradient on the residual path is the upstream gradient of the Attn (Pre-Attn-B) / MLP (Pre-MLP-B)
+      // unit, so (1/t) of its column sum is the gradient of that unit's row-parallel bias b_o / b_fc2 (Eq. 1
+      // adds b/t on every rank).  This unit reads it anyway: it fills the accumulator when it is handed one.
+      float *dbias = (wg && d->has_bias) ? (first ? wg->b_o : wg->b_fc2) : nullptr;
       // Eq. 2: dX = norm_bwd(reduced gradient) + 1 * (gradient arriving on the residual path)
       return stp_norm_backward(ctx, d->dtype, d->norm, T, h, x_in, gam, (const float *)f.p[first ? STP_ST_STATS1 : STP_ST_STATS2],
-                               dy, d_resid, dx, dgam, dbet, lane, hip_stream);
+                               dy, d_resid, dx, dgam, dbet, dbias, 1.0f / (float)d->tp, lane, hip_stream);
     }
     case STP_ATTN: {
       RET_IF(need_ptr(ctx, w->w_qkv, "w_qkv"));

@@ -53,6 +53,13 @@ class LayerOnDevice:
         self.g_dev = {k: torch.zeros(v.shape, dtype=torch.float32, device="cuda") for k, v in self.w_host.items()}
         self.w = stp.Weights(**{k: v.data_ptr() for k, v in self.w_dev.items()})
         self.g = stp.WGrads(**{k: v.data_ptr() for k, v in self.g_dev.items()})
+        # Every accumulator goes to exactly one unit.  The row-parallel bias gradients b_o / b_fc2 can be filled by
+        # the W units (tables g_b / g) or ride in the norm backward of the Pre-* B units (tables g_b_bias / g_w_nobias).
+        ptr = {k: v.data_ptr() for k, v in self.g_dev.items()}
+        norm_keys = [k for k in ptr if k.startswith("norm")]
+        self.g_b = stp.WGrads(**{k: ptr[k] for k in norm_keys})
+        self.g_b_bias = stp.WGrads(**{k: ptr[k] for k in norm_keys + [k for k in ("b_o", "b_fc2") if k in ptr]})
+        self.g_w_nobias = stp.WGrads(**{k: v for k, v in ptr.items() if k not in ("b_o", "b_fc2")})
         nbytes = ctx.stash_bytes(self.desc)
         self.stash_mem = [torch.zeros(nbytes, dtype=torch.uint8, device="cuda") for _ in range(n_mb)]
         self.stash = [stp.Stash(base=m.data_ptr(), bytes=nbytes) for m in self.stash_mem]
@@ -73,9 +80,12 @@ class LayerOnDevice:
         return {k: v.astype(np.float64) for k, v in self.w_host.items()}
 
 
-def gpu_layer_pass(ctx, lay: LayerOnDevice, X: torch.Tensor, dO: torch.Tensor, mb: int = 0, stream=None):
-    """F units, then B units, then W units of one rank with identity at the AR points."""
+def gpu_layer_pass(ctx, lay: LayerOnDevice, X: torch.Tensor, dO: torch.Tensor, mb: int = 0, stream=None,
+                   bias_in_b: bool = False):
+    """F units, then B units, then W units of one rank with identity at the AR points.  bias_in_b: the Pre-* B units
+    fill b_o / b_fc2 (as stp_braid_step wires it) instead of the W units."""
     d, w, st = lay.desc, lay.w, lay.stash[mb]
+    g_b, g_w = (lay.g_b_bias, lay.g_w_nobias) if bias_in_b else (lay.g_b, lay.g)
     out = {k: lay.new_act() for k in ("x_attn", "x_out", "dz", "dx_attn", "dx_ln", "dx")}
     ctx.forward_unit(d, stp.PRE_ATTN, w, st, x_in=X, stream=stream)
     ctx.forward_unit(d, stp.ATTN, w, st, x_resid=X, y_out=out["x_attn"], stream=stream)
@@ -83,12 +93,12 @@ def gpu_layer_pass(ctx, lay: LayerOnDevice, X: torch.Tensor, dO: torch.Tensor, m
     ctx.forward_unit(d, stp.MLP, w, st, x_resid=out["x_attn"], y_out=out["x_out"], stream=stream)
     ctx.backward_input_unit(d, stp.MLP, w, st, dy=dO, dx=out["dz"], stream=stream)
     ctx.backward_input_unit(d, stp.PRE_MLP, w, st, x_in=out["x_attn"], dy=out["dz"], d_resid=dO, dx=out["dx_attn"],
-                            wgrads=lay.g, stream=stream)
+                            wgrads=g_b, stream=stream)
     ctx.backward_input_unit(d, stp.ATTN, w, st, dy=out["dx_attn"], dx=out["dx_ln"], stream=stream)
     ctx.backward_input_unit(d, stp.PRE_ATTN, w, st, x_in=X, dy=out["dx_ln"], d_resid=out["dx_attn"], dx=out["dx"],
-                            wgrads=lay.g, stream=stream)
-    ctx.backward_weight_unit(d, stp.MLP, st, dO, lay.g, stream=stream)
-    ctx.backward_weight_unit(d, stp.ATTN, st, out["dx_attn"], lay.g, stream=stream)
+                            wgrads=g_b, stream=stream)
+    ctx.backward_weight_unit(d, stp.MLP, st, dO, g_w, stream=stream)
+    ctx.backward_weight_unit(d, stp.ATTN, st, out["dx_attn"], g_w, stream=stream)
     return out
 
 

@@ -196,6 +196,21 @@ def test_norm_forward_backward(ctx, dtype, norm, T, h):
     assert rel_err(to_host(dgam), 1.0 + rdg) < 1e-5
     if norm == "ln":
         assert rel_err(to_host(dbet), -1.0 + rdb) < 1e-5
+    # the same pass also hands out the scaled column sum of the residual-path gradient (the row-parallel bias
+    # gradient of the unit above: (1/t) * sum over tokens, Eq. 1); dx and the norm gradients keep their bits
+    dx2, rsum = torch.empty_like(xd), torch.full((h,), 0.5, dtype=torch.float32, device="cuda")
+    dgam2 = torch.full((h,), 1.0, dtype=torch.float32, device="cuda")
+    dbet2 = torch.full((h,), -1.0, dtype=torch.float32, device="cuda")
+    ctx.norm_backward(code, ncode, T, h, xd, gd, stats, dyd, drd, dx2, dgam2, dbet2, lane=2, d_resid_sum=rsum,
+                      d_resid_sum_scale=0.25)
+    torch.cuda.synchronize()
+    assert torch.equal(dx2, dx) and torch.equal(dgam2, dgam)
+    assert rel_err(to_host(rsum), 0.5 + 0.25 * dres.astype(np.float64).sum(0)) < 1e-5
+    rsum.fill_(0.0)
+    ctx.norm_backward(code, ncode, T, h, xd, gd, stats, dyd, drd, dx2, None, None, d_resid_sum=rsum)
+    torch.cuda.synchronize()
+    assert torch.equal(dx2, dx)
+    assert rel_err(to_host(rsum), dres.astype(np.float64).sum(0)) < 1e-5
     # no residual, no parameter gradients
     ctx.norm_backward(code, ncode, T, h, xd, gd, stats, dyd, None, dx, None, None)
     torch.cuda.synchronize()

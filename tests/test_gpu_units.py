@@ -34,14 +34,21 @@ def ctx():
     c.close()
 
 
+@pytest.mark.parametrize("bias_in_b", [False, True], ids=["bias_grads_in_W", "bias_grads_in_PreB"])
 @pytest.mark.parametrize("name", list(CASES))
-def test_units_match_oracle(ctx, name):
+def test_units_match_oracle(ctx, name, bias_in_b):
+    """Every unit output, stash field and weight gradient against the oracle.  The gradients of the row-parallel
+    biases (b_o, b_fc2) are (1/t) of the column sum of the Attn / MLP unit's upstream gradient: the W units
+    compute them when handed the accumulators, and so do the Pre-Attn-B / Pre-MLP-B units (which read that
+    gradient on their residual path, Eq. 2); both routes are run."""
     wl = CASES[name]
+    if bias_in_b and not wl.has_bias:
+        pytest.skip("no biases in this layer")
     tol = TOL[wl.dtype]
     lay = LayerOnDevice(ctx, wl, seed=0)
     X = synth.make_activation(wl, 0, "x.mb0")
     dO = synth.make_activation(wl, 0, "dy.mb0")
-    got = gpu_layer_pass(ctx, lay, to_dev(X, wl.dtype), to_dev(dO, wl.dtype))
+    got = gpu_layer_pass(ctx, lay, to_dev(X, wl.dtype), to_dev(dO, wl.dtype), bias_in_b=bias_in_b)
     torch.cuda.synchronize()
     ref, st, g = oracle_layer_pass(oracle_cfg(wl), lay.w64(), X.astype(np.float64), dO.astype(np.float64))
     T, a = wl.seq, wl.attn_local

@@ -42,7 +42,7 @@ def test_colsum_noalloc_matches_colsum_on_two_calls_in_a_row(dtype):
 
 def test_colsum_noalloc_rejects_sizes_beyond_its_scratch():
     ctx = stp.Context(0)
-    T, N = 64 * 1024, 2048            # 1024 slabs x 2048 columns = 2 Mi partial sums > 1 Mi
+    T, N = 64 * 1024, 2048            # 1024 patches of 64 rows x 2048 columns = 2 Mi partial sums > 1 Mi
     x = torch.zeros(8, dtype=torch.bfloat16, device="cuda")   # never read: the size check comes first
     out = torch.zeros(N, dtype=torch.float32, device="cuda")
     with pytest.raises(stp.StpError) as e:
