@@ -22,9 +22,10 @@ sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak (256 CU x 4096 flop/clk x 2.4 GHz ~ 2.5e15)
 # HBM-side bytes per launch of the dominant kernel on its four shapes, from the two rocprofv3 --pmc runs
-# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors calibrated on a 1 GiB copy) summarised in
-# profiles/gemm_bf16_fwd_layout_gpt7b_tp8.txt; counters cannot be read from inside this process.
+# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors calibrated on a 1 GiB copy) summarised in the file named below;
+# counters cannot be read from inside this process, so this is a recorded figure, not one this run measured.
 GEMM_FWD_TRAFFIC_BYTES = 177.9e6
+GEMM_FWD_TRAFFIC_SOURCE = "profiles/gemm_bf16_fwd_layout_gpt7b_tp8.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --only-gemm`; a constant recorded from that profile, not measured by this run)"
 
 
 def unit_flops(wl):
@@ -51,6 +52,33 @@ def time_steps(fn, steps, warmup, torch):
         fn()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def event_steps(ctx, stage, arr, streams, steps, torch):
+    """Per-step makespans of `steps` braided steps from HIP events: after every step a timing stream waits for
+    the step's end on all three streams and records an event; a step's time is the distance between two such
+    events (the next step waits for the same three ends, so the steps do not overlap).  Returns the list in ms."""
+    sF, sB, sW = streams
+    sT = torch.cuda.Stream()
+    marks = []
+
+    def mark():
+        for s in (sF, sB, sW):
+            e = torch.cuda.Event()
+            e.record(s)
+            sT.wait_event(e)
+        m = torch.cuda.Event(enable_timing=True)
+        m.record(sT)
+        marks.append(m)
+
+    for _ in range(3):
+        ctx.braid_step(stage, arr, sF, sB, sW)
+    mark()
+    for _ in range(steps):
+        ctx.braid_step(stage, arr, sF, sB, sW)
+        mark()
+    torch.cuda.synchronize()
+    return [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
 
 
 def gemm_leg(ctx, wl, reps, torch, stp):
@@ -100,16 +128,28 @@ def hbm_leg(ctx, wl, torch, stp):
     g, b = torch.ones(h, device="cuda").to(td), torch.zeros(h, device="cuda").to(td)
     stats = torch.empty((T, 2), device="cuda")
     dg, db, outb = torch.zeros(h, device="cuda"), torch.zeros(h, device="cuda"), torch.zeros(h, device="cuda")
+    rsum = torch.zeros(h, device="cuda")
     hh, hd, hy = mk(T, f), mk(T, f), torch.empty((T, f), device="cuda", dtype=td)
     legs = [
         ("norm_fwd", 2 * T * h * es, lambda: ctx.norm_forward(code, norm, T, h, wl.eps, x, g, b, y, stats)),
         ("norm_bwd_resid_dgamma", 4 * T * h * es,
          lambda: ctx.norm_backward(code, norm, T, h, x, g, stats, dy, dr, y, dg, db)),
+        # as the Pre-* B units run it: the row-parallel bias gradient (column sum of the residual-path gradient) rides along
+        ("norm_bwd_resid_dgamma_biasgrad", 4 * T * h * es,
+         lambda: ctx.norm_backward(code, norm, T, h, x, g, stats, dy, dr, y, dg, db, d_resid_sum=rsum, d_resid_sum_scale=0.125)),
         ("gelu_fwd", 2 * T * f * es, lambda: ctx.gelu_forward(code, T * f, hh, hy)),
         ("gelu_bwd", 3 * T * f * es, lambda: ctx.gelu_backward(code, T * f, hh, hd, hy)),
         ("swiglu_fwd", 3 * T * f * es, lambda: ctx.swiglu_forward(code, T * f, hh, hd, hy)),
         ("colsum_T_h", T * h * es, lambda: ctx.colsum(code, T, h, x, 1.0, outb)),
+        ("colsum_T_f", T * f * es, lambda: ctx.colsum(code, T, f, hh, 1.0, outb[:f])),
+        # the practical ceiling: plain device copies of the same sizes (tensors of 25-100 MB are partly served by
+        # the 256 MB last-level cache) and of 1 GiB (HBM alone)
+        ("device_copy_T_h", 2 * T * h * es, lambda: y.copy_(x)),
+        ("device_copy_T_f", 2 * T * f * es, lambda: hy.copy_(hh)),
+        ("device_copy_1GiB", 2 << 30, lambda: big_dst.copy_(big_src)),
     ]
+    big_src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    big_dst = torch.empty_like(big_src)
     out = {}
     for name, nbytes, fn in legs:
         for _ in range(3):
@@ -125,6 +165,44 @@ def hbm_leg(ctx, wl, torch, stp):
         gbs = nbytes / ms / 1e6
         out[name] = {"us": ms * 1e3, "GB/s": gbs, "frac_of_8TBs": gbs / HBM_PEAK_GBS, "bytes": nbytes}
     return out
+
+
+def cpu_baseline(wl, w_host, fl, synth, reps=1):
+    """The fp64 oracle on the host cores: the F, B and W units of one layer-microbatch of `wl`, timed apart."""
+    import numpy as np
+    from oracle import stp_oracle as O
+    cfg = O.LayerCfg(hidden=wl.hidden, heads_local=wl.heads_local, head_dim=wl.head_dim, ffn_local=wl.ffn_local, tp=wl.tp,
+                     norm=wl.norm, act=wl.act, causal=wl.causal, rope=wl.rope, has_bias=wl.has_bias,
+                     eps=wl.eps, rope_base=wl.rope_base, kv_heads_local=wl.kv_heads)
+    W64 = {k: v.astype(np.float64) for k, v in w_host.items()}
+    X = synth.make_activation(wl, 0, "x.mb0").astype(np.float64)
+    dO = synth.make_activation(wl, 0, "dy.mb0").astype(np.float64)
+    tF = tB = tW = 0.0
+    for _ in range(reps):
+        st, g = {}, {}
+        t0 = time.perf_counter()
+        O.forward_unit(cfg, O.PRE_ATTN, W64, st, x_in=X)
+        xa = O.forward_unit(cfg, O.ATTN, W64, st, x_resid=X)
+        O.forward_unit(cfg, O.PRE_MLP, W64, st, x_in=xa)
+        O.forward_unit(cfg, O.MLP, W64, st, x_resid=xa)
+        t1 = time.perf_counter()
+        dz = O.backward_input_unit(cfg, O.MLP, W64, st, dO)
+        dxa = O.backward_input_unit(cfg, O.PRE_MLP, W64, st, dz, d_resid=dO, grads=g)
+        dxl = O.backward_input_unit(cfg, O.ATTN, W64, st, dxa)
+        O.backward_input_unit(cfg, O.PRE_ATTN, W64, st, dxl, d_resid=dxa, grads=g)
+        t2 = time.perf_counter()
+        O.backward_weight_unit(cfg, O.MLP, st, dO, g)
+        O.backward_weight_unit(cfg, O.ATTN, st, dxa, g)
+        t3 = time.perf_counter()
+        tF, tB, tW = tF + (t1 - t0) / reps, tB + (t2 - t1) / reps, tW + (t3 - t2) / reps
+    total = fl["F"] + fl["B"] + fl["W"]
+    return {"value": total / (tF + tB + tW) / 1e12, "unit": "TFLOP/s", "cores": len(os.sched_getaffinity(0)),
+            "kind": "oracle",
+            "sample": f"one full layer-microbatch (F, B and W units, all of a step's work) of workload {wl.name} in numpy fp64"
+                      + (f", mean of {reps} passes" if reps > 1 else ""),
+            "seconds": tF + tB + tW,
+            "units": {"F": {"seconds": tF, "tflops": fl["F"] / tF / 1e12}, "B": {"seconds": tB, "tflops": fl["B"] / tB / 1e12},
+                      "W": {"seconds": tW, "tflops": fl["W"] / tW / 1e12}}}
 
 
 def stage_bench(ctx, args, torch, stp, synth):
@@ -345,9 +423,13 @@ def main():
             ctx.clock_probe(probe_out, 8.0, stream=s_probe)
     torch.cuda.synchronize()
     cyc, ticks = (int(v) for v in probe_out.tolist())
-    wall_khz = 100000            # the constant-rate counter the probe reads beside the shader clock: 100 MHz on gfx950
+    wall_khz = ctx.wall_clock_khz()   # rate of the constant counter the probe reads beside the shader clock
     sustained_mhz = cyc / (ticks / wall_khz) / 1e3 if ticks else None
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+
+    # ---- per-step makespans from HIP events (median over >= 20 steps) ----------------
+    per_step = sorted(event_steps(ctx, stg.stage, arr, (sF, sB, sW), max(20, args.steps), torch))
+    ms_median = per_step[len(per_step) // 2]
 
     # ---- the same op list on one stream, and the isolated units ----------------------
     ms_serial = time_steps(lambda: ctx.braid_step(stg.stage, arr, s0, s0, s0), args.steps, args.warmup, torch)
@@ -371,6 +453,9 @@ def main():
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_braided,
+        "ms_per_step_events": {"median": ms_median, "min": per_step[0], "max": per_step[-1], "n": len(per_step),
+                               "tflops_at_median": total_flops / (ms_median * 1e-3) / 1e12,
+                               "how": "HIP events after the end of every step on all three streams"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: hidden {h}, {wl.heads_local} local heads x {wl.head_dim}, ffn shard {f}, "
@@ -392,37 +477,18 @@ def main():
                      "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "avg_launch_ms": gemm_avg_ms,
                      "flops_per_launch": gemm_flops_per_launch,
-                     "traffic": GEMM_FWD_TRAFFIC_BYTES if args.workload == "gpt7b_tp8" else None},
+                     "traffic": GEMM_FWD_TRAFFIC_BYTES if args.workload == "gpt7b_tp8" else None,
+                     "traffic_source": GEMM_FWD_TRAFFIC_SOURCE if args.workload == "gpt7b_tp8" else None,
+                     "algorithmic_bytes_per_launch": sum(2 * (M * K + K * N + M * N) for (M, N, K) in
+                                                         [(T, wl.qkv_local, h), (T, h, a), (T, f, h), (T, h, f)]) / 4},
         "hbm_kernels": hbm,
     }
 
     if not args.no_cpu_baseline:
-        # the fp64 oracle, as it stands, on this machine's host cores: one full layer-microbatch (F+B+W)
-        import numpy as np
-        from oracle import stp_oracle as O
-        cfg = O.LayerCfg(hidden=h, heads_local=wl.heads_local, head_dim=wl.head_dim, ffn_local=f, tp=wl.tp,
-                         norm=wl.norm, act=wl.act, causal=wl.causal, rope=wl.rope, has_bias=wl.has_bias,
-                         eps=wl.eps, rope_base=wl.rope_base, kv_heads_local=wl.kv_heads)
-        W64 = {k: v.astype(np.float64) for k, v in stg.w_host[0].items()}
-        X = synth.make_activation(wl, 0, "x.mb0").astype(np.float64)
-        dO = synth.make_activation(wl, 0, "dy.mb0").astype(np.float64)
-        t0 = time.perf_counter()
-        st, g = {}, {}
-        O.forward_unit(cfg, O.PRE_ATTN, W64, st, x_in=X)
-        xa = O.forward_unit(cfg, O.ATTN, W64, st, x_resid=X)
-        O.forward_unit(cfg, O.PRE_MLP, W64, st, x_in=xa)
-        O.forward_unit(cfg, O.MLP, W64, st, x_resid=xa)
-        dz = O.backward_input_unit(cfg, O.MLP, W64, st, dO)
-        dxa = O.backward_input_unit(cfg, O.PRE_MLP, W64, st, dz, d_resid=dO, grads=g)
-        dxl = O.backward_input_unit(cfg, O.ATTN, W64, st, dxa)
-        O.backward_input_unit(cfg, O.PRE_ATTN, W64, st, dxl, d_resid=dxa, grads=g)
-        O.backward_weight_unit(cfg, O.MLP, st, dO, g)
-        O.backward_weight_unit(cfg, O.ATTN, st, dxa, g)
-        cpu_s = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": total_flops / cpu_s / 1e12, "unit": "TFLOP/s",
-                                  "cores": len(os.sched_getaffinity(0)), "kind": "oracle",
-                                  "sample": "one full layer-microbatch (F+B+W units, all of the step's work) of the "
-                                            "same workload in numpy fp64", "seconds": cpu_s}
+        # the fp64 oracle, as it stands, on this machine's host cores: one full layer-microbatch, timed per unit kind
+        result["cpu_baseline"] = cpu_baseline(wl, stg.w_host[0], fl, synth)
+        tiny = synth.WORKLOADS["tiny"]
+        result["cpu_baseline_tiny"] = cpu_baseline(tiny, synth.make_weights(tiny, 0), unit_flops(tiny), synth, reps=20)
     print(json.dumps(result))
     torch.cuda.synchronize()
     ctx.close()

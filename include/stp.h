@@ -363,6 +363,8 @@ int stp_colsum_noalloc(stp_ctx *ctx, int dtype, int32_t T, int32_t N, const void
  * clock ticks at hipDeviceAttributeWallClockRate kHz).  Run on a side stream while the units execute, it
  * yields the sustained shader clock the MFMA roofline should be read against. */
 int stp_clock_probe(stp_ctx *ctx, long long *device_out2, double milliseconds, void *hip_stream);
+/* The rate of that wall clock in kHz (hipDeviceAttributeWallClockRate of the context's device). */
+int stp_wall_clock_khz(stp_ctx *ctx, int *khz);
 
 #ifdef __cplusplus
 }

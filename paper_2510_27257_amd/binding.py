@@ -32,7 +32,7 @@ EXPORTED_SYMBOLS = [
     "stp_backward_input_unit", "stp_backward_weight_unit", "stp_braid_step", "stp_validate_ops",
     "stp_braid_reset", "stp_braid_detach", "stp_attention_plan", "stp_gemm", "stp_norm_forward", "stp_norm_backward", "stp_attention_forward",
     "stp_attention_backward", "stp_gelu_forward", "stp_gelu_backward", "stp_swiglu_forward",
-    "stp_swiglu_backward", "stp_rope", "stp_colsum", "stp_colsum_noalloc", "stp_clock_probe",
+    "stp_swiglu_backward", "stp_rope", "stp_colsum", "stp_colsum_noalloc", "stp_clock_probe", "stp_wall_clock_khz",
     "stp_offload_bytes", "stp_stash_offload", "stp_stash_reload",
 ]
 
@@ -143,6 +143,7 @@ def lib() -> C.CDLL:
     L.stp_colsum.argtypes = [vp, C.c_int, i32, i32, vp, f32, vp, C.c_int, vp]
     L.stp_colsum_noalloc.argtypes = [vp, C.c_int, i32, i32, vp, f32, vp, vp]
     L.stp_clock_probe.argtypes = [vp, vp, C.c_double, vp]
+    L.stp_wall_clock_khz.argtypes = [vp, P(C.c_int)]
     L.stp_offload_bytes.argtypes = [P(LayerDesc), C.c_int, f32, P(sz)]
     L.stp_stash_offload.argtypes = [vp, P(LayerDesc), C.c_int, f32, P(Stash), vp, sz, vp, vp]
     L.stp_stash_reload.argtypes = [vp, P(LayerDesc), C.c_int, f32, P(Stash), vp, sz, vp, vp]
@@ -359,6 +360,12 @@ class Context:
         """out2: int64 device tensor with 2 elements -> (shader cycles, wall ticks at 100 MHz-class rate)."""
         self.check(self._lib.stp_clock_probe(self._h, _ptr(out2), float(milliseconds), _stream(stream)),
                    "stp_clock_probe")
+
+    def wall_clock_khz(self) -> int:
+        """Rate of the constant wall clock the clock probe reads, in kHz."""
+        k = C.c_int()
+        self.check(self._lib.stp_wall_clock_khz(self._h, C.byref(k)), "stp_wall_clock_khz")
+        return k.value
 
     def colsum(self, dtype, T, N, x, scale, out, lane=0, stream=None):
         self.check(self._lib.stp_colsum(self._h, dtype, T, N, _ptr(x), scale, _ptr(out), lane, _stream(stream)),

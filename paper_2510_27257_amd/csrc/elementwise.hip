@@ -375,8 +375,33 @@ __global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int toke
 
 // ======================================================================
 // delta[b, head, i] = sum_c dctx[tok, head*d + c] * ctx[tok, head*d + c]
-// (the rowsum(dP o P) term of the softmax backward).  One wave per (token, head).
+// (the rowsum(dP o P) term of the softmax backward).  A (token, head) pair is d contiguous elements at
+// (tok*n + head)*d, so consecutive pairs are consecutive memory: a lane takes 8 elements, LPP = d/8 lanes a
+// pair, a wave 64/LPP pairs (1 KB contiguous per operand), and the pair's lanes are summed by cross-lane
+// operand modifiers.  LPP must be 2, 4, 8 or 16; other head dimensions take the one-pair-per-wave kernel below.
 // ======================================================================
+template <typename T, int LPP>
+__global__ __launch_bounds__(256) void rowdot_packed_kernel(const T *__restrict__ a, const T *__restrict__ b,
+                                                            float *__restrict__ delta, size_t pairs, int seq, int n) {
+  const size_t v = blockIdx.x * (size_t)256 + threadIdx.x;     // 8-element vector index
+  const size_t pair = v / LPP;
+  float s = 0.f;
+  if (pair < pairs) {
+    float x[8], y[8];
+    Vec8<T>::load(a + v * 8, x);
+    Vec8<T>::load(b + v * 8, y);
+#pragma unroll
+    for (int i = 0; i < 8; i++) s += x[i] * y[i];
+  }
+  s += dpp_f32<0xB1>(s);                           // lanes 4k .. 4k+3
+  if (LPP >= 4) s += dpp_f32<0x4E>(s);
+  if (LPP >= 8) s += dpp_f32<0x141>(s);            // 8 lanes
+  if (LPP >= 16) s += dpp_f32<0x140>(s);           // 16 lanes
+  if (pair < pairs && v % LPP == 0) {
+    const size_t tok = pair / n, head = pair % n;
+    delta[((tok / seq) * n + head) * seq + tok % seq] = s;
+  }
+}
 template <typename T>
 __global__ __launch_bounds__(256) void rowdot_kernel(const T *__restrict__ a, const T *__restrict__ b,
                                                      float *__restrict__ delta, int tokens, int seq, int n, int d) {
@@ -650,14 +675,24 @@ extern "C" int stp_rope(stp_ctx *ctx, const stp_layer_desc *d, void *qkv, int in
 }
 
 // used by the attention backward launchers
+template <typename T>
+static void rowdot_dispatch(const stp_layer_desc *d, const void *a, const void *b, float *delta, hipStream_t s) {
+  const int tokens = d->seq * d->mbsz, n = d->heads_local, hd = d->head_dim;
+  const size_t pairs = (size_t)tokens * n;
+  const int lpp = hd / 8;
+  if (lpp == 2 || lpp == 4 || lpp == 8 || lpp == 16) {
+    dim3 grid((pairs * lpp + 255) / 256), block(256);
+#define LAUNCH(L) hipLaunchKernelGGL((rowdot_packed_kernel<T, L>), grid, block, 0, s, (const T *)a, (const T *)b, delta, pairs, d->seq, n)
+    if (lpp == 16) LAUNCH(16); else if (lpp == 8) LAUNCH(8); else if (lpp == 4) LAUNCH(4); else LAUNCH(2);
+#undef LAUNCH
+  } else {
+    dim3 grid((pairs + 3) / 4), block(256);
+    hipLaunchKernelGGL(rowdot_kernel<T>, grid, block, 0, s, (const T *)a, (const T *)b, delta, tokens, d->seq, n, hd);
+  }
+}
 int stp_launch_rowdot(stp_ctx *ctx, const stp_layer_desc *d, const void *a, const void *b, float *delta, hipStream_t s) {
-  int tokens = d->seq * d->mbsz;
-  size_t waves = (size_t)tokens * d->heads_local;
-  dim3 grid((waves + 3) / 4), block(256);
-  if (d->dtype == STP_BF16)
-    hipLaunchKernelGGL(rowdot_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)a, (const bf16_t *)b, delta, tokens, d->seq, d->heads_local, d->head_dim);
-  else
-    hipLaunchKernelGGL(rowdot_kernel<float>, grid, block, 0, s, (const float *)a, (const float *)b, delta, tokens, d->seq, d->heads_local, d->head_dim);
+  if (d->dtype == STP_BF16) rowdot_dispatch<bf16_t>(d, a, b, delta, s);
+  else rowdot_dispatch<float>(d, a, b, delta, s);
   STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }
@@ -685,5 +720,12 @@ extern "C" int stp_clock_probe(stp_ctx *ctx, long long *device_out2, double mill
   hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, device_out2,
                      (long long)(milliseconds * rate_khz));
   STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+
+extern "C" int stp_wall_clock_khz(stp_ctx *ctx, int *khz) {
+  if (!ctx) return STP_EINVAL;
+  if (!khz) return stp_fail(ctx, STP_EINVAL, "stp_wall_clock_khz: null pointer%s");
+  STP_HIP(ctx, hipDeviceGetAttribute(khz, hipDeviceAttributeWallClockRate, ctx->device));
   return STP_OK;
 }

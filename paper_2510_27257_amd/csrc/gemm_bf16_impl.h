@@ -469,7 +469,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(c
   // eight waves would queue on the address FIFO with the matrix pipes idle.  Per K-tile kt the first
   // LF loads of tile kt+4 go into the MFMA block that follows the barrier (stage kt is free from there on)
   // and the remaining LS loads into the MFMA block before the next barrier.
-  constexpr int LF = (LOADS_PER_TILE + 1) / 2, LS = LOADS_PER_TILE - LF;
 #define STP_ISSUE(q, ktile, stage)                                                                               \
   do {                                                                                                           \
     const int kt_ = min((ktile), KT - 1);                                                                        \
@@ -484,13 +483,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(c
       dma_load16(rb, dst_, offb[(q) >= OA::NINST ? (q) - OA::NINST : 0], kt_ * stepb);                           \
     }                                                                                                            \
   } while (0)
+  u32x4_t fa0[MI], fb0[NI], fa1[MI], fb1[NI];
+  constexpr int LF = (LOADS_PER_TILE + 1) / 2, LS = LOADS_PER_TILE - LF;
   // prologue: tiles 0 .. NSTG-2 and the first LF loads of tile NSTG-1
 #pragma unroll
   for (int t = 0; t < NSTG; t++)
 #pragma unroll
     for (int q = 0; q < (t < NSTG - 1 ? LOADS_PER_TILE : LF); q++) STP_ISSUE(q, t, t);
 
-  u32x4_t fa0[MI], fb0[NI], fa1[MI], fb1[NI];
   using SeqM = std::make_integer_sequence<int, MI>;
   using SeqN = std::make_integer_sequence<int, NI>;
 #define STP_READ(H, FA, FB, stage)                                                   \

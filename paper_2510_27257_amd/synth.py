@@ -36,6 +36,7 @@ class Workload:
     eps: float = 1e-5
     rope_base: float = 10000.0
     kv_heads: int = 0        # key / value heads on this rank (grouped-query attention); 0 = heads_local
+    w_std: float = 0.02      # standard deviation of the linear weights and biases
 
     @property
     def attn_local(self) -> int:
@@ -63,6 +64,30 @@ WORKLOADS = {
     # TP=4 shard: 10 query heads over 2 key / value heads; the FFN width is not given in the paper (synthetic)
     "gqa12b_tp4": Workload("gqa12b_tp4", 5120, 10, 128, 3456, 4096, 4, norm="rms", act="swiglu", rope=True,
                            has_bias=False, kv_heads=2),
+    # the same model at the sequence lengths and TP sizes of its throughput table (Appendix, LLM results: 3072 and
+    # 6144 tokens, TP 4 and 8); TP=8: 5 query heads over 1 key / value head
+    "gqa12b_tp4_s3072": Workload("gqa12b_tp4_s3072", 5120, 10, 128, 3456, 3072, 4, norm="rms", act="swiglu", rope=True,
+                                 has_bias=False, kv_heads=2),
+    "gqa12b_tp4_s6144": Workload("gqa12b_tp4_s6144", 5120, 10, 128, 3456, 6144, 4, norm="rms", act="swiglu", rope=True,
+                                 has_bias=False, kv_heads=2),
+    "gqa12b_tp8_s3072": Workload("gqa12b_tp8_s3072", 5120, 5, 128, 1728, 3072, 8, norm="rms", act="swiglu", rope=True,
+                                 has_bias=False, kv_heads=1),
+    "gqa12b_tp8_s6144": Workload("gqa12b_tp8_s6144", 5120, 5, 128, 1728, 6144, 8, norm="rms", act="swiglu", rope=True,
+                                 has_bias=False, kv_heads=1),
+    # layer with the head counts of the 26.3B model of Section 5.1 (56 query / 8 key-value heads, hidden 7168) at the
+    # sequence lengths of its throughput rows (2048, 4096).  TP=8 shard: 7 query heads over 1 key / value head;
+    # TP=4 shard: 14 over 2.  The FFN width is not given in the paper (synthetic: 20480 in all).  Weights N(0, 0.015):
+    # 0.02 * sqrt(4096 / 7168), which keeps the pre-activations at the scale they have in the benchmark layer of
+    # hidden 4096 (with 0.02 the gate and up projections of this wider layer have a standard deviation of 1.7 and
+    # their product amplifies the bf16 rounding of the stored intermediates past the tolerance stated for that layer)
+    "gqa26b_tp8": Workload("gqa26b_tp8", 7168, 7, 128, 2560, 4096, 8, norm="rms", act="swiglu", rope=True,
+                           has_bias=False, kv_heads=1, w_std=0.015),
+    "gqa26b_tp8_s2048": Workload("gqa26b_tp8_s2048", 7168, 7, 128, 2560, 2048, 8, norm="rms", act="swiglu", rope=True,
+                                 has_bias=False, kv_heads=1, w_std=0.015),
+    "gqa26b_tp4": Workload("gqa26b_tp4", 7168, 14, 128, 5120, 4096, 4, norm="rms", act="swiglu", rope=True,
+                           has_bias=False, kv_heads=2, w_std=0.015),
+    "gqa26b_tp4_s2048": Workload("gqa26b_tp4_s2048", 7168, 14, 128, 5120, 2048, 4, norm="rms", act="swiglu", rope=True,
+                                 has_bias=False, kv_heads=2, w_std=0.015),
 }
 
 
@@ -119,8 +144,9 @@ def make_weights(wl: Workload, seed: int, layer: int = 0) -> dict:
     columns are ordered [Q heads | K heads | V heads], head-major."""
     out = {}
     for key, shape in weight_shapes(wl).items():
-        mean = 1.0 if key in ("norm1_g", "norm2_g") else 0.0
-        out[key] = quantize(normal(seed, f"L{layer}.{key}", shape, 0.02, mean), wl.dtype)
+        gain = key in ("norm1_g", "norm2_g")
+        std = 0.02 if key.startswith("norm") else wl.w_std
+        out[key] = quantize(normal(seed, f"L{layer}.{key}", shape, std, 1.0 if gain else 0.0), wl.dtype)
     return out
 
 

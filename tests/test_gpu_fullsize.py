@@ -15,7 +15,11 @@ from oracle import stp_oracle as O
 from harness import TOL, oracle_cfg, oracle_layer_pass, rel_err, to_host
 
 
-@pytest.mark.parametrize("name", ["gpt7b_tp8", "llama13b_tp4", "vit", "gqa12b_tp4"])
+# the benchmark configurations, then the shards of the two language models of the model table of Section 5.1 at
+# sequence lengths of their throughput rows: 10 / 2, 5 / 1 (12.1B at TP 4 / 8) and 7 / 1 (26.3B at TP 8) query /
+# key-value heads on the rank
+@pytest.mark.parametrize("name", ["gpt7b_tp8", "llama13b_tp4", "vit", "gqa12b_tp4", "gqa12b_tp4_s6144", "gqa12b_tp8_s3072",
+                                  "gqa26b_tp8", "gqa26b_tp8_s2048"])
 def test_full_size_braided_block_matches_oracle(name):
     wl = synth.WORKLOADS[name]
     tol = TOL[wl.dtype]

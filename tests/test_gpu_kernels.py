@@ -296,7 +296,9 @@ ATTN_CASES = [("f32", 128, 1, 4, 64, True, 0), ("f32", 52, 2, 2, 32, False, 0), 
               ("bf16", 4360, 1, 1, 128, True, 0),
               # grouped-query attention: groups of 2, 3 and 5 query heads per key / value head
               ("f32", 96, 2, 4, 32, True, 2), ("bf16", 264, 1, 6, 128, True, 2), ("bf16", 520, 2, 4, 64, False, 2),
-              ("bf16", 1160, 1, 5, 128, True, 1)]
+              ("bf16", 1160, 1, 5, 128, True, 1),
+              # 7 query heads over one key / value head (the 56 / 8-head model of Section 5.1 at TP = 8)
+              ("bf16", 904, 1, 7, 128, True, 1), ("f32", 40, 1, 7, 16, True, 1)]
 
 
 @pytest.mark.parametrize("dtype,seq,mbsz,n,d,causal,nk", ATTN_CASES)
