@@ -25,6 +25,10 @@ alternates chunk-1 and chunk-0 blocks):
   cool-down   the remaining backward passes as full backward passes (their own W hides the all-reduce); the W
               blocks stored in the degraded phase float into waits that are long enough for them.
 It needs m >= 3p microbatches (the paper assumes p << m).
+
+For the simulator only, the two comparison rows of Table 1: `program_1f1b_interleaved` (parallel flow, unsplit
+backward; reproduces the table's PP and TP bubbles exactly) and `greedy_zero_bubble_v` (a list-scheduled
+Zero-Bubble-V style program; reproduces the table's TP bubble and peak memory).
 """
 from __future__ import annotations
 
@@ -62,8 +66,12 @@ class Times:
     TAR: float = 0.0
 
 
-def vstage(p: int, d: int, chunk: int) -> int:
-    return d if chunk == 0 else 2 * p - 1 - d
+def vstage(p: int, d: int, chunk: int, flow: str = "v") -> int:
+    """Virtual stage of model chunk `chunk` of device d: the "V" flow folds the second half back (device 0 holds the
+    first and the last stage), the parallel flow of interleaved 1F1B runs both halves in device order."""
+    if chunk == 0:
+        return d
+    return 2 * p - 1 - d if flow == "v" else p + d
 
 
 def device_program(p: int, m: int, d: int, steady_w_tail: int = 0) -> List[Block]:
@@ -128,14 +136,21 @@ def block_time(blk: Block, t: Times) -> Tuple[float, float]:
     return dur + exposed, exposed
 
 
-def simulate(p: int, programs: List[List[Block]], t: Times, float_w: bool = True) -> float:
+def simulate(p: int, programs: List[List[Block]], t: Times, float_w: bool = True, flow: str = "v",
+             atomic_bw: bool = False) -> float:
     """Fills start / end of every block and returns the makespan.  A device runs its blocks in order; F(v, i) waits
     for F(v-1, i), B(v, j) for F(v, j) and B(v+1, j), a W part for its B.  Results leave a block as soon as they
     exist: after T_F (+ exposed all-reduce) for a forward-only block, after T_B for a backward-only block (its W
     parts run last), after T_F + T_B for a braided block (its units interleave).  With float_w a W-only block
     whose B is done moves forward into a wait of at least T_W (the stored weight gradients fill the bubbles of
-    the cool-down phase); the programs are reordered in place accordingly."""
+    the cool-down phase); the programs are reordered in place accordingly.  `flow` names the stage order ("v" or
+    "parallel"); with atomic_bw a full backward pass hands its gradient on only when its W part is done too
+    (interleaved 1F1B does not split the backward pass)."""
     V = 2 * p
+
+    def vs(p_, d_, c_):          # virtual stage under the flow of this run
+        return vstage(p_, d_, c_, flow)
+
     f_out: Dict[Part, float] = {}
     b_out: Dict[Part, float] = {}
     idx, now = [0] * p, [0.0] * p
@@ -147,14 +162,14 @@ def simulate(p: int, programs: List[List[Block]], t: Times, float_w: bool = True
                 blk = programs[d][idx[d]]
                 ready, ok = now[d], True
                 if blk.f:
-                    v = vstage(p, d, blk.f[0])
+                    v = vs(p, d, blk.f[0])
                     if v > 0:
                         if (v - 1, blk.f[1]) not in f_out:
                             ok = False
                         else:
                             ready = max(ready, f_out[(v - 1, blk.f[1])])
                 if ok and blk.b:
-                    v = vstage(p, d, blk.b[0])
+                    v = vs(p, d, blk.b[0])
                     if (v, blk.b[1]) not in f_out:
                         ok = False
                     else:
@@ -167,17 +182,17 @@ def simulate(p: int, programs: List[List[Block]], t: Times, float_w: bool = True
                 if ok:
                     for x in blk.w:
                         if x != blk.b:
-                            if (vstage(p, d, x[0]), x[1]) not in b_out:
+                            if (vs(p, d, x[0]), x[1]) not in b_out:
                                 ok = False
                             else:
-                                ready = max(ready, b_out[(vstage(p, d, x[0]), x[1])])
+                                ready = max(ready, b_out[(vs(p, d, x[0]), x[1])])
                 if not ok:
                     break
                 w_only = bool(blk.w) and not blk.f and not blk.b
                 if float_w and not w_only and ready - now[d] >= t.TW - 1e-9:
                     k = next((k for k in range(idx[d] + 1, len(programs[d]))
                               if programs[d][k].w and not programs[d][k].f and not programs[d][k].b
-                              and all(b_out.get((vstage(p, d, x[0]), x[1]), float("inf")) <= now[d] + 1e-9
+                              and all(b_out.get((vs(p, d, x[0]), x[1]), float("inf")) <= now[d] + 1e-9
                                       for x in programs[d][k].w)), None)
                     if k is not None:
                         programs[d].insert(idx[d], programs[d].pop(k))
@@ -190,11 +205,11 @@ def simulate(p: int, programs: List[List[Block]], t: Times, float_w: bool = True
                 elif blk.f:
                     out = ready + t.TF + exposed
                 else:
-                    out = ready + t.TB + exposed
+                    out = ready + t.TB + exposed + (t.TW if atomic_bw and blk.b in blk.w else 0.0)
                 if blk.f:
-                    f_out[(vstage(p, d, blk.f[0]), blk.f[1])] = out
+                    f_out[(vs(p, d, blk.f[0]), blk.f[1])] = out
                 if blk.b:
-                    b_out[(vstage(p, d, blk.b[0]), blk.b[1])] = out
+                    b_out[(vs(p, d, blk.b[0]), blk.b[1])] = out
                 idx[d] += 1
                 done += 1
                 progress = True
@@ -235,10 +250,121 @@ def metrics(p: int, programs: List[List[Block]], t: Times) -> List[dict]:
     return out
 
 
-def table1(p: int, t: Times) -> dict:
-    """Table 1's closed forms for the proposed schedule (the paper calls the bubble size approximate)."""
-    return {"pp_bubble": (p - 1) * (t.TF + t.TAR + t.TB - t.TW), "tp_bubble": (2 * p + 1) * t.TAR,
-            "peak_activation": 3 * p}
+def table1(p: int, t: Times, row: str = "ours", m: int = 0) -> dict:
+    """Table 1's closed forms (the paper calls the bubble sizes approximate).  Rows: "ours" (the proposed schedule),
+    "1f1b-i" (interleaved 1F1B, two virtual stages) and "zb-v" (Zero Bubble V); the TP bubbles of the latter two
+    grow with the number of microbatches m."""
+    if row == "ours":
+        return {"pp_bubble": (p - 1) * (t.TF + t.TAR + t.TB - t.TW), "tp_bubble": (2 * p + 1) * t.TAR,
+                "peak_activation": 3 * p}
+    if row == "1f1b-i":
+        return {"pp_bubble": (p - 1) * (t.TF + t.TAR + t.TB + t.TW), "tp_bubble": 2 * m * t.TAR,
+                "peak_activation": 3 * p - 2}
+    if row == "zb-v":
+        return {"pp_bubble": (p - 1) * (t.TF + 2 * t.TAR + t.TB - 2 * t.TW), "tp_bubble": 4 * m * t.TAR,
+                "peak_activation": 2 * p}
+    raise ValueError(row)
+
+
+# ---- the two comparison rows of Table 1, for the simulator only (nothing of them runs on the GPU) -----------------
+def program_1f1b_interleaved(p: int, m: int, d: int) -> List[Block]:
+    """Interleaved 1F1B with two virtual stages per device in the parallel flow (device d holds stages d and p + d):
+    microbatches go through in groups of p, chunk 0 of a group then its chunk 1; device d runs 2(p-d-1) + p
+    forward passes ahead, then alternates one forward and one full backward pass, then drains.  Every forward
+    pass is a plain block (its all-reduce is exposed), every backward pass carries its own W (which hides its
+    all-reduce): Table 1's 2 m T_AR.  Needs m to be a multiple of p."""
+    if m % p:
+        raise ValueError("interleaved 1F1B takes the microbatches in groups of p: m must be a multiple of p")
+
+    def slot(k: int, backward: bool) -> Part:
+        c = (k // p) % 2
+        return (1 - c if backward else c, (k // (2 * p)) * p + k % p)
+
+    total = 2 * m
+    warm = min(2 * (p - d - 1) + p, total)
+    prog = [Block(f=slot(k, False)) for k in range(warm)]
+    for i in range(total - warm):
+        prog.append(Block(f=slot(warm + i, False)))
+        b = slot(i, True)
+        prog.append(Block(b=b, w=(b,)))
+    for i in range(total - warm, total):
+        b = slot(i, True)
+        prog.append(Block(b=b, w=(b,)))
+    return prog
+
+
+def greedy_zero_bubble_v(p: int, m: int, t: Times, cap: Optional[int] = None) -> List[List[Block]]:
+    """A Zero-Bubble-V style schedule for the simulator: the "V" flow, forward, activation-gradient and weight-
+    gradient passes all separate (every F and every B is a plain block with an exposed all-reduce: Table 1's
+    4 m T_AR), at most `cap` chunk-activations alive per device (default 2p, Table 1's peak).  Built by list
+    scheduling in simulated time: a free device takes a ready B (the one that became ready first), else a ready F
+    if its memory allows (one slot is kept for chunk 1), else a W whose B is done, else waits for the next result; the weight-gradient passes
+    so fill the waits.  Returns the programs with their start and end times filled."""
+    cap = 2 * p if cap is None else cap
+    V = 2 * p
+    INF = float("inf")
+    f_out: Dict[Part, float] = {}
+    b_out: Dict[Part, float] = {}
+    progs: List[List[Block]] = [[] for _ in range(p)]
+    now = [0.0] * p
+    nf, nb = [[0, 0] for _ in range(p)], [[0, 0] for _ in range(p)]
+    w_pending: List[List[Part]] = [[] for _ in range(p)]
+    alive = [0] * p
+    todo = 3 * 2 * m * p
+    def candidates(d: int):
+        cands = []
+        for c in (1, 0):
+            j = nb[d][c]
+            if j < m:
+                v = vstage(p, d, c)
+                r = max(f_out.get((v, j), INF), b_out.get((v + 1, j), INF) if v < V - 1 else 0.0)
+                if r < INF:
+                    cands.append((max(r, now[d]), 0, r, "b", c, j))
+        for c in (0, 1):
+            i = nf[d][c]
+            # one slot stays free for chunk 1, whose forward pass is what lets a backward pass (and with it the
+            # release of memory) begin: without it the chunk-0 forwards fill the memory and nothing can move
+            if i < m and alive[d] < (cap if c == 1 else cap - 1):
+                v = vstage(p, d, c)
+                r = f_out.get((v - 1, i), INF) if v > 0 else 0.0
+                if r < INF:
+                    cands.append((max(r, now[d]), 1, r, "f", c, i))
+        if w_pending[d]:
+            cands.append((now[d], 2, now[d], "w", *w_pending[d][0]))
+        return cands
+
+    while todo:
+        # the device that is free first and has something it can start moves next (ties: lowest index)
+        d, cands = -1, []
+        for x in sorted(range(p), key=lambda x: (now[x], x)):
+            cands = candidates(x)
+            if cands:
+                d = x
+                break
+        if d < 0:
+            raise RuntimeError("the greedy schedule deadlocks (memory cap too small?)")
+        # start as early as possible; among those, B before F before W
+        start, _, _, kind, c, i = min(cands)
+        if kind != "w" and start > now[d] + 1e-12 and w_pending[d] and start - now[d] >= t.TW - 1e-12:
+            kind, (c, i), start = "w", w_pending[d][0], now[d]
+        if kind == "f":
+            blk = Block(f=(c, i), start=start, end=start + t.TF + t.TAR)
+            f_out[(vstage(p, d, c), i)] = blk.end
+            nf[d][c] += 1
+            alive[d] += 1
+        elif kind == "b":
+            blk = Block(b=(c, i), start=start, end=start + t.TB + t.TAR)
+            b_out[(vstage(p, d, c), i)] = blk.end
+            nb[d][c] += 1
+            alive[d] -= 1
+            w_pending[d].append((c, i))
+        else:
+            blk = Block(w=((c, i),), start=start, end=start + t.TW)
+            w_pending[d].pop(0)
+        progs[d].append(blk)
+        now[d] = blk.end
+        todo -= 1
+    return progs
 
 
 def braid_steps(program: Sequence[Block], n_layers: int, first_of_chunk1: int):

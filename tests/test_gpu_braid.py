@@ -266,7 +266,8 @@ def test_two_chunk_patterns_give_the_same_bits_and_match_the_oracle(ctx):
 def test_generated_device_program_runs_and_matches_the_two_chunk_sequence(ctx, p, m, d):
     """A device's program from the schedule generator (Section 4.2), replayed block by block on a two-chunk stage:
     same activation gradients bit for bit as the plain two-chunk sequence, weight gradients equal up to the
-    order in which the microbatches are added."""
+    order in which the microbatches are added, and the outputs and input gradients of sampled microbatches equal
+    to the oracle's."""
     from paper_2510_27257_amd import schedule as S
     from paper_2510_27257_amd.stage import two_chunk_sequence
     lm = Workload("g", 256, 2, 64, 512, 136, 4)
@@ -286,3 +287,27 @@ def test_generated_device_program_runs_and_matches_the_two_chunk_sequence(ctx, p
         for k, r in ref_w[l].items():
             got = stg.g_dev[l][k]
             assert float((got - r).abs().max()) <= 1e-5 * float(r.abs().max()) + 1e-12, (l, k)
+    # and against the oracle directly: the first and the last microbatch of either chunk, forward output and input
+    # gradient, through every layer of the chunk (identity at the AR points)
+    for ci, (first, last) in enumerate(stg.chains()):
+        for mb in (0, m - 1):
+            x = synth.make_activation(layers[first], 8, f"c{ci}.x.mb{mb}").astype(np.float64)
+            dy = synth.make_activation(layers[last], 8, f"c{ci}.dy.mb{mb}").astype(np.float64)
+            sts = []
+            for l in range(first, last + 1):
+                cfg, W = oracle_cfg(layers[l]), {k: v.astype(np.float64) for k, v in stg.w_host[l].items()}
+                st = {}
+                O.forward_unit(cfg, O.PRE_ATTN, W, st, x_in=x)
+                xa = O.forward_unit(cfg, O.ATTN, W, st, x_resid=x)
+                O.forward_unit(cfg, O.PRE_MLP, W, st, x_in=xa)
+                x = O.forward_unit(cfg, O.MLP, W, st, x_resid=xa)
+                sts.append(st)
+            assert rel_err(to_host(stg.chain_output(last, mb)), x) < TOL[lm.dtype], (ci, mb)
+            for l in reversed(range(first, last + 1)):
+                cfg, W = oracle_cfg(layers[l]), {k: v.astype(np.float64) for k, v in stg.w_host[l].items()}
+                st = sts[l - first]
+                dz = O.backward_input_unit(cfg, O.MLP, W, st, dy)
+                dxa = O.backward_input_unit(cfg, O.PRE_MLP, W, st, dz, d_resid=dy)
+                dxl = O.backward_input_unit(cfg, O.ATTN, W, st, dxa)
+                dy = O.backward_input_unit(cfg, O.PRE_ATTN, W, st, dxl, d_resid=dxa)
+            assert rel_err(to_host(stg.grad_slot(first, mb)), dy) < TOL[lm.dtype], (ci, mb)

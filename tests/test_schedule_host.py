@@ -32,9 +32,10 @@ def test_every_part_runs_exactly_once_on_its_device(p, m):
             assert all(x in seen for x in b.w)
 
 
-def check_dependencies(p, progs, t):
+def check_dependencies(p, progs, t, flow="v", atomic_bw=False):
     """Independent of the simulator's bookkeeping: every start respects the results it needs."""
     V = 2 * p
+    vstage = lambda p_, d_, c_: S.vstage(p_, d_, c_, flow)
     f_done, b_done, pos = {}, {}, {}
     for d, prog in enumerate(progs):
         prev_end = 0.0
@@ -49,25 +50,25 @@ def check_dependencies(p, progs, t):
             elif blk.f:
                 out = blk.start + t.TF + (t.TAR if alone else 0)
             else:
-                out = blk.start + t.TB + (t.TAR if alone else 0)
+                out = blk.start + t.TB + (t.TAR if alone else 0) + (t.TW if atomic_bw and blk.b in blk.w else 0)
             if blk.f:
-                f_done[(S.vstage(p, d, blk.f[0]), blk.f[1])] = out
+                f_done[(vstage(p, d, blk.f[0]), blk.f[1])] = out
             if blk.b:
-                b_done[(S.vstage(p, d, blk.b[0]), blk.b[1])] = out
+                b_done[(vstage(p, d, blk.b[0]), blk.b[1])] = out
     for d, prog in enumerate(progs):
         for blk in prog:
             if blk.f:
-                v, i = S.vstage(p, d, blk.f[0]), blk.f[1]
+                v, i = vstage(p, d, blk.f[0]), blk.f[1]
                 if v > 0:
                     assert blk.start >= f_done[(v - 1, i)] - 1e-9
             if blk.b:
-                v, j = S.vstage(p, d, blk.b[0]), blk.b[1]
+                v, j = vstage(p, d, blk.b[0]), blk.b[1]
                 assert blk.start >= f_done[(v, j)] - 1e-9
                 if v < V - 1:
                     assert blk.start >= b_done[(v + 1, j)] - 1e-9
             for x in blk.w:
                 if x != blk.b:
-                    assert blk.start >= b_done[(S.vstage(p, d, x[0]), x[1])] - 1e-9
+                    assert blk.start >= b_done[(vstage(p, d, x[0]), x[1])] - 1e-9
 
 
 @pytest.mark.parametrize("p,m", CASES)
@@ -98,8 +99,102 @@ def test_table1_tp_bubble_and_peak_activation_memory(p, m, t):
         assert x["peak_with_w_stash"] >= x["peak_activation"]
     assert ms[0]["peak_activation"] == ref["peak_activation"]
     # every device waits the same total time, and never less than Table 1's (approximate) PP bubble
+    # (test_pp_bubble_against_table1_and_its_floor looks at what the difference is made of)
     assert max(x["pp_bubble"] for x in ms) - min(x["pp_bubble"] for x in ms) < 1e-6
     assert ms[0]["pp_bubble"] >= ref["pp_bubble"] - 1e-9
+
+
+def test_pp_bubble_against_table1_and_its_floor():
+    """Table 1 gives the PP bubble of the proposed schedule as approximately (p-1)(T_F + T_AR + T_B - T_W).  Its
+    first part, (p-1)(T_F + T_AR), is a floor for ANY schedule: the last device cannot start before the first
+    microbatch has crossed p-1 stages, every device is busy for the same time, so nobody waits less in total.  The
+    construction here (made from the text; the schedule figure is not in it) meets that floor exactly at the start
+    of the last device, does not depend on the number of microbatches, and with no weight-gradient separation in
+    the steady phase stays above the closed form (at most 2.5 times): its excess sits in the last device's wait
+    for the first gradient to come round and in the cool-down, which only stored weight-gradient blocks can fill.
+    Storing the W of the last steady braids (steady_w_tail) never makes it larger and never brings it below the
+    closed form (it comes within 6 % of it for T_AR = T_F)."""
+    for t in TIMES:
+        for p in (2, 3, 4, 8):
+            bubbles = []
+            for m in (3 * p, 3 * p + 5, 6 * p):
+                progs = S.build(p, m)
+                S.simulate(p, progs, t)
+                ms = S.metrics(p, progs, t)
+                floor = (p - 1) * (t.TF + t.TAR)
+                assert abs(ms[p - 1]["start_idle"] - floor) < 1e-9
+                assert all(x["pp_bubble"] >= floor - 1e-9 for x in ms)
+                bubbles.append(ms[0]["pp_bubble"])
+            assert max(bubbles) - min(bubbles) < 1e-6               # the bubble is a property of p and the times only
+            ref = S.table1(p, t)["pp_bubble"]
+            assert ref - 1e-9 <= bubbles[0] <= 2.5 * ref
+            for tail in (p, 2 * p):
+                progs = S.build(p, 6 * p, steady_w_tail=tail)
+                S.simulate(p, progs, t)
+                b = S.metrics(p, progs, t)[0]["pp_bubble"]
+                assert ref - 1e-9 <= b <= bubbles[0] + 1e-9
+                prev = b
+
+
+ROW_CASES = [(1, 3), (2, 8), (3, 9), (4, 12), (4, 24), (8, 24), (8, 40)]
+
+
+@pytest.mark.parametrize("p,m", ROW_CASES)
+@pytest.mark.parametrize("t", TIMES)
+def test_table1_row_of_interleaved_1f1b(p, m, t):
+    """Table 1, row 1F1B-I (two virtual stages, parallel flow, unsplit backward): the simulated programs give the PP
+    bubble (p-1)(T_F + T_AR + T_B + T_W) and the TP bubble 2 m T_AR exactly, on every device; the activations alive
+    on device d peak at 3p - 2 - 2d before the steady phase (the table's figure for device 0) plus the one forward
+    pass of a steady pair that runs before its backward pass frees a slot."""
+    progs = [S.program_1f1b_interleaved(p, m, d) for d in range(p)]
+    want = sorted(itertools.product((0, 1), range(m)))
+    for prog in progs:
+        assert sorted(b.f for b in prog if b.f) == want and sorted(b.b for b in prog if b.b) == want
+        assert all(b.w == (b.b,) for b in prog if b.b) and all(not b.w for b in prog if b.f)
+    S.simulate(p, progs, t, float_w=False, flow="parallel", atomic_bw=True)
+    check_dependencies(p, progs, t, flow="parallel", atomic_bw=True)
+    ref = S.table1(p, t, "1f1b-i", m)
+    for d, x in enumerate(S.metrics(p, progs, t)):
+        assert abs(x["pp_bubble"] - ref["pp_bubble"]) < 1e-6
+        assert abs(x["tp_bubble"] - ref["tp_bubble"]) < 1e-9
+        warm = min(2 * (p - d - 1) + p, 2 * m)
+        assert x["peak_activation"] == min(warm + 1, 2 * m)
+    assert min(2 * (p - 1) + p, 2 * m) == min(ref["peak_activation"], 2 * m)
+
+
+@pytest.mark.parametrize("p,m", ROW_CASES)
+@pytest.mark.parametrize("t", TIMES)
+def test_table1_row_of_zero_bubble_v(p, m, t):
+    """Table 1, row ZB-V, from a list-scheduled program (forward, activation-gradient and weight-gradient passes all
+    separate, "V" flow, at most 2p chunk-activations alive): TP bubble 4 m T_AR and peak activation memory 2p as
+    in the table.  The PP bubble of this greedy program is above the table's (p-1)(T_F + 2 T_AR + T_B - 2 T_W),
+    which belongs to a hand-made schedule: unpinned."""
+    progs = S.greedy_zero_bubble_v(p, m, t)
+    want = sorted(itertools.product((0, 1), range(m)))
+    for prog in progs:
+        assert sorted(b.f for b in prog if b.f) == want and sorted(b.b for b in prog if b.b) == want
+        assert sorted(x for b in prog for x in b.w) == want
+        assert all(sum(map(bool, (b.f, b.b, b.w))) == 1 for b in prog)
+    check_dependencies(p, progs, t)
+    ref = S.table1(p, t, "zb-v", m)
+    for x in S.metrics(p, progs, t):
+        assert abs(x["tp_bubble"] - ref["tp_bubble"]) < 1e-9
+        assert x["peak_activation"] == min(ref["peak_activation"], 2 * m)
+        assert x["pp_bubble"] >= min(ref["pp_bubble"], (p - 1) * (t.TF + t.TAR)) - 1e-9
+
+
+@pytest.mark.parametrize("p,m", [(2, 8), (4, 12), (4, 24), (8, 24), (8, 40)])
+def test_with_tp_communication_the_proposed_schedule_finishes_first(p, m):
+    """The comparison of Section 5 in the simulator: once the all-reduce time is a sizeable part of a chunk's
+    forward time, the proposed schedule finishes before interleaved 1F1B, and Zero Bubble V, which exposes the
+    all-reduce of every forward and every backward pass, is the slowest of the three."""
+    for t in (S.Times(1.0, 1.0, 0.6, 0.25), S.Times(1.0, 2.0, 1.0, 0.5), S.Times(1.0, 1.3, 1.1, 1.0)):
+        ours = S.build(p, m)
+        T_ours = S.simulate(p, ours, t)
+        i1 = [S.program_1f1b_interleaved(p, m, d) for d in range(p)]
+        T_1f1b = S.simulate(p, i1, t, float_w=False, flow="parallel", atomic_bw=True)
+        T_zbv = max(b.end for pr in S.greedy_zero_bubble_v(p, m, t) for b in pr)
+        assert T_ours < T_1f1b < T_zbv
 
 
 def test_simulator_on_a_case_worked_by_hand():
