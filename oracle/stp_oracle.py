@@ -148,6 +148,29 @@ def rope(x, base: float, inverse: bool = False):
 
 
 # --------------------------------------------------------------------------
+# Row softmax on its own (the normalisation inside "Attention(.)" of Eq. 1, as a stand-alone operation:
+# the HIP side has a stand-alone softmax kernel pair that is judged on memory bandwidth)
+# --------------------------------------------------------------------------
+def softmax_fwd(x, scale: float = 1.0, causal: bool = False):
+    """y[r, :] = softmax(scale * x[r, :]).  causal: the rows are stacked [n, n] squares and element j of row r is
+    masked when j > r mod n (a key after the query)."""
+    x = np.asarray(x, np.float64) * scale
+    rows, n = x.shape
+    if causal:
+        r = np.arange(rows)[:, None] % n
+        x = np.where(np.arange(n)[None, :] <= r, x, -np.inf)
+    e = np.exp(x - x.max(axis=1, keepdims=True))
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def softmax_bwd(y, dy, scale: float = 1.0):
+    """Gradient w.r.t. x of softmax_fwd given its output y and the upstream gradient dy:
+    dx = scale * y o (dy - rowsum(dy o y))."""
+    y, dy = np.asarray(y, np.float64), np.asarray(dy, np.float64)
+    return scale * y * (dy - (dy * y).sum(axis=1, keepdims=True))
+
+
+# --------------------------------------------------------------------------
 # Attention core (per head, no communication; "Attention(.)" of Eq. 1)
 # --------------------------------------------------------------------------
 def _probs(q, k, causal: bool):

@@ -424,3 +424,49 @@ def test_zero_weights_leave_pure_residual(t):
     np.testing.assert_allclose(dxl, 0, atol=1e-15)
     dx = O.backward_input_unit(cfg, O.PRE_ATTN, W, st, dxl, d_resid=dxa)
     np.testing.assert_allclose(dx, dxa, atol=1e-15)
+
+
+# ---- the stand-alone row softmax ------------------------------------------------------------------------------
+def test_softmax_against_torch_and_its_closed_forms():
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((12, 6)) * 3
+    dy = rng.standard_normal((12, 6))
+    for scale in (1.0, 0.35):
+        xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+        yt = torch.softmax(xt * scale, dim=1)
+        yt.backward(torch.tensor(dy))
+        y = O.softmax_fwd(x, scale)
+        np.testing.assert_allclose(y, yt.detach().numpy(), rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(O.softmax_bwd(y, dy, scale), xt.grad.numpy(), rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(y.sum(1), 1.0, rtol=1e-14)                      # rows are distributions
+        np.testing.assert_allclose(O.softmax_bwd(y, dy, scale).sum(1), 0.0, atol=1e-14)   # shifts of a row change nothing
+    # a constant row is uniform; adding a constant to a row changes nothing; a far larger entry takes everything
+    np.testing.assert_allclose(O.softmax_fwd(np.full((2, 5), 7.0)), 0.2, rtol=1e-15)
+    np.testing.assert_allclose(O.softmax_fwd(x + 100.0), O.softmax_fwd(x), rtol=1e-12)
+    big = np.zeros((1, 4)); big[0, 2] = 800.0
+    np.testing.assert_allclose(O.softmax_fwd(big), [[0, 0, 1, 0]], atol=1e-300)
+    # central differences of sum(y * R)
+    R = rng.standard_normal(x.shape)
+    g = O.softmax_bwd(O.softmax_fwd(x, 0.7), R, 0.7)
+    for (i, j) in [(0, 0), (5, 3), (11, 5)]:
+        h = 1e-6
+        xp, xm = x.copy(), x.copy()
+        xp[i, j] += h; xm[i, j] -= h
+        fd = ((O.softmax_fwd(xp, 0.7) * R).sum() - (O.softmax_fwd(xm, 0.7) * R).sum()) / (2 * h)
+        assert abs(fd - g[i, j]) < 1e-8
+
+
+def test_causal_softmax_masks_keys_after_the_query():
+    rng = np.random.default_rng(12)
+    n = 5
+    x = rng.standard_normal((2 * n, n))          # two stacked [n, n] squares
+    y = O.softmax_fwd(x, 0.5, causal=True)
+    for r in range(2 * n):
+        i = r % n
+        assert np.all(y[r, i + 1:] == 0.0)
+        e = np.exp(0.5 * (x[r, :i + 1] - x[r, :i + 1].max()))      # the unmasked prefix, by its own definition
+        np.testing.assert_allclose(y[r, :i + 1], e / e.sum(), rtol=1e-14)
+    np.testing.assert_allclose(y[0], [1, 0, 0, 0, 0], atol=0)       # the first query sees only its own key
+    # and it is the normalisation the attention oracle applies to q k^T / sqrt(d)
+    q, k = rng.standard_normal((n, 8)), rng.standard_normal((n, 8))
+    np.testing.assert_allclose(O.softmax_fwd(q @ k.T, 1 / np.sqrt(8), causal=True), O._probs(q, k, True), rtol=1e-13)
