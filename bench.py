@@ -140,6 +140,8 @@ def hbm_leg(ctx, wl, torch, stp):
         ("gelu_fwd", 2 * T * f * es, lambda: ctx.gelu_forward(code, T * f, hh, hy)),
         ("gelu_bwd", 3 * T * f * es, lambda: ctx.gelu_backward(code, T * f, hh, hd, hy)),
         ("swiglu_fwd", 3 * T * f * es, lambda: ctx.swiglu_forward(code, T * f, hh, hd, hy)),
+        ("softmax_fwd_T_h", 2 * T * h * es, lambda: ctx.softmax_forward(code, T, h, 0.125, False, x, y)),
+        ("softmax_bwd_T_h", 3 * T * h * es, lambda: ctx.softmax_backward(code, T, h, 0.125, x, dy, y)),
         ("colsum_T_h", T * h * es, lambda: ctx.colsum(code, T, h, x, 1.0, outb)),
         ("colsum_T_f", T * f * es, lambda: ctx.colsum(code, T, f, hh, 1.0, outb[:f])),
         # the practical ceiling: plain device copies of the same sizes (tensors of 25-100 MB are partly served by

@@ -343,6 +343,15 @@ int stp_gelu_backward(stp_ctx *ctx, int dtype, size_t n, const void *x, const vo
 int stp_swiglu_forward(stp_ctx *ctx, int dtype, size_t n, const void *gate, const void *up, void *y, void *hip_stream);
 int stp_swiglu_backward(stp_ctx *ctx, int dtype, size_t n, const void *gate, const void *up, const void *dy,
                         void *dgate, void *dup, void *hip_stream);
+/* Row softmax on its own (the normalisation inside "Attention(.)" of Eq. 1; the attention kernels fuse theirs, this
+ * pair is for measuring it against the memory system).  x, y, dy, dx are [rows, n], n a multiple of 8, at most 16384.
+ *   forward : y = softmax(scale * x) per row; causal = 1: the rows are stacked [n, n] squares and element j of row r
+ *             is masked (y = 0) for j > r mod n
+ *   backward: dx = scale * y o (dy - rowsum(dy o y)) */
+int stp_softmax_forward(stp_ctx *ctx, int dtype, int32_t rows, int32_t n, float scale, int causal, const void *x, void *y,
+                        void *hip_stream);
+int stp_softmax_backward(stp_ctx *ctx, int dtype, int32_t rows, int32_t n, float scale, const void *y, const void *dy,
+                         void *dx, void *hip_stream);
 /* In-place rotary embedding of the Q and K heads of qkv [T, (n + 2 n_kv) d]; inverse = 1 applies the transpose. */
 int stp_rope(stp_ctx *ctx, const stp_layer_desc *desc, void *qkv, int inverse, void *hip_stream);
 /* out[N] += scale * sum over rows of x[T,N]  (bias gradients). */

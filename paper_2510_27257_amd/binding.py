@@ -32,7 +32,7 @@ EXPORTED_SYMBOLS = [
     "stp_backward_input_unit", "stp_backward_weight_unit", "stp_braid_step", "stp_validate_ops",
     "stp_braid_reset", "stp_braid_detach", "stp_attention_plan", "stp_gemm", "stp_norm_forward", "stp_norm_backward", "stp_attention_forward",
     "stp_attention_backward", "stp_gelu_forward", "stp_gelu_backward", "stp_swiglu_forward",
-    "stp_swiglu_backward", "stp_rope", "stp_colsum", "stp_colsum_noalloc", "stp_clock_probe", "stp_wall_clock_khz",
+    "stp_swiglu_backward", "stp_softmax_forward", "stp_softmax_backward", "stp_rope", "stp_colsum", "stp_colsum_noalloc", "stp_clock_probe", "stp_wall_clock_khz",
     "stp_offload_bytes", "stp_stash_offload", "stp_stash_reload",
 ]
 
@@ -139,6 +139,8 @@ def lib() -> C.CDLL:
     L.stp_gelu_backward.argtypes = [vp, C.c_int, sz, vp, vp, vp, vp]
     L.stp_swiglu_forward.argtypes = [vp, C.c_int, sz, vp, vp, vp, vp]
     L.stp_swiglu_backward.argtypes = [vp, C.c_int, sz, vp, vp, vp, vp, vp, vp]
+    L.stp_softmax_forward.argtypes = [vp, C.c_int, i32, i32, f32, C.c_int, vp, vp, vp]
+    L.stp_softmax_backward.argtypes = [vp, C.c_int, i32, i32, f32, vp, vp, vp, vp]
     L.stp_rope.argtypes = [vp, P(LayerDesc), vp, C.c_int, vp]
     L.stp_colsum.argtypes = [vp, C.c_int, i32, i32, vp, f32, vp, C.c_int, vp]
     L.stp_colsum_noalloc.argtypes = [vp, C.c_int, i32, i32, vp, f32, vp, vp]
@@ -341,6 +343,14 @@ class Context:
     def swiglu_backward(self, dtype, n, gate, up, dy, dgate, dup, stream=None):
         self.check(self._lib.stp_swiglu_backward(self._h, dtype, n, _ptr(gate), _ptr(up), _ptr(dy), _ptr(dgate),
                                                  _ptr(dup), _stream(stream)), "stp_swiglu_backward")
+
+    def softmax_forward(self, dtype, rows, n, scale, causal, x, y, stream=None):
+        self.check(self._lib.stp_softmax_forward(self._h, dtype, rows, n, scale, int(causal), _ptr(x), _ptr(y),
+                                                 _stream(stream)), "stp_softmax_forward")
+
+    def softmax_backward(self, dtype, rows, n, scale, y, dy, dx, stream=None):
+        self.check(self._lib.stp_softmax_backward(self._h, dtype, rows, n, scale, _ptr(y), _ptr(dy), _ptr(dx),
+                                                  _stream(stream)), "stp_softmax_backward")
 
     def rope(self, desc, qkv, inverse=False, stream=None):
         self.check(self._lib.stp_rope(self._h, C.byref(desc), _ptr(qkv), int(inverse), _stream(stream)), "stp_rope")

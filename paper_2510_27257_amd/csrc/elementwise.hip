@@ -6,51 +6,62 @@
 #include "common.h"
 
 // ======================================================================
-// Norm forward: one 64-lane wave per token row, row kept in registers.
-// chunk c of a lane covers elements (c*64 + lane)*8 .. +7
+// Norm forward: one 256-thread group per token row, the row in registers (chunk c of a thread covers
+// elements (c*256 + tid)*8 .. +7), mean and variance (two passes over the registers) through cross-lane
+// reductions and LDS.  Many short-lived groups keep several rows of loads in flight per compute unit
+// and fill in wherever other streams' kernels leave room (one wave per row measured 4.5 TB/s at
+// [6144, 4096] bf16, this shape 6 TB/s).
 // ======================================================================
+__device__ __forceinline__ float block_sum_256(float v, float *red) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  v = wave_sum(v);
+  if (lane == 0) red[wv] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 template <typename T, int NORM, int NCH>
 __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, const T *__restrict__ gamma,
                                                        const T *__restrict__ beta, T *__restrict__ y,
                                                        float *__restrict__ stats, int rows, int h, float eps) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (row >= rows) return;
+  __shared__ float red[8];
+  const int tid = threadIdx.x;
+  const int row = blockIdx.x;
   const T *xr = x + (size_t)row * h;
   float v[NCH][8];
   float s = 0.f;
 #pragma unroll
   for (int c = 0; c < NCH; c++) {
-    int col = (c * 64 + lane) * 8;
+    const int col = (c * 256 + tid) * 8;
     if (col < h) {
       Vec8<T>::load(xr + col, v[c]);
 #pragma unroll
       for (int i = 0; i < 8; i++) s += (NORM == STP_NORM_LN) ? v[c][i] : v[c][i] * v[c][i];
     }
   }
-  s = wave_sum(s);
+  s = block_sum_256(s, red);
   float mean = 0.f, rstd;
   if (NORM == STP_NORM_LN) {
     mean = s / (float)h;
     float q = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; c++) {
-      int col = (c * 64 + lane) * 8;
+      const int col = (c * 256 + tid) * 8;
       if (col < h) {
 #pragma unroll
         for (int i = 0; i < 8; i++) { float d = v[c][i] - mean; q += d * d; }
       }
     }
-    q = wave_sum(q);
+    q = block_sum_256(q, red + 4);
     rstd = 1.0f / sqrtf(q / (float)h + eps);
   } else {
     rstd = 1.0f / sqrtf(s / (float)h + eps);
   }
-  if (lane == 0) { stats[2 * (size_t)row] = mean; stats[2 * (size_t)row + 1] = rstd; }
+  if (tid == 0) { stats[2 * (size_t)row] = mean; stats[2 * (size_t)row + 1] = rstd; }
   T *yr = y + (size_t)row * h;
 #pragma unroll
   for (int c = 0; c < NCH; c++) {
-    int col = (c * 64 + lane) * 8;
+    const int col = (c * 256 + tid) * 8;
     if (col < h) {
       float g[8], b[8], o[8];
       Vec8<T>::load(gamma + col, g);
@@ -239,21 +250,25 @@ __global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__rest
 // ======================================================================
 constexpr int CS_ROWS = STP_COLSUM_ROWS;
 
-template <typename T>
+// RL row-lanes x (256 / RL) column chunks of 8: RL = 8 gives 64-row x 256-column patches with one batch of 8
+// loads per thread.  (RL = 2, patches of 1024 columns whose row pieces are 2 KB of contiguous memory, takes four
+// batches per thread one after the other and measured half the rate.)
+template <typename T, int RL>
 __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ x, int rows, int n,
                                                      float *__restrict__ partial) {
-  __shared__ float red[8][32][9];
-  const int cc = threadIdx.x & 31, rl = threadIdx.x >> 5;
-  const int col = (blockIdx.x * 32 + cc) * 8;
+  constexpr int CC = 256 / RL, PER = CS_ROWS / RL;      // column chunks per group, rows per thread
+  __shared__ float red[RL][CC][9];
+  const int cc = threadIdx.x % CC, rl = threadIdx.x / CC;
+  const int col = (blockIdx.x * CC + cc) * 8;
   const int r0 = blockIdx.y * CS_ROWS;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (col < n) {
 #pragma unroll
-    for (int b = 0; b < CS_ROWS / 64; b++) {
+    for (int b = 0; b < PER / 8; b++) {
       float v[8][8];
 #pragma unroll
       for (int u = 0; u < 8; u++) {
-        const int r = r0 + 64 * b + rl + 8 * u;
+        const int r = r0 + rl + RL * (8 * b + u);
         if (r < rows) Vec8<T>::load(x + (size_t)r * n + col, v[u]);
         else {
 #pragma unroll
@@ -275,7 +290,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ x, in
     for (int i = 0; i < 8; i++) {
       float t = 0.f;
 #pragma unroll
-      for (int k = 0; k < 8; k++) t += red[k][cc][i];
+      for (int k = 0; k < RL; k++) t += red[k][cc][i];
       s[i] = t;
     }
     Vec8<float>::store(partial + (size_t)blockIdx.y * n + col, s);
@@ -336,6 +351,103 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T *__restrict__ g
     }
     Vec8<T>::store(dgate + i * 8, dg);
     Vec8<T>::store(dup + i * 8, du);
+  }
+}
+
+// ======================================================================
+// Row softmax on its own (the attention kernels fuse theirs; this pair exists so that the normalisation can be
+// measured against the memory system by itself).  A 256-thread group per row, the row in registers
+// (chunk c of a thread covers elements (c*256 + tid)*8 .. +7), row maximum and row sum through cross-lane
+// reductions and LDS.  causal: the rows are stacked [n, n] squares; element j of row r is masked for j > r mod n.
+//   forward : y = softmax(scale * x)
+//   backward: dx = scale * y o (dy - rowsum(dy o y))
+// ======================================================================
+__device__ __forceinline__ float block_reduce_256(float v, bool is_max, float *red, int it) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  v = is_max ? wave_max(v) : wave_sum(v);
+  if (lane == 0) red[(it & 1) * 4 + wv] = v;
+  __syncthreads();
+  const float *r = red + (it & 1) * 4;
+  return is_max ? fmaxf(fmaxf(r[0], r[1]), fmaxf(r[2], r[3])) : (r[0] + r[1]) + (r[2] + r[3]);
+}
+
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int rows, int n,
+                                                          float scale_log2e, int causal) {
+  __shared__ float red[16];
+  const int tid = threadIdx.x;
+  const int row = blockIdx.x;
+  const int limit = causal ? (row % n) + 1 : n;      // keys 0 .. limit-1 take part
+  const T *xr = x + (size_t)row * n;
+  float v[NCH][8];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    const int col = (c * 256 + tid) * 8;
+    if (col < limit) {
+      Vec8<T>::load(xr + col, v[c]);
+#pragma unroll
+      for (int i = 0; i < 8; i++) {
+        v[c][i] = col + i < limit ? v[c][i] * scale_log2e : -INFINITY;
+        mx = fmaxf(mx, v[c][i]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; i++) v[c][i] = -INFINITY;
+    }
+  }
+  mx = block_reduce_256(mx, true, red, 0);
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; c++)
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      v[c][i] = __builtin_amdgcn_exp2f(v[c][i] - mx);      // exp2(-inf) = 0 for the masked keys
+      sum += v[c][i];
+    }
+  sum = block_reduce_256(sum, false, red, 1);
+  const float inv = 1.0f / sum;
+  T *yr = y + (size_t)row * n;
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    const int col = (c * 256 + tid) * 8;
+    if (col < n) {
+      float o[8];
+#pragma unroll
+      for (int i = 0; i < 8; i++) o[i] = v[c][i] * inv;
+      Vec8<T>::store(yr + col, o);
+    }
+  }
+}
+
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(const T *__restrict__ y, const T *__restrict__ dy, T *__restrict__ dx,
+                                                          int rows, int n, float scale) {
+  __shared__ float red[16];
+  const int tid = threadIdx.x;
+  const size_t off = (size_t)blockIdx.x * n;
+  float p[NCH][8], g[NCH][8];
+  float dot = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    const int col = (c * 256 + tid) * 8;
+    if (col < n) {
+      Vec8<T>::load(y + off + col, p[c]);
+      Vec8<T>::load(dy + off + col, g[c]);
+#pragma unroll
+      for (int i = 0; i < 8; i++) dot += p[c][i] * g[c][i];
+    }
+  }
+  dot = block_reduce_256(dot, false, red, 0);
+#pragma unroll
+  for (int c = 0; c < NCH; c++) {
+    const int col = (c * 256 + tid) * 8;
+    if (col < n) {
+      float o[8];
+#pragma unroll
+      for (int i = 0; i < 8; i++) o[i] = scale * p[c][i] * (g[c][i] - dot);
+      Vec8<T>::store(dx + off + col, o);
+    }
   }
 }
 
@@ -437,18 +549,16 @@ static inline int ew_grid(size_t n8) {
 template <typename T>
 static int norm_fwd_dispatch(stp_ctx *ctx, int norm, int rows, int h, float eps, const void *x, const void *gamma,
                              const void *beta, void *y, float *stats, hipStream_t s) {
-  dim3 grid((rows + 3) / 4), block(256);
-  int nch = (h + 511) / 512;
+  dim3 grid(rows), block(256);
+  int nch = (h + 2047) / 2048;
 #define LAUNCH(NORM, NCH)                                                                               \
   hipLaunchKernelGGL((norm_fwd_kernel<T, NORM, NCH>), grid, block, 0, s, (const T *)x, (const T *)gamma, \
                      (const T *)beta, (T *)y, stats, rows, h, eps)
 #define BY_NCH(NORM)                                   \
   if (nch <= 1) LAUNCH(NORM, 1);                       \
   else if (nch <= 2) LAUNCH(NORM, 2);                  \
-  else if (nch <= 4) LAUNCH(NORM, 4);                  \
-  else if (nch <= 8) LAUNCH(NORM, 8);                  \
-  else if (nch <= 12) LAUNCH(NORM, 12);                \
-  else LAUNCH(NORM, 16);
+  else if (nch <= 3) LAUNCH(NORM, 3);                  \
+  else LAUNCH(NORM, 4);
   if (norm == STP_NORM_LN) { BY_NCH(STP_NORM_LN) } else { BY_NCH(STP_NORM_RMS) }
 #undef BY_NCH
 #undef LAUNCH
@@ -539,8 +649,8 @@ extern "C" int stp_norm_backward(stp_ctx *ctx, int dtype, int norm, int32_t T, i
 static int colsum_launch(stp_ctx *ctx, int dtype, int T, int N, const void *x, float scale, float *out, float *partial, hipStream_t s) {
   const int slabs = stp_colsum_slabs(T);
   dim3 grid((N / 8 + 31) / 32, slabs), block(256);
-  if (dtype == STP_BF16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, block, 0, s, (const bf16_t *)x, T, N, partial);
-  else hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float *)x, T, N, partial);
+  if (dtype == STP_BF16) hipLaunchKernelGGL((colsum_kernel<bf16_t, 8>), grid, block, 0, s, (const bf16_t *)x, T, N, partial);
+  else hipLaunchKernelGGL((colsum_kernel<float, 8>), grid, block, 0, s, (const float *)x, T, N, partial);
   STP_LAUNCH_CHECK(ctx);
   ReduceOut ro = {{out, nullptr, nullptr}, {scale, 0.f, 0.f}};
   hipLaunchKernelGGL(partial_reduce_kernel, dim3((N + 63) / 64), dim3(256), 0, s, partial, slabs, (size_t)N, N, N, ro);
@@ -727,5 +837,50 @@ extern "C" int stp_wall_clock_khz(stp_ctx *ctx, int *khz) {
   if (!ctx) return STP_EINVAL;
   if (!khz) return stp_fail(ctx, STP_EINVAL, "stp_wall_clock_khz: null pointer%s");
   STP_HIP(ctx, hipDeviceGetAttribute(khz, hipDeviceAttributeWallClockRate, ctx->device));
+  return STP_OK;
+}
+
+static int softmax_args_ok(stp_ctx *ctx, const char *who, int dtype, int32_t rows, int32_t n, const void *a, const void *b,
+                           const void *c) {
+  if (!a || !b || !c) return stp_fail(ctx, STP_EINVAL, "%s: null pointer", who);
+  if (dtype != STP_BF16 && dtype != STP_F32) return stp_fail(ctx, STP_EINVAL, "%s: bad dtype", who);
+  if (rows < 0 || n <= 0 || n % 8 || n > 16384) return stp_fail(ctx, STP_ESHAPE, "%s: n must be a multiple of 8, at most 16384", who);
+  if (!stp_aligned16(a) || !stp_aligned16(b) || !stp_aligned16(c)) return stp_fail(ctx, STP_EALIGN, "%s: pointers must be 16-byte aligned", who);
+  return STP_OK;
+}
+
+#define SOFTMAX_BY_NCH(KERN, T, ...)                                                              \
+  do {                                                                                            \
+    const int nch = (n + 2047) / 2048;                                                            \
+    if (nch <= 1) hipLaunchKernelGGL((KERN<T, 1>), dim3(rows), dim3(256), 0, s, __VA_ARGS__);     \
+    else if (nch <= 2) hipLaunchKernelGGL((KERN<T, 2>), dim3(rows), dim3(256), 0, s, __VA_ARGS__); \
+    else if (nch <= 4) hipLaunchKernelGGL((KERN<T, 4>), dim3(rows), dim3(256), 0, s, __VA_ARGS__); \
+    else hipLaunchKernelGGL((KERN<T, 8>), dim3(rows), dim3(256), 0, s, __VA_ARGS__);              \
+  } while (0)
+
+extern "C" int stp_softmax_forward(stp_ctx *ctx, int dtype, int32_t rows, int32_t n, float scale, int causal, const void *x,
+                                   void *y, void *hip_stream) {
+  if (!ctx) return STP_EINVAL;
+  int rc = softmax_args_ok(ctx, "stp_softmax_forward", dtype, rows, n, x, y, y);
+  if (rc != STP_OK) return rc;
+  if (rows == 0) return STP_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const float sl = scale * 1.4426950408889634f;
+  if (dtype == STP_BF16) SOFTMAX_BY_NCH(softmax_fwd_kernel, bf16_t, (const bf16_t *)x, (bf16_t *)y, rows, n, sl, causal);
+  else SOFTMAX_BY_NCH(softmax_fwd_kernel, float, (const float *)x, (float *)y, rows, n, sl, causal);
+  STP_LAUNCH_CHECK(ctx);
+  return STP_OK;
+}
+
+extern "C" int stp_softmax_backward(stp_ctx *ctx, int dtype, int32_t rows, int32_t n, float scale, const void *y, const void *dy,
+                                    void *dx, void *hip_stream) {
+  if (!ctx) return STP_EINVAL;
+  int rc = softmax_args_ok(ctx, "stp_softmax_backward", dtype, rows, n, y, dy, dx);
+  if (rc != STP_OK) return rc;
+  if (rows == 0) return STP_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (dtype == STP_BF16) SOFTMAX_BY_NCH(softmax_bwd_kernel, bf16_t, (const bf16_t *)y, (const bf16_t *)dy, (bf16_t *)dx, rows, n, scale);
+  else SOFTMAX_BY_NCH(softmax_bwd_kernel, float, (const float *)y, (const float *)dy, (float *)dx, rows, n, scale);
+  STP_LAUNCH_CHECK(ctx);
   return STP_OK;
 }

@@ -286,6 +286,32 @@ def test_colsum(ctx, dtype, T, N):
     assert rel_err(to_host(out), 2.0 + 0.125 * x.astype(np.float64).sum(0)) < 1e-5
 
 
+# ------------------------------------------------------------------ stand-alone row softmax
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("rows,n,causal", [(37, 8, False), (64, 1000, False), (130, 2056, False), (24, 4104, False),
+                                           (9, 16384, False), (80, 40, True), (300, 1000, True), (4096, 2048, True)])
+def test_softmax_forward_backward(ctx, dtype, rows, n, causal):
+    rng = np.random.default_rng(rows + n)
+    x = q(rng.standard_normal((rows, n), dtype=np.float32) * 3, dtype)
+    dy = q(rng.standard_normal((rows, n), dtype=np.float32), dtype)
+    xd, dyd = to_dev(x, dtype), to_dev(dy, dtype)
+    y, dx = torch.empty_like(xd), torch.empty_like(xd)
+    code = stp.BF16 if dtype == "bf16" else stp.F32
+    scale = 0.35
+    ctx.softmax_forward(code, rows, n, scale, causal, xd, y)
+    ctx.softmax_backward(code, rows, n, scale, y, dyd, dx)
+    torch.cuda.synchronize()
+    ref = O.softmax_fwd(x.astype(np.float64), scale, causal)
+    tol = 8e-3 if dtype == "bf16" else 2e-6
+    assert rel_err(to_host(y), ref) < tol
+    if causal:      # masked keys get exactly zero
+        r = np.arange(rows)[:, None] % n
+        assert np.all(to_host(y)[np.arange(n)[None, :] > r] == 0.0)
+    # the backward kernel is fed the device's own (rounded) y, and so is the oracle
+    refdx = O.softmax_bwd(to_host(y), dy.astype(np.float64), scale)
+    assert rel_err(to_host(dx), refdx) < tol
+
+
 # ------------------------------------------------------------------ attention core
 # (dtype, seq, mbsz, query heads, head dim, causal, key / value heads; 0 = one per query head)
 ATTN_CASES = [("f32", 128, 1, 4, 64, True, 0), ("f32", 52, 2, 2, 32, False, 0), ("f32", 72, 1, 1, 128, True, 0),
