@@ -357,6 +357,9 @@ def main():
                     help="what --offload-alpha moves: the W-stashes of microbatches whose weight gradients are "
                          "deferred (long-lived), the forward stashes (short-lived in a one-stage sequence), or both")
     ap.add_argument("--print-gemm", action="store_true", help="with --only-gemm: print the leg's result as JSON")
+    ap.add_argument("--only-step", action="store_true",
+                    help="run only the braided steps (warm-up + timed region) and print their time: under "
+                         "rocprofv3 --kernel-trace --stats every kernel average is then a per-step figure")
     ap.add_argument("--only-gemm", action="store_true",
                     help="run only the dominant-kernel leg plus a 1 GiB device copy (counter calibration runs)")
     args = ap.parse_args()
@@ -414,6 +417,13 @@ def main():
 
     # ---- the timed region: K braided steps ------------------------------------------
     ms_braided = time_steps(lambda: ctx.braid_step(stg.stage, arr, sF, sB, sW), args.steps, args.warmup, torch)
+
+    if args.only_step:
+        print(json.dumps({"ms_per_step": ms_braided, "tflops": total_flops / (ms_braided * 1e-3) / 1e12,
+                          "steps": args.steps, "warmup": args.warmup, "workload": wl.name}))
+        torch.cuda.synchronize()
+        ctx.close()
+        return
 
     # ---- sustained shader clock while braided steps run (probe wave on a side stream) -------------
     probe_out = torch.zeros(2, dtype=torch.int64, device="cuda")
