@@ -7,6 +7,10 @@ same layer, on three HIP streams.  One step therefore performs exactly the F + B
 one layer-microbatch.  Headline workload: GPT-7B-style layer, TP=8 shard (hidden 4096, 4 of 32
 heads x 128, FFN shard 2048), sequence 6144, microbatch 1, bf16 storage with fp32 accumulation.
 
+The defaults time 200 steps after 20 warm-up steps: after an idle period the chip needs some tens of
+milliseconds to reach its steady clocks (30 timed steps read 4 % slower than 200 or 1000, which agree), and a
+training loop runs in the steady state.  The single-kernel legs repeat their launches as often for the same reason.
+
 Prints one JSON line (see the repository's design notes for the field definitions).
 """
 from __future__ import annotations
@@ -81,40 +85,92 @@ def event_steps(ctx, stage, arr, streams, steps, torch):
     return [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
 
 
-def gemm_leg(ctx, wl, reps, torch, stp):
+GEMM_SHAPE_OVERRIDE = None     # --gemm-shape M,N,K: one shape instead of the workload's four (with --only-gemm)
+
+
+def gemm_shapes(wl):
+    if GEMM_SHAPE_OVERRIDE:
+        return [GEMM_SHAPE_OVERRIDE]
+    return [(wl.seq, wl.qkv_local, wl.hidden), (wl.seq, wl.hidden, wl.attn_local),
+            (wl.seq, wl.ffn_local, wl.hidden), (wl.seq, wl.hidden, wl.ffn_local)]
+
+
+def gemm_operands(shape, td, operands, torch):
+    """A [M, K] and B [K, N]: N(0,1) activations against N(0, 0.02) weights, or all zeros.  The MFMA rate this
+    chip sustains depends on the operand bits (power management slows the shader clock when the multipliers toggle
+    on every bit), so a figure must say which data it ran on: the zeros leg shows what the same instruction stream
+    reaches when power does not limit it."""
+    M, N, K = shape
+    if operands == "zeros":
+        return torch.zeros((M, K), device="cuda", dtype=td), torch.zeros((K, N), device="cuda", dtype=td)
+    return torch.randn((M, K), device="cuda").to(td), (torch.randn((K, N), device="cuda") * 0.02).to(td)
+
+
+def gemm_leg(ctx, wl, reps, torch, stp, operands="random", library=False, per_shape=False):
     """Dominant kernel: the bf16 MFMA GEMM in its forward layout (A row-major, B = W[in,out]).  Its four
     launches per step (QKV, out-proj, FC1, FC2 shapes of the workload) are replayed alone on the current
     stream between HIP events recorded on that same stream.  Returns (average ms per launch, average
-    algorithmic flops per launch)."""
-    T, h, a, f = wl.seq, wl.hidden, wl.attn_local, wl.ffn_local
+    algorithmic flops per launch), or the per-shape times in ms with `per_shape`.  With `library` the same
+    shapes and operands go through torch.matmul (the vendor GEMM library) instead: a point of comparison that is
+    reported beside the kernel's figure, never part of the path."""
     td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     code = stp.BF16 if wl.dtype == "bf16" else stp.F32
-    shapes = [(T, wl.qkv_local, h), (T, h, a), (T, f, h), (T, h, f)]
-    bufs = []
+    shapes = gemm_shapes(wl)
+    runs = []
     for (M, N, K) in shapes:
-        A = torch.randn((M, K), device="cuda").to(td)
-        Bm = (torch.randn((K, N), device="cuda") * 0.02).to(td)
+        A, Bm = gemm_operands((M, N, K), td, operands, torch)
         Cm = torch.empty((M, N), device="cuda", dtype=td)
-        bufs.append((stp.GemmArgs(dtype=code, M=M, N=N, K=K, A=A.data_ptr(), lda=K, B=Bm.data_ptr(), ldb=N,
-                                  C=Cm.data_ptr(), ldc=N, bias_scale=1.0, resid_scale=1.0), A, Bm, Cm))
-    for g, *_ in bufs:
-        ctx.gemm(g)
+        if library:
+            runs.append((lambda A=A, Bm=Bm, Cm=Cm: torch.matmul(A, Bm, out=Cm)))
+        else:
+            g = stp.GemmArgs(dtype=code, M=M, N=N, K=K, A=A.data_ptr(), lda=K, B=Bm.data_ptr(), ldb=N,
+                             C=Cm.data_ptr(), ldc=N, bias_scale=1.0, resid_scale=1.0)
+            runs.append((lambda g=g, keep=(A, Bm, Cm): ctx.gemm(g)))
+    for _ in range(3 if library else 1):
+        for run in runs:
+            run()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if per_shape:
+        out = []
+        for run in runs:
+            e0.record()
+            for _ in range(reps):
+                run()
+            e1.record()
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) / reps)
+        return out
     e0.record()
     for _ in range(reps):
-        for g, *_ in bufs:
-            ctx.gemm(g)
+        for run in runs:
+            run()
     e1.record()
     torch.cuda.synchronize()
-    avg_ms = e0.elapsed_time(e1) / (reps * len(bufs))
+    avg_ms = e0.elapsed_time(e1) / (reps * len(runs))
     return avg_ms, sum(2 * M * N * K for (M, N, K) in shapes) / len(shapes)
+
+
+def gemm_context(ctx, wl, reps, torch, stp):
+    """What frames the dominant kernel's figure: the same four launches on all-zero operands, and the vendor
+    library's GEMM on both kinds of operands."""
+    out = {"operands_of_achieved": "A ~ N(0,1), B ~ N(0,0.02), bf16"}
+    for operands in ("zeros", "random"):
+        for library in (False, True):
+            if operands == "random" and not library:
+                continue
+            ms, fl = gemm_leg(ctx, wl, reps, torch, stp, operands=operands, library=library)
+            key = ("library_" if library else "this_kernel_") + operands
+            out[key] = {"avg_launch_ms": ms, "achieved": fl / (ms * 1e-3) / 1e12,
+                        "frac": fl / (ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
+    out["library"] = "torch.matmul(out=) on the same shapes, bf16 (the vendor GEMM library; comparison only)"
+    return out
 
 
 HBM_PEAK_GBS = 8000.0
 
 
-def hbm_leg(ctx, wl, torch, stp):
+def hbm_leg(ctx, wl, torch, stp, reps=200):
     """The HBM-bound kernels of the units at the workload's sizes, alone on the current stream: achieved
     GB/s = algorithmic bytes (each tensor read or written once) / HIP-event time.  At these sizes (25-200 MB)
     part of the traffic is served by the 256 MB last-level cache, so a figure can exceed what HBM alone gives."""
@@ -154,16 +210,15 @@ def hbm_leg(ctx, wl, torch, stp):
     big_dst = torch.empty_like(big_src)
     out = {}
     for name, nbytes, fn in legs:
-        for _ in range(3):
+        for _ in range(20):
             fn()
-        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for _ in range(30):
+        for _ in range(reps):
             fn()
         e1.record()
         torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 30
+        ms = e0.elapsed_time(e1) / reps
         gbs = nbytes / ms / 1e6
         out[name] = {"us": ms * 1e3, "GB/s": gbs, "frac_of_8TBs": gbs / HBM_PEAK_GBS, "bytes": nbytes}
     return out
@@ -267,7 +322,7 @@ def stage_bench(ctx, args, torch, stp, synth):
         for arr in steps:
             ctx.braid_step(stg.stage, arr, *streams)
 
-    reps = max(3, args.steps // 6)
+    reps = max(3, min(10, args.steps // 6))
     ms_braided = time_steps(lambda: run((sF, sB, sW)), reps, 1, torch)
     ms_serial = time_steps(lambda: run((s0, s0, s0)), reps, 1, torch)
     # isolated units, per layer kind: F, B, W of one layer-microbatch alone on one stream
@@ -329,8 +384,8 @@ def stage_bench(ctx, args, torch, stp, synth):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="gpt7b_tp8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage", choices=["pp4", "mllm"], default=None,
@@ -356,7 +411,13 @@ def main():
     ap.add_argument("--offload-sets", choices=["w", "fwd", "both"], default="w",
                     help="what --offload-alpha moves: the W-stashes of microbatches whose weight gradients are "
                          "deferred (long-lived), the forward stashes (short-lived in a one-stage sequence), or both")
-    ap.add_argument("--print-gemm", action="store_true", help="with --only-gemm: print the leg's result as JSON")
+    ap.add_argument("--print-gemm", action="store_true",
+                    help="with --only-gemm: print the leg's result as JSON, with per-shape times of this kernel and of the "
+                         "vendor library on random and on zero operands")
+    ap.add_argument("--gemm-shape", default=None, metavar="M,N,K",
+                    help="with --only-gemm: time this one shape (forward layout) instead of the workload's four")
+    ap.add_argument("--gemm-operands", choices=["random", "zeros"], default="random",
+                    help="with --only-gemm: operand data of the replayed launches")
     ap.add_argument("--only-step", action="store_true",
                     help="run only the braided steps (warm-up + timed region) and print their time: under "
                          "rocprofv3 --kernel-trace --stats every kernel average is then a per-step figure")
@@ -388,10 +449,19 @@ def main():
     total_flops = fl["F"] + fl["B"] + fl["W"]
 
     ctx = stp.Context(0)
+    if args.gemm_shape:
+        global GEMM_SHAPE_OVERRIDE
+        GEMM_SHAPE_OVERRIDE = tuple(int(v) for v in args.gemm_shape.split(","))
     if args.only_gemm:
-        ms, fl = gemm_leg(ctx, wl, max(10, args.steps), torch, stp)
+        ms, fl = gemm_leg(ctx, wl, max(10, args.steps), torch, stp, operands=args.gemm_operands)
         if args.print_gemm:
-            print(json.dumps({"avg_launch_ms": ms, "flops_per_launch": fl, "tflops": fl / (ms * 1e-3) / 1e12}))
+            line = {"avg_launch_ms": ms, "flops_per_launch": fl, "tflops": fl / (ms * 1e-3) / 1e12,
+                    "operands": args.gemm_operands, "shapes_MNK": gemm_shapes(wl), "per_shape_ms": {}}
+            for operands in ("random", "zeros"):
+                for library in (False, True):
+                    line["per_shape_ms"][("library_" if library else "this_kernel_") + operands] = gemm_leg(
+                        ctx, wl, 20, torch, stp, operands=operands, library=library, per_shape=True)
+            print(json.dumps(line))
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         for _ in range(5):
@@ -475,6 +545,9 @@ def main():
                    "flops_per_step": total_flops},
         "mfma_util_frac_of_bf16_peak": total_flops / (ms_braided * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
         "sustained_shader_clock_mhz": sustained_mhz,
+        "sustained_shader_clock_source": "stp_clock_probe: one wave of one compute unit counting shader cycles for a 12 ms window while braided "
+                                         "steps run; rocm-smi's chip-wide average over seconds is lower (about 1.95 GHz under this load: "
+                                         "profiles/gemm_operand_data_and_clock.txt)",
         "mfma_util_frac_at_sustained_clock": (total_flops / (ms_braided * 1e-3) / 1e12 /
                                               (n_cu * 4096 * sustained_mhz * 1e6 / 1e12)) if sustained_mhz else None,
         "compute_units": n_cu,
@@ -491,8 +564,8 @@ def main():
                      "flops_per_launch": gemm_flops_per_launch,
                      "traffic": GEMM_FWD_TRAFFIC_BYTES if args.workload == "gpt7b_tp8" else None,
                      "traffic_source": GEMM_FWD_TRAFFIC_SOURCE if args.workload == "gpt7b_tp8" else None,
-                     "algorithmic_bytes_per_launch": sum(2 * (M * K + K * N + M * N) for (M, N, K) in
-                                                         [(T, wl.qkv_local, h), (T, h, a), (T, f, h), (T, h, f)]) / 4},
+                     "algorithmic_bytes_per_launch": sum(2 * (M * K + K * N + M * N) for (M, N, K) in gemm_shapes(wl)) / 4,
+                     "context": gemm_context(ctx, wl, max(10, args.steps), torch, stp)},
         "hbm_kernels": hbm,
     }
 

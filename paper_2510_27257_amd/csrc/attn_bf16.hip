@@ -102,9 +102,16 @@ __device__ __forceinline__ void mfma_pv(f32x16_t (&o)[D / 32], const u32x4_t (&b
 template <int D>
 __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__restrict__ qkv, float *__restrict__ part, int seq,
                                                             int n, int nk, int causal, int max_chunks, int chunk_steps, float scale_log2,
-                                                            int n_items, stp_attn_order ord) {
+                                                            int n_items, stp_attn_order ord
+#ifdef STP_ATTN_TRACE
+                                                            , long long *trace
+#endif
+                                                            ) {
   using G = AttnGeom<D>;
   static_assert(D == 64 || D == 128, "head dimension");
+#ifdef STP_ATTN_TRACE
+  const long long tr0 = wall_clock64();
+#endif
   constexpr int RB = G::RB, CPR = G::CPR, RPB = G::RPB, RPI = G::RPI, NLD = G::NLD, TILE = G::TILE;
   constexpr int KREADS = 4, VREADS = 2 * (D / 32);   // LDS operations of one fragment group
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];   // K ring [2][TILE], V ring [2][TILE]
@@ -339,6 +346,9 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
   } else {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NLD) : "memory");
   }
+#ifdef STP_ATTN_TRACE
+  const long long tr1 = wall_clock64();
+#endif
   for (int k = -1; k < ns; k++) {
     const bool do_qk = k + 1 < ns && (k + 1 < ns - 1 || last_active), do_pv = k >= 0 && (k < ns - 1 || last_active);
     const bool ld_k = k >= 0 && k + 2 < ns, ld_v = k >= 0 && k + 1 < ns;
@@ -361,6 +371,9 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
   }
 #undef STP_SB
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#ifdef STP_ATTN_TRACE
+  const long long tr2 = wall_clock64();
+#endif
 
   // ---- merge the two key halves (upper half -> LDS -> lower half), then write this chunk's partial:
   // O (un-normalised, relative to m), m (log2 domain), l.
@@ -399,6 +412,20 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
       if (lg == 0) { po[QB * D + qloc] = M; po[QB * D + QB + qloc] = l; }
     }
   }
+#ifdef STP_ATTN_TRACE
+  if (trace) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const long long tr3 = wall_clock64();
+    if (tid == 0) {
+      unsigned hw, xcc;
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+      long long *t = trace + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8;
+      t[0] = tr0; t[1] = tr1; t[2] = tr2; t[3] = tr3; t[4] = hw; t[5] = xcc; t[6] = ns; t[7] = 1;
+    }
+  }
+#endif
 }
 
 // out[q, :] = sum_c O_c e^{m_c - M} / sum_c l_c e^{m_c - M}; lse = (M + log2 L) ln 2.  One wave per (token, head).
@@ -474,7 +501,11 @@ int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out
   const dim3 block(512);
   float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
   hipLaunchKernelGGL(kern, grid, block, smem, s, (const bf16_t *)qkv, ws, d->seq, d->heads_local, stp_kv_heads(d), d->causal, max_chunks, chunk_steps,
-                     scale_log2, plan->n_items, plan->order);
+                     scale_log2, plan->n_items, plan->order
+#ifdef STP_ATTN_TRACE
+                     , getenv("STP_TRACE_PTR") ? (long long *)strtoull(getenv("STP_TRACE_PTR"), nullptr, 0) : (long long *)nullptr
+#endif
+                     );
   STP_LAUNCH_CHECK(ctx);
   size_t waves = (size_t)d->mbsz * d->heads_local * d->seq;
   hipLaunchKernelGGL(attn_fwd_combine_kernel<D>, dim3((waves + 3) / 4), dim3(256), 0, s, ws, (bf16_t *)out, lse, d->seq,
