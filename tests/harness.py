@@ -32,6 +32,25 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.max(np.abs(np.asarray(got, np.float64) - ref))) / (den if den > 0 else 1.0)
 
 
+# half a unit in the last place of a stored value, relative to the value (24 / 8 significant bits): the one
+# rounding of the sum branch + residual
+STORE_ULP = {"f32": 2.0 ** -24, "bf16": 2.0 ** -8}
+
+
+def branch_err(got, got_resid, ref, ref_resid, coeff: float, dtype: str) -> float:
+    """Parity of the computed branch of a residual-carrying output (Eq. 1: out = branch + X/t; Eq. 2:
+    dX = norm_bwd(..) + dY), which max|got - ref| / max|ref| dilutes when the residual dominates the output.
+    Each side has its own residual input subtracted (the path's is the value it stored, already rounded; the
+    oracle's is its own), so what is compared is what the unit computed.  The bound is the parity tolerance
+    relative to max|branch| plus the one rounding of the stored sum, half a unit in the last place of max|out|.
+    Returns error / bound: below 1 passes."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    b_got = got - coeff * np.asarray(got_resid, np.float64).reshape(got.shape)
+    b_ref = ref - coeff * np.asarray(ref_resid, np.float64).reshape(ref.shape)
+    bound = TOL[dtype] * float(np.max(np.abs(b_ref))) + STORE_ULP[dtype] * float(np.max(np.abs(ref)))
+    return float(np.max(np.abs(b_got - b_ref))) / (bound if bound > 0 else 1.0)
+
+
 def oracle_cfg(wl: synth.Workload) -> O.LayerCfg:
     return O.LayerCfg(hidden=wl.hidden, heads_local=wl.heads_local, head_dim=wl.head_dim, ffn_local=wl.ffn_local,
                       tp=wl.tp, norm=wl.norm, act=wl.act, causal=wl.causal, rope=wl.rope, has_bias=wl.has_bias,

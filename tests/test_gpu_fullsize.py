@@ -12,7 +12,7 @@ from paper_2510_27257_amd import synth
 from paper_2510_27257_amd.binding import OP_BW
 from paper_2510_27257_amd.stage import StageOnDevice, backward_ops, braid, forward_ops
 from oracle import stp_oracle as O
-from harness import TOL, oracle_cfg, oracle_layer_pass, rel_err, to_host
+from harness import TOL, branch_err, oracle_cfg, oracle_layer_pass, rel_err, to_host
 
 
 # the benchmark configurations, then the shards of the two language models of the model table of Section 5.1 at
@@ -45,6 +45,13 @@ def test_full_size_braided_block_matches_oracle(name):
             "dqkv.mb0": rel_err(to_host(stg.field(0, 0, "DQKV")).reshape(st["dqkv"].shape), st["dqkv"])}
     for k, r in g.items():
         errs["grad." + k] = rel_err(to_host(stg.g_dev[0][k]), r)
+    # the residual-carrying outputs of Eq. 1 / Eq. 2 with the residual taken off (error / bound, below 1 passes)
+    xa_gpu = to_host(stg.field(0, 0, "X_ATTN")).reshape(ref["x_attn"].shape)
+    dxa_gpu = to_host(stg.field(0, 0, "DX_ATTN")).reshape(ref["dx_attn"].shape)
+    branch = {"x_attn.mb0": branch_err(xa_gpu, X0, ref["x_attn"], X0, 1.0 / wl.tp, wl.dtype),
+              "x_out.mb0": branch_err(to_host(stg.act_slot(1, 0)), xa_gpu, ref["x_out"], ref["x_attn"], 1.0 / wl.tp, wl.dtype),
+              "dx_attn.mb0": branch_err(dxa_gpu, dO, ref["dx_attn"], dO, 1.0, wl.dtype),
+              "dx.mb0": branch_err(to_host(stg.grad_slot(0, 0)), dxa_gpu, ref["dx"], ref["dx_attn"], 1.0, wl.dtype)}
     del ref, st, g
     # the forward half of the block (microbatch 1)
     X1 = synth.make_activation(wl, 0, "x.mb1").astype(np.float64)
@@ -56,5 +63,8 @@ def test_full_size_braided_block_matches_oracle(name):
     errs["x_out.mb1"] = rel_err(to_host(stg.act_slot(1, 1)), out1)
     ctx.close()
     print(f"[{name}] {errs}", flush=True)
+    print(f"[{name}] computed branches, error / bound: {branch}", flush=True)
     bad = {k: v for k, v in errs.items() if not v < tol}
     assert not bad, f"{name}: over tolerance {tol}: {bad}"
+    bad = {k: v for k, v in branch.items() if not v < 1.0}
+    assert not bad, f"{name}: computed branch over its bound: {bad}"

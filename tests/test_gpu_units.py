@@ -9,7 +9,7 @@ import paper_2510_27257_amd as stp
 from paper_2510_27257_amd import synth
 from paper_2510_27257_amd.synth import Workload
 from oracle import stp_oracle as O
-from harness import (LayerOnDevice, TOL, gpu_layer_pass, oracle_cfg, oracle_layer_pass, rel_err, to_dev, to_host)
+from harness import (LayerOnDevice, TOL, branch_err, gpu_layer_pass, oracle_cfg, oracle_layer_pass, rel_err, to_dev, to_host)
 
 # sizes the oracle finishes in seconds that still span several 128/256 tiles and leave ragged tails
 CASES = {
@@ -67,6 +67,15 @@ def test_units_match_oracle(ctx, name, bias_in_b):
         errs["grad." + k] = rel_err(to_host(lay.g_dev[k]), r)
     bad = {k: v for k, v in errs.items() if not v < tol}
     assert not bad, f"{name}: over tolerance {tol}: {bad}\nall: {errs}"
+    # the residual-carrying outputs once more with the residual taken off, so that an error of the computed
+    # branch is not measured against the (larger) residual
+    X64, dO64 = X.astype(np.float64), dO.astype(np.float64)
+    branch = {"x_attn": branch_err(to_host(got["x_attn"]), X64, ref["x_attn"], X64, 1.0 / wl.tp, wl.dtype),
+              "x_out": branch_err(to_host(got["x_out"]), to_host(got["x_attn"]), ref["x_out"], ref["x_attn"], 1.0 / wl.tp, wl.dtype),
+              "dx_attn": branch_err(to_host(got["dx_attn"]), dO64, ref["dx_attn"], dO64, 1.0, wl.dtype),
+              "dx": branch_err(to_host(got["dx"]), to_host(got["dx_attn"]), ref["dx"], ref["dx_attn"], 1.0, wl.dtype)}
+    bad = {k: v for k, v in branch.items() if not v < 1.0}
+    assert not bad, f"{name}: computed branch over its bound (error / bound): {bad}\nall: {branch}"
 
 
 @pytest.mark.parametrize("name", ["gpt_bf16", "gpt_fp32_tp2"])
