@@ -1,6 +1,8 @@
 """Parity at the full benchmark sizes, in the launch configuration bench.py times: one braided
 block F(mb1) | B+W(mb0) on three streams, every output tensor compared with the fp64 oracle
 element by element (the numpy oracle finishes a full-size layer-microbatch in seconds)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -13,6 +15,20 @@ from paper_2510_27257_amd.binding import OP_BW
 from paper_2510_27257_amd.stage import StageOnDevice, backward_ops, braid, forward_ops
 from oracle import stp_oracle as O
 from harness import TOL, branch_err, oracle_cfg, oracle_layer_pass, rel_err, to_host
+
+
+OBSERVED = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "fullsize_bf16_observed_errors.txt")
+
+
+def observed_errors(name):
+    """Per-tensor errors this block showed when the table was written (a drift alarm beside the tolerance)."""
+    out = {}
+    if os.path.exists(OBSERVED):
+        for line in open(OBSERVED):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == name:
+                out[parts[1]] = float(parts[2])
+    return out
 
 
 # the benchmark configurations, then the shards of the two language models of the model table of Section 5.1 at
@@ -68,3 +84,12 @@ def test_full_size_braided_block_matches_oracle(name):
     assert not bad, f"{name}: over tolerance {tol}: {bad}"
     bad = {k: v for k, v in branch.items() if not v < 1.0}
     assert not bad, f"{name}: computed branch over its bound: {bad}"
+    record = os.environ.get("STP_RECORD_ERRORS")
+    if record:
+        with open(record, "a") as f:
+            for k, v in errs.items():
+                f.write(f"{name} {k} {v:.4e}\n")
+        return
+    seen = observed_errors(name)
+    drift = {k: (v, seen[k]) for k, v in errs.items() if k in seen and not v < 1.5 * seen[k] + 1e-6}
+    assert not drift, f"{name}: error (now, when the table was written) grew by more than half: {drift}"
