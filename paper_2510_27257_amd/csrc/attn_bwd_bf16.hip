@@ -542,11 +542,29 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16_t *__res
                                                              const float *__restrict__ lse, const float *__restrict__ delta,
                                                              float *__restrict__ part_kv, float *__restrict__ part_q, int seq, int n,
                                                              int nk, int causal, int mc_kv, int ch_kv, int mc_q, int ch_q, float scale,
-                                                             stp_attn_order ord) {
+                                                             stp_attn_order ord
+#ifdef STP_ATTN_TRACE
+                                                             , long long *trace
+#endif
+                                                             ) {
+#ifdef STP_ATTN_TRACE
+  const long long tr0 = wall_clock64();
+#endif
   const int item = ord.item[blockIdx.y];
   const int block = item & 0xfff, chunk = (item >> 12) & 7, bz = blockIdx.x;
   if (item & 0x8000) dq_body<D>(qkv, dout, lse, delta, part_q, seq, n, nk, causal, mc_q, ch_q, scale, block, chunk, bz);
   else dkv_body<D>(qkv, dout, lse, delta, part_kv, seq, n, nk, causal, mc_kv, ch_kv, scale, block, chunk, bz);
+#ifdef STP_ATTN_TRACE
+  if (trace) {   // per-workgroup life time: start, end, work item
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const long long tr3 = wall_clock64();
+    if (threadIdx.x == 0) {
+      long long *t = trace + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 4;
+      t[0] = tr0; t[1] = tr3; t[2] = item; t[3] = 1;
+    }
+  }
+#endif
 }
 
 template <int D>
@@ -657,7 +675,11 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
   if (fused) {
     const stp_attn_plan *pf = fused_plan(ctx, d, pkv, pq);
     hipLaunchKernelGGL(kf, dim3((unsigned)bh, pf->n_items), dim3(512), smem_f, s, (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta,
-                       ws_kv, ws_q, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv, mc_q, ch_q, scale, pf->order);
+                       ws_kv, ws_q, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv, mc_q, ch_q, scale, pf->order
+#ifdef STP_ATTN_TRACE
+                       , getenv("STP_TRACE_PTR") ? (long long *)strtoull(getenv("STP_TRACE_PTR"), nullptr, 0) : (long long *)nullptr
+#endif
+                       );
     STP_LAUNCH_CHECK(ctx);
   } else {
     hipLaunchKernelGGL(kkv, pkv.n_items ? dim3((unsigned)bk, pkv.n_items) : dim3(nkvb, mc_kv, (unsigned)bk), dim3(512), smem_kv, s,
