@@ -100,7 +100,8 @@ __device__ __forceinline__ void mfma_pv(f32x16_t (&o)[D / 32], const u32x4_t (&b
 }
 
 template <int D>
-__global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__restrict__ qkv, float *__restrict__ part, int seq,
+__global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__restrict__ qkv, float *__restrict__ part,
+                                                            bf16_t *__restrict__ out, float *__restrict__ lse_out, int seq,
                                                             int n, int nk, int causal, int max_chunks, int chunk_steps, float scale_log2,
                                                             int n_items, stp_attn_order ord
 #ifdef STP_ATTN_TRACE
@@ -393,7 +394,26 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
     const float m_ref = M == -INFINITY ? 0.f : M;
     const float ea = __builtin_amdgcn_exp2f(m - m_ref), eb = __builtin_amdgcn_exp2f(m_b - m_ref);
     l = l * ea + l_b * eb;
-    if (qg < seq) {
+    if (qg < seq && nsteps <= chunk_steps) {
+      // the query block has this one chunk: its rows are final, so they go to the output (and the log-sum-exp)
+      // directly and the combine kernel leaves them alone
+      const float inv = 1.0f / l;
+      bf16_t *op = out + ((size_t)b * seq + qg) * a + head * D;
+      typedef bf16_t bf16x4_t __attribute__((ext_vector_type(4)));
+#pragma unroll
+      for (int i = 0; i < D / 32; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          bf16x4_t w;
+#pragma unroll
+          for (int r = 0; r < 4; r++) {
+            const int v = 4 * j + r;
+            w[r] = (bf16_t)((o[i][v] * ea + red[(qsub * (D / 2) + i * 16 + v) * 64 + lane] * eb) * inv);
+          }
+          *reinterpret_cast<bf16x4_t *>(op + 32 * i + 8 * j + 4 * lg) = w;
+        }
+      if (lg == 0) lse_out[((size_t)b * n + head) * seq + qg] = (M + log2f(l)) * LN2;
+    } else if (qg < seq) {
       const size_t piece = (((size_t)b * n + head) * nqb + qb) * max_chunks + chunk;
       float *po = part + piece * G::piece_floats;
       const int qloc = qsub * 32 + lr;
@@ -432,14 +452,16 @@ __global__ __launch_bounds__(512) void attn_fwd_bf16_kernel(const bf16_t *__rest
 template <int D>
 __global__ __launch_bounds__(256) void attn_fwd_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ out,
                                                                float *__restrict__ lse, int seq, int n, int mbsz, int causal,
-                                                               int max_chunks, int chunk_steps) {
+                                                               int max_chunks, int chunk_steps, int q_first) {
   using G = AttnGeom<D>;
   const int lane = threadIdx.x & 63;
   const size_t w = blockIdx.x * (size_t)4 + (threadIdx.x >> 6);
-  if (w >= (size_t)mbsz * n * seq) return;
-  const int q = w % seq, head = (w / seq) % n, b = w / ((size_t)seq * n);
+  const int rows = seq - q_first;             // rows below q_first belong to one-chunk blocks, which the main kernel finished
+  if (w >= (size_t)mbsz * n * rows) return;
+  const int q = q_first + w % rows, head = (w / rows) % n, b = w / ((size_t)rows * n);
   const int nqb = (seq + QB - 1) / QB, qb = q / QB, qloc = q % QB;
   const int nch = (attn_steps(qb, seq, causal) + chunk_steps - 1) / chunk_steps;
+  if (nch <= 1) return;
   const float *p0 = part + ((((size_t)b * n + head) * nqb + qb) * max_chunks) * G::piece_floats;
   float M = -INFINITY;
   for (int c = 0; c < nch; c++) M = fmaxf(M, p0[(size_t)c * G::piece_floats + QB * D + qloc]);
@@ -500,17 +522,23 @@ int launch_fwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, void *out
   const dim3 grid = plan->n_items ? dim3(d->heads_local * d->mbsz, plan->n_items) : dim3(nqb, max_chunks, d->heads_local * d->mbsz);
   const dim3 block(512);
   float scale_log2 = 1.4426950408889634f / sqrtf((float)D);
-  hipLaunchKernelGGL(kern, grid, block, smem, s, (const bf16_t *)qkv, ws, d->seq, d->heads_local, stp_kv_heads(d), d->causal, max_chunks, chunk_steps,
+  hipLaunchKernelGGL(kern, grid, block, smem, s, (const bf16_t *)qkv, ws, (bf16_t *)out, lse, d->seq, d->heads_local, stp_kv_heads(d), d->causal, max_chunks, chunk_steps,
                      scale_log2, plan->n_items, plan->order
 #ifdef STP_ATTN_TRACE
                      , getenv("STP_TRACE_PTR") ? (long long *)strtoull(getenv("STP_TRACE_PTR"), nullptr, 0) : (long long *)nullptr
 #endif
                      );
   STP_LAUNCH_CHECK(ctx);
-  size_t waves = (size_t)d->mbsz * d->heads_local * d->seq;
-  hipLaunchKernelGGL(attn_fwd_combine_kernel<D>, dim3((waves + 3) / 4), dim3(256), 0, s, ws, (bf16_t *)out, lse, d->seq,
-                     d->heads_local, d->mbsz, d->causal, max_chunks, chunk_steps);
-  STP_LAUNCH_CHECK(ctx);
+  // query blocks with a single chunk were finished by the main kernel; with the causal mask they are the first ones
+  int qb_first = 0;
+  while (qb_first < nqb && attn_steps(qb_first, d->seq, d->causal) <= chunk_steps) qb_first++;
+  if (qb_first < nqb) {
+    const int q_first = qb_first * QB;
+    size_t waves = (size_t)d->mbsz * d->heads_local * (d->seq - q_first);
+    hipLaunchKernelGGL(attn_fwd_combine_kernel<D>, dim3((waves + 3) / 4), dim3(256), 0, s, ws, (bf16_t *)out, lse, d->seq,
+                       d->heads_local, d->mbsz, d->causal, max_chunks, chunk_steps, q_first);
+    STP_LAUNCH_CHECK(ctx);
+  }
   return STP_OK;
 }
 

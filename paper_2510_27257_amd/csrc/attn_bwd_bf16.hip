@@ -121,8 +121,8 @@ __host__ __device__ inline int dq_steps(int qb, int seq, int causal) {
 template <int D>
 __device__ __forceinline__ void dkv_body(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                          const float *__restrict__ lse, const float *__restrict__ delta,
-                                         float *__restrict__ part, int seq, int n, int nk, int causal, int max_chunks,
-                                         int chunk_steps, float scale, int kvb, int chunk, int bz) {
+                                         float *__restrict__ part, bf16_t *__restrict__ dqkv, int seq, int n, int nk, int causal,
+                                         int max_chunks, int chunk_steps, float scale, int kvb, int chunk, int bz) {
   using G = BG<D>;
   constexpr int RB = G::RB;
   constexpr int KV_TILE = KVB * RB, Q_TILE = QSTEP * RB, STAGE = 2 * Q_TILE;
@@ -290,7 +290,27 @@ __device__ __forceinline__ void dkv_body(const bf16_t *__restrict__ qkv, const b
       }
   }
   __syncthreads();
-  if (qhalf == 0 && kvg < seq) {
+  if (qhalf == 0 && kvg < seq && group * nq_k <= chunk_steps) {
+    // the key block has this one chunk: its rows are final and go to dK (scaled) and dV directly; the combine
+    // kernel leaves them alone
+    typedef bf16_t bf16x4_t __attribute__((ext_vector_type(4)));
+    bf16_t *dkp = dqkv + ((size_t)b * seq + kvg) * ((size_t)(n + 2 * nk) * D) + (n + kh) * D;
+    bf16_t *dvp = dkp + nk * D;
+#pragma unroll
+    for (int i = 0; i < D / 32; i++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        bf16x4_t wk, wv;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          const int v = 4 * j + r;
+          wk[r] = (bf16_t)((dk[i][v] + red[(ksub * D + i * 16 + v) * 64 + lane]) * scale);
+          wv[r] = (bf16_t)(dv[i][v] + red[(ksub * D + D / 2 + i * 16 + v) * 64 + lane]);
+        }
+        *reinterpret_cast<bf16x4_t *>(dkp + 32 * i + 8 * j + 4 * lg) = wk;
+        *reinterpret_cast<bf16x4_t *>(dvp + 32 * i + 8 * j + 4 * lg) = wv;
+      }
+  } else if (qhalf == 0 && kvg < seq) {
     const int nkvb = (seq + KVB - 1) / KVB;
     const size_t piece = (((size_t)b * nk + kh) * nkvb + kvb) * max_chunks + chunk;
     float *pk = part + piece * (size_t)(2 * KVB * D) + (size_t)(ksub * 32 + lr) * D;
@@ -317,29 +337,31 @@ __device__ __forceinline__ void dkv_body(const bf16_t *__restrict__ qkv, const b
 template <int D>
 __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                                            const float *__restrict__ lse, const float *__restrict__ delta,
-                                                           float *__restrict__ part, int seq, int n, int nk, int causal,
-                                                           int max_chunks, int chunk_steps, float scale, int n_items,
+                                                           float *__restrict__ part, bf16_t *__restrict__ dqkv, int seq, int n, int nk,
+                                                           int causal, int max_chunks, int chunk_steps, float scale, int n_items,
                                                            stp_attn_order ord) {
   const int item = n_items ? ord.item[blockIdx.y] : 0;
   const int kvb = n_items ? (item & 0xfff) : (int)blockIdx.x, chunk = n_items ? (item >> 12) : (int)blockIdx.y;
   const int bz = n_items ? blockIdx.x : blockIdx.z;
-  dkv_body<D>(qkv, dout, lse, delta, part, seq, n, nk, causal, max_chunks, chunk_steps, scale, kvb, chunk, bz);
+  dkv_body<D>(qkv, dout, lse, delta, part, dqkv, seq, n, nk, causal, max_chunks, chunk_steps, scale, kvb, chunk, bz);
 }
 
 // dK = scale * sum_c, dV = sum_c over the chunks of a key block (fixed order).  One thread per 8 columns of a key row.
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ dqkv,
                                                                    int seq, int n, int nk, int mbsz, int causal, int max_chunks,
-                                                                   int chunk_steps, float scale) {
+                                                                   int chunk_steps, float scale, int kv_end) {
   const size_t idx = blockIdx.x * (size_t)256 + threadIdx.x;
   constexpr int CPR = D / 8;
-  if (idx >= (size_t)mbsz * nk * seq * CPR) return;
+  // key rows from kv_end on belong to one-chunk blocks, which the main kernel finished
+  if (idx >= (size_t)mbsz * nk * kv_end * CPR) return;
   const int c8 = (idx % CPR) * 8;
   const size_t row = idx / CPR;
-  const int kv = row % seq, kh = (row / seq) % nk, b = row / ((size_t)seq * nk);
+  const int kv = row % kv_end, kh = (row / kv_end) % nk, b = row / ((size_t)kv_end * nk);
   const int kvb = kv / KVB, kloc = kv % KVB;
   const int nkvb = (seq + KVB - 1) / KVB, nq = (seq + QSTEP - 1) / QSTEP;
   const int nch = ((n / nk) * (nq - dkv_first_step(kvb, causal)) + chunk_steps - 1) / chunk_steps;
+  if (nch <= 1) return;
   const float *p0 = part + ((((size_t)b * nk + kh) * nkvb + kvb) * max_chunks) * (size_t)(2 * KVB * D) + (size_t)kloc * D + c8;
   float sk[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sv[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int c = 0; c < nch; c++) {
@@ -362,8 +384,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_combine_kernel(const float *
 template <int D>
 __device__ __forceinline__ void dq_body(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                         const float *__restrict__ lse, const float *__restrict__ delta,
-                                        float *__restrict__ part, int seq, int n, int nk, int causal, int max_chunks,
-                                        int chunk_steps, float scale, int qb, int chunk, int bz) {
+                                        float *__restrict__ part, bf16_t *__restrict__ dqkv, int seq, int n, int nk, int causal,
+                                        int max_chunks, int chunk_steps, float scale, int qb, int chunk, int bz) {
   using G = BG<D>;
   constexpr int RB = G::RB;
   constexpr int KV_TILE = KVB * RB, STAGE = 2 * KV_TILE;      // LDS: ring of two stages { K [128][D], V [128][D] }
@@ -501,7 +523,23 @@ __device__ __forceinline__ void dq_body(const bf16_t *__restrict__ qkv, const bf
       for (int v = 0; v < 16; v++) red[(qsub * (D / 2) + i * 16 + v) * 64 + lane] = dq[i][v];
   }
   __syncthreads();
-  if (half == 0 && qg < seq) {
+  if (half == 0 && qg < seq && nsteps <= chunk_steps) {
+    // the query block has this one chunk: its rows are final and go to dQ (scaled) directly
+    typedef bf16_t bf16x4_t __attribute__((ext_vector_type(4)));
+    bf16_t *dqp = dqkv + ((size_t)b * seq + qg) * ((size_t)(n + 2 * nk) * D) + head * D;
+#pragma unroll
+    for (int i = 0; i < D / 32; i++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        bf16x4_t w;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          const int v = 4 * j + r;
+          w[r] = (bf16_t)((dq[i][v] + red[(qsub * (D / 2) + i * 16 + v) * 64 + lane]) * scale);
+        }
+        *reinterpret_cast<bf16x4_t *>(dqp + 32 * i + 8 * j + 4 * lg) = w;
+      }
+  } else if (half == 0 && qg < seq) {
     const size_t piece = (((size_t)b * n + head) * nqblk + qb) * max_chunks + chunk;
     float *pq = part + piece * (size_t)(128 * D) + (size_t)(qsub * 32 + lr) * D;
 #pragma unroll
@@ -524,14 +562,15 @@ __device__ __forceinline__ void dq_body(const bf16_t *__restrict__ qkv, const bf
 template <int D>
 __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                                           const float *__restrict__ lse, const float *__restrict__ delta,
-                                                          float *__restrict__ part, int seq, int n, int nk, int causal, int max_chunks,
-                                                          int chunk_steps, float scale, int n_items, stp_attn_order ord) {
+                                                          float *__restrict__ part, bf16_t *__restrict__ dqkv, int seq, int n, int nk,
+                                                          int causal, int max_chunks, int chunk_steps, float scale, int n_items,
+                                                          stp_attn_order ord) {
   const int nqblk = (seq + 127) / 128;
   const int item = n_items ? ord.item[blockIdx.y] : 0;
   const int qb = n_items ? (item & 0xfff) : nqblk - 1 - (int)blockIdx.x;
   const int chunk = n_items ? (item >> 12) : (int)blockIdx.y;
   const int bz = n_items ? blockIdx.x : blockIdx.z;
-  dq_body<D>(qkv, dout, lse, delta, part, seq, n, nk, causal, max_chunks, chunk_steps, scale, qb, chunk, bz);
+  dq_body<D>(qkv, dout, lse, delta, part, dqkv, seq, n, nk, causal, max_chunks, chunk_steps, scale, qb, chunk, bz);
 }
 
 // Both kernels in one launch (same number of query and key / value heads): a work item is a dkv or a dq
@@ -540,7 +579,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(const bf16_t *__restri
 template <int D>
 __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ dout,
                                                              const float *__restrict__ lse, const float *__restrict__ delta,
-                                                             float *__restrict__ part_kv, float *__restrict__ part_q, int seq, int n,
+                                                             float *__restrict__ part_kv, float *__restrict__ part_q,
+                                                             bf16_t *__restrict__ dqkv, int seq, int n,
                                                              int nk, int causal, int mc_kv, int ch_kv, int mc_q, int ch_q, float scale,
                                                              stp_attn_order ord
 #ifdef STP_ATTN_TRACE
@@ -552,8 +592,8 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16_t *__res
 #endif
   const int item = ord.item[blockIdx.y];
   const int block = item & 0xfff, chunk = (item >> 12) & 7, bz = blockIdx.x;
-  if (item & 0x8000) dq_body<D>(qkv, dout, lse, delta, part_q, seq, n, nk, causal, mc_q, ch_q, scale, block, chunk, bz);
-  else dkv_body<D>(qkv, dout, lse, delta, part_kv, seq, n, nk, causal, mc_kv, ch_kv, scale, block, chunk, bz);
+  if (item & 0x8000) dq_body<D>(qkv, dout, lse, delta, part_q, dqkv, seq, n, nk, causal, mc_q, ch_q, scale, block, chunk, bz);
+  else dkv_body<D>(qkv, dout, lse, delta, part_kv, dqkv, seq, n, nk, causal, mc_kv, ch_kv, scale, block, chunk, bz);
 #ifdef STP_ATTN_TRACE
   if (trace) {   // per-workgroup life time: start, end, work item
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -570,16 +610,18 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_kernel(const bf16_t *__res
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dq_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ dqkv,
                                                                   int seq, int n, int nk, int mbsz, int causal, int max_chunks,
-                                                                  int chunk_steps, float scale) {
+                                                                  int chunk_steps, float scale, int q_first) {
   const size_t idx = blockIdx.x * (size_t)256 + threadIdx.x;
   constexpr int CPR = D / 8;
-  if (idx >= (size_t)mbsz * n * seq * CPR) return;
+  const int rows = seq - q_first;           // query rows below q_first belong to one-chunk blocks, which the main kernel finished
+  if (idx >= (size_t)mbsz * n * rows * CPR) return;
   const int c8 = (idx % CPR) * 8;
   const size_t row = idx / CPR;
-  const int q = row % seq, head = (row / seq) % n, b = row / ((size_t)seq * n);
+  const int q = q_first + row % rows, head = (row / rows) % n, b = row / ((size_t)rows * n);
   const int qb = q / 128, qloc = q % 128;
   const int nqblk = (seq + 127) / 128;
   const int nch = (dq_steps(qb, seq, causal) + chunk_steps - 1) / chunk_steps;
+  if (nch <= 1) return;
   const float *p0 = part + ((((size_t)b * n + head) * nqblk + qb) * max_chunks) * (size_t)(128 * D) + (size_t)qloc * D + c8;
   float sq[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int c = 0; c < nch; c++) {
@@ -670,12 +712,11 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
   if (!ws || ws_bytes < need)
     return stp_fail(ctx, STP_ENOSPACE, "attention backward: workspace lane too small%s (need %ld bytes)", "", (long)need);
   float *ws_kv = ws, *ws_q = ws + need_kv / sizeof(float);
-  const size_t rows8 = bh * d->seq * (D / 8), rows8_kv = bk * d->seq * (D / 8);
   const bool fused = bk == bh && pkv.n_items && pq.n_items && pkv.n_items + pq.n_items <= STP_ATTN_ORDER_CAP;
   if (fused) {
     const stp_attn_plan *pf = fused_plan(ctx, d, pkv, pq);
     hipLaunchKernelGGL(kf, dim3((unsigned)bh, pf->n_items), dim3(512), smem_f, s, (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta,
-                       ws_kv, ws_q, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv, mc_q, ch_q, scale, pf->order
+                       ws_kv, ws_q, (bf16_t *)dqkv, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv, mc_q, ch_q, scale, pf->order
 #ifdef STP_ATTN_TRACE
                        , getenv("STP_TRACE_PTR") ? (long long *)strtoull(getenv("STP_TRACE_PTR"), nullptr, 0) : (long long *)nullptr
 #endif
@@ -683,20 +724,34 @@ int launch_bwd(stp_ctx *ctx, const stp_layer_desc *d, const void *qkv, const flo
     STP_LAUNCH_CHECK(ctx);
   } else {
     hipLaunchKernelGGL(kkv, pkv.n_items ? dim3((unsigned)bk, pkv.n_items) : dim3(nkvb, mc_kv, (unsigned)bk), dim3(512), smem_kv, s,
-                       (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta, ws_kv, d->seq, d->heads_local, nk, d->causal, mc_kv, ch_kv,
-                       scale, pkv.n_items, pkv.order);
+                       (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta, ws_kv, (bf16_t *)dqkv, d->seq, d->heads_local, nk, d->causal, mc_kv,
+                       ch_kv, scale, pkv.n_items, pkv.order);
     STP_LAUNCH_CHECK(ctx);
     hipLaunchKernelGGL(kq, pq.n_items ? dim3((unsigned)bh, pq.n_items) : dim3(nqb, mc_q, (unsigned)bh), dim3(512), smem_q, s,
-                       (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta, ws_q, d->seq, d->heads_local, nk, d->causal, mc_q, ch_q, scale,
-                       pq.n_items, pq.order);
+                       (const bf16_t *)qkv, (const bf16_t *)dout, lse, delta, ws_q, (bf16_t *)dqkv, d->seq, d->heads_local, nk, d->causal, mc_q, ch_q,
+                       scale, pq.n_items, pq.order);
     STP_LAUNCH_CHECK(ctx);
   }
-  hipLaunchKernelGGL(attn_bwd_dkv_combine_kernel<D>, dim3((rows8_kv + 255) / 256), dim3(256), 0, s, ws_kv, (bf16_t *)dqkv, d->seq,
-                     d->heads_local, nk, d->mbsz, d->causal, mc_kv, ch_kv, scale);
-  STP_LAUNCH_CHECK(ctx);
-  hipLaunchKernelGGL(attn_bwd_dq_combine_kernel<D>, dim3((rows8 + 255) / 256), dim3(256), 0, s, ws_q, (bf16_t *)dqkv, d->seq,
-                     d->heads_local, nk, d->mbsz, d->causal, mc_q, ch_q, scale);
-  STP_LAUNCH_CHECK(ctx);
+  // Blocks with a single chunk were finished by the main kernels.  A key block's steps fall with its index (with the
+  // causal mask; otherwise all are equal), a query block's rise: the combine kernels run over the other rows only.
+  const int nq64 = (d->seq + QSTEP - 1) / QSTEP, group = d->heads_local / nk;
+  int kvb_end = nkvb, qb_first = 0;
+  while (kvb_end > 0 && group * (nq64 - dkv_first_step(kvb_end - 1, d->causal)) <= ch_kv) kvb_end--;
+  while (qb_first < nqb && dq_steps(qb_first, d->seq, d->causal) <= ch_q) qb_first++;
+  if (kvb_end > 0) {
+    const int kv_end = std::min(d->seq, kvb_end * KVB);
+    const size_t r8 = bk * kv_end * (D / 8);
+    hipLaunchKernelGGL(attn_bwd_dkv_combine_kernel<D>, dim3((r8 + 255) / 256), dim3(256), 0, s, ws_kv, (bf16_t *)dqkv, d->seq,
+                       d->heads_local, nk, d->mbsz, d->causal, mc_kv, ch_kv, scale, kv_end);
+    STP_LAUNCH_CHECK(ctx);
+  }
+  if (qb_first < nqb) {
+    const int q_first = qb_first * 128;
+    const size_t r8 = bh * (d->seq - q_first) * (D / 8);
+    hipLaunchKernelGGL(attn_bwd_dq_combine_kernel<D>, dim3((r8 + 255) / 256), dim3(256), 0, s, ws_q, (bf16_t *)dqkv, d->seq,
+                       d->heads_local, nk, d->mbsz, d->causal, mc_q, ch_q, scale, q_first);
+    STP_LAUNCH_CHECK(ctx);
+  }
   return STP_OK;
 }
 
