@@ -312,6 +312,40 @@ def test_softmax_forward_backward(ctx, dtype, rows, n, causal):
     assert rel_err(to_host(dx), refdx) < tol
 
 
+def test_row_kernels_reject_bad_arguments(ctx):
+    """Shape, alignment and null-pointer errors of the kernel-level entry points are statuses, raised before any launch."""
+    x = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
+    f = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
+    off = x[1:]                                     # 2 bytes past a 16-byte boundary
+    cases = [
+        (lambda: ctx.softmax_forward(stp.BF16, 4, 12, 1.0, False, x, x), 2),        # n not a multiple of 8
+        (lambda: ctx.softmax_forward(stp.BF16, 4, 16392, 1.0, False, x, x), 2),     # n beyond 16384
+        (lambda: ctx.softmax_forward(stp.BF16, 4, 64, 1.0, False, None, x), 1),
+        (lambda: ctx.softmax_forward(stp.BF16, 4, 64, 1.0, False, off, x), 3),
+        (lambda: ctx.softmax_forward(9, 4, 64, 1.0, False, x, x), 1),
+        (lambda: ctx.softmax_backward(stp.BF16, 4, 64, 1.0, x, None, x), 1),
+        (lambda: ctx.softmax_backward(stp.BF16, -1, 64, 1.0, x, x, x), 2),
+        (lambda: ctx.norm_forward(stp.BF16, stp.NORM_LN, 4, 60, 1e-5, x, x, x, x, f), 2),     # h not a multiple of 8
+        (lambda: ctx.norm_forward(stp.BF16, stp.NORM_LN, 4, 8200, 1e-5, x, x, x, x, f), 2),   # h beyond 8192
+        (lambda: ctx.norm_forward(stp.BF16, 5, 4, 64, 1e-5, x, x, x, x, f), 1),
+        (lambda: ctx.norm_forward(stp.BF16, stp.NORM_LN, 4, 64, 1e-5, x, x, x, off, f), 3),
+        (lambda: ctx.norm_forward(stp.BF16, stp.NORM_LN, 4, 64, 1e-5, x, x, x, x, None), 1),
+        (lambda: ctx.colsum(stp.BF16, 4, 60, x, 1.0, f), 2),
+        (lambda: ctx.colsum(stp.BF16, 4, 64, x, 1.0, f, lane=3), 1),
+        (lambda: ctx.colsum(stp.BF16, 4, 64, off, 1.0, f), 3),
+        (lambda: ctx.gelu_forward(stp.BF16, 64, off, x), 3),
+        (lambda: ctx.gelu_backward(stp.BF16, 64, x, None, x), 1),
+    ]
+    for i, (call, status) in enumerate(cases):
+        with pytest.raises(stp.StpError) as e:
+            call()
+        assert e.value.status == status, (i, e.value)
+    ctx.softmax_forward(stp.BF16, 0, 64, 1.0, False, x, x)      # empty problems are no-ops
+    ctx.norm_forward(stp.BF16, stp.NORM_LN, 0, 64, 1e-5, x, x, x, x, f)
+    ctx.colsum(stp.BF16, 0, 64, x, 1.0, f)
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ attention core
 # (dtype, seq, mbsz, query heads, head dim, causal, key / value heads; 0 = one per query head)
 ATTN_CASES = [("f32", 128, 1, 4, 64, True, 0), ("f32", 52, 2, 2, 32, False, 0), ("f32", 72, 1, 1, 128, True, 0),
