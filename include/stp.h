@@ -234,7 +234,9 @@ int stp_backward_weight_unit(stp_ctx *ctx, const stp_layer_desc *desc, int unit,
  * BW ops to microbatches j < i (Appendix A) unless the list has no F op; units
  * of one direction appear in dependence order; a W op needs its B in this list
  * or in an earlier step.  Passing the same stream three times serialises the
- * step (used to check braided == sequential bit for bit).
+ * step (used to check braided == sequential bit for bit).  The join with the
+ * previous step holds whichever streams that step ran on: the streams may change
+ * from one step to the next without a synchronisation by the caller.
  * STP_ESHAPE: two consecutive layers with no chain break between them differ in
  * tokens (seq * mbsz), hidden or dtype (the first writes into the second's input
  * slot).  STP_EUNSUPPORTED: one of the streams is being captured into a HIP graph.

@@ -2,7 +2,7 @@
 // the F units of microbatch i are issued on one HIP stream, the B units of an earlier
 // microbatch j on a second, the W units on a third, in the caller's interleaved order.
 // Only true data dependences are turned into events: a W waits for its B; a step waits
-// for the previous step on all three streams.  The four TP All-Reduce points per layer
+// for the previous step on all three streams (whichever streams that step ran on).  The four TP All-Reduce points per layer
 // are reported to the caller's boundary callback (no collective runs here).
 #include <stdlib.h>
 #include <string.h>
@@ -187,11 +187,15 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
   }
   rc = ensure_events(ctx, (int)n_ops);
   if (rc != STP_OK) return rc;
-  // join with the previous step: its stashes and gradients may be read by any stream now
-  if (!serial && ctx->ev_next) {
-    for (int i = 0; i < 3; i++)
+  // Join with the previous step: its stashes and gradients may be read by any stream now.  Every stream of this
+  // step waits for the end of the previous step on every stream but itself, also when the caller has changed
+  // streams between the two steps (a serialised step after a concurrent one, or the reverse).
+  if (ctx->ev_next) {
+    for (int i = 0; i < 3; i++) {
+      if (i > 0 && (streams[i] == streams[i - 1] || streams[i] == streams[0])) continue;   // already joined
       for (int j = 0; j < 3; j++)
-        if (streams[i] != streams[j]) STP_HIP(ctx, hipStreamWaitEvent(streams[i], ctx->ev_step[j], 0));
+        if (streams[i] != ctx->ev_stream[j]) STP_HIP(ctx, hipStreamWaitEvent(streams[i], ctx->ev_step[j], 0));
+    }
   }
   int *ev_of = (int *)malloc(sizeof(int) * bsz);
   uint8_t *b_now = (uint8_t *)calloc(bsz, 1);      // B units issued by this step; committed to the context when the step is whole
@@ -281,11 +285,10 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
   ctx->concurrent = 0;
   // The end-of-step events are recorded on the error path too: whatever part of the step was enqueued, the next
   // step still joins all three streams.  The B units count as done only when the whole step was issued.
-  if (!serial) {
-    for (int i = 0; i < 3; i++) {
-      const hipError_t e = hipEventRecord(ctx->ev_step[i], streams[i]);
-      if (e != hipSuccess && rc == STP_OK) rc = stp_fail(ctx, STP_EHIP, "hipEventRecord failed: %s", hipGetErrorString(e));
-    }
+  for (int i = 0; i < 3; i++) {
+    const hipError_t e = hipEventRecord(ctx->ev_step[i], streams[i]);
+    if (e != hipSuccess && rc == STP_OK) rc = stp_fail(ctx, STP_EHIP, "hipEventRecord failed: %s", hipGetErrorString(e));
+    ctx->ev_stream[i] = streams[i];
   }
   ctx->ev_next = 1;
   if (rc == STP_OK)

@@ -36,6 +36,7 @@ struct stp_ctx {
   char *ws;          // caller-supplied workspace (device)
   size_t ws_bytes;
   hipEvent_t ev_step[3];   // end-of-step events of the three braid streams
+  hipStream_t ev_stream[3]; // the stream each of them was last recorded on
   int have_step_events;
   hipEvent_t *ev_pool;     // events recorded after B ops, waited on by their W ops
   int ev_pool_size;

@@ -97,6 +97,32 @@ def test_braided_equals_serialized_bitwise_and_matches_oracle(ctx, name):
             assert rel_err(to_host(stg.g_dev[l][k]), r) < tol, (l, k)
 
 
+def test_streams_may_change_between_steps_without_a_synchronisation(ctx):
+    """A step joins the previous one whichever streams that one ran on: alternating between three streams, another
+    set of three and a single stream from step to step, with no synchronisation in between, gives the serialized
+    run's bits."""
+    layers, n_mb = STAGES["gpt_bf16_x2"]
+    stg = StageOnDevice(ctx, layers, n_mb, seed=2)
+    stg.load_inputs()
+    s0 = torch.cuda.current_stream()
+    run_sequence(ctx, stg, (s0, s0, s0))
+    serial = snapshot(stg)
+    a = tuple(torch.cuda.Stream() for _ in range(3))
+    b = tuple(torch.cuda.Stream() for _ in range(3))
+    c = torch.cuda.Stream()
+    choices = [a, (c, c, c), b, (s0, s0, s0), (b[2], b[0], a[1])]
+    for rep in range(2):
+        torch.cuda.synchronize()
+        ctx.braid_reset()
+        stg.zero_grads()
+        torch.cuda.synchronize()
+        for i, step in enumerate(stage_sequence(len(stg.layers), stg.n_mb)):
+            ctx.braid_step(stg.stage, step, *choices[(i + rep) % len(choices)])
+        torch.cuda.synchronize()
+        for u, v in zip(serial, snapshot(stg)):
+            assert torch.equal(u, v), f"run {rep} with changing streams differs from the serialized order"
+
+
 def test_boundary_callback_sees_every_all_reduce_point(ctx):
     stg = StageOnDevice(ctx, [synth.WORKLOADS["tiny"]] * 2, 2, seed=1)
     stg.load_inputs()
