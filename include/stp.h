@@ -228,15 +228,23 @@ int stp_backward_weight_unit(stp_ctx *ctx, const stp_layer_desc *desc, int unit,
 
 /* ---- the braided block (Section 3, Fig. 3; Section 4.1 pattern (2); Appendix A)
  * Issues `ops` in the given order: F ops on s_fwd, B ops on s_bwd, W ops (and
- * the W half of BW ops) on s_wgrad, with events only on true data dependences
- * (a W waits for its B; the step waits for the previous step).  The list is
+ * the W half of BW ops) on s_wgrad, with events only on true data dependences:
+ * a W waits for its B; of the previous step, a stream waits only for the streams
+ * whose work it reads or overwrites (the forward stream for B / W work on the
+ * microbatch whose stash it refills, the backward stream for the forward pass of
+ * its microbatches and for W work on them, the weight-gradient stream for their
+ * B units), and every stream waits for the whole of the step before that: at
+ * most two blocks are in flight, and a block's tail overlaps the next one's head.
+ * (Gradient accumulators and workspace lanes are touched by one stream each;
+ * units called directly on other streams are the caller's to order.)  The list is
  * validated first (STP_ESEQ): all F ops belong to one microbatch i, all B / W /
  * BW ops to microbatches j < i (Appendix A) unless the list has no F op; units
  * of one direction appear in dependence order; a W op needs its B in this list
  * or in an earlier step.  Passing the same stream three times serialises the
- * step (used to check braided == sequential bit for bit).  The join with the
- * previous step holds whichever streams that step ran on: the streams may change
- * from one step to the next without a synchronisation by the caller.
+ * step (used to check braided == sequential bit for bit).  If the streams differ
+ * from the previous step's, every stream waits for the whole of the steps before:
+ * the streams may change from one step to the next without a synchronisation by
+ * the caller.
  * STP_ESHAPE: two consecutive layers with no chain break between them differ in
  * tokens (seq * mbsz), hidden or dtype (the first writes into the second's input
  * slot).  STP_EUNSUPPORTED: one of the streams is being captured into a HIP graph.

@@ -1,8 +1,10 @@
 // The braided execution block (Section 3, Fig. 3; Section 4.1 pattern (2); Appendix A):
 // the F units of microbatch i are issued on one HIP stream, the B units of an earlier
 // microbatch j on a second, the W units on a third, in the caller's interleaved order.
-// Only true data dependences are turned into events: a W waits for its B; a step waits
-// for the previous step on all three streams (whichever streams that step ran on).  The four TP All-Reduce points per layer
+// Only true data dependences are turned into events: a W waits for its B; a stream of a step waits for
+// the streams of the previous step whose results it reads or overwrites, and every stream waits for
+// the whole of the step before that, so at most two blocks are in flight and a block's tail overlaps
+// the head of the next.  The four TP All-Reduce points per layer
 // are reported to the caller's boundary callback (no collective runs here).
 #include <stdlib.h>
 #include <string.h>
@@ -99,7 +101,7 @@ int validate(const stp_stage *st, const stp_op *ops, size_t n, const uint8_t *b_
 
 int ensure_events(stp_ctx *ctx, int want) {
   if (!ctx->have_step_events) {
-    for (int i = 0; i < 3; i++) STP_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_step[i], hipEventDisableTiming));
+    for (int i = 0; i < 6; i++) STP_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_step[i / 3][i % 3], hipEventDisableTiming));
     ctx->have_step_events = 1;
   }
   if (ctx->ev_pool_size < want) {
@@ -137,6 +139,7 @@ extern "C" int stp_braid_reset(stp_ctx *ctx) {
 extern "C" int stp_braid_detach(stp_ctx *ctx) {
   if (!ctx) return STP_EINVAL;
   ctx->ev_next = 0;
+  ctx->ev_valid[0] = ctx->ev_valid[1] = 0;
   return STP_OK;
 }
 
@@ -187,19 +190,60 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
   }
   rc = ensure_events(ctx, (int)n_ops);
   if (rc != STP_OK) return rc;
-  // Join with the previous step: its stashes and gradients may be read by any stream now.  Every stream of this
-  // step waits for the end of the previous step on every stream but itself, also when the caller has changed
-  // streams between the two steps (a serialised step after a concurrent one, or the reverse).
-  if (ctx->ev_next) {
-    for (int i = 0; i < 3; i++) {
-      if (i > 0 && (streams[i] == streams[i - 1] || streams[i] == streams[0])) continue;   // already joined
-      for (int j = 0; j < 3; j++)
-        if (streams[i] != ctx->ev_stream[j]) STP_HIP(ctx, hipStreamWaitEvent(streams[i], ctx->ev_step[j], 0));
-    }
+  // What this step touches: its forward microbatch and the microbatches with B / W work.
+  int f_mb = -1;
+  uint8_t *cur_b = (uint8_t *)calloc(2 * (size_t)MB, 1), *cur_w = cur_b ? cur_b + MB : nullptr;
+  if (!cur_b) return stp_fail(ctx, STP_ENOSPACE, "out of host memory%s");
+  for (size_t i = 0; i < n_ops; i++) {
+    const stp_op &o = ops[i];
+    if (o.kind == STP_OP_F) f_mb = o.microbatch;
+    if (o.kind == STP_OP_B || o.kind == STP_OP_BW) cur_b[o.microbatch] = 1;
+    if (o.kind == STP_OP_W || o.kind == STP_OP_BW) cur_w[o.microbatch] = 1;
   }
+  // Joins with the steps before.  Data of a (layer, microbatch) is written by that microbatch's F units (forward
+  // stream), read and extended by its B units (backward stream), read by its W units (weight-gradient stream);
+  // gradient accumulators and workspace lanes belong to one stream each.  So, of the last step, a stream waits
+  // only for   F: the B / W streams if they worked on the microbatch this step's F overwrites;
+  //            B: the F stream if it produced one of this step's backward microbatches, the W stream if it read one;
+  //            W: the B stream if it produced what this step's W units read (and the F stream likewise).
+  // All streams wait for the whole of the step before last, which bounds the skew to one block.  If the caller
+  // changed streams, or the stage's extent changed, every stream waits for everything.
+  const int last = ctx->ev_gen ^ 1, older = ctx->ev_gen;
+  bool same_streams = ctx->ev_valid[last] && ctx->last_mbs == MB && ctx->last_b;
+  for (int i = 0; i < 3 && same_streams; i++) same_streams = ctx->ev_stream[last][i] == streams[i];
+  auto wait_for = [&](hipStream_t s, int gen, int j) -> int {
+    if (!ctx->ev_valid[gen] || ctx->ev_stream[gen][j] == s) return STP_OK;
+    STP_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_step[gen][j], 0));
+    return STP_OK;
+  };
+  rc = STP_OK;
+  if (ctx->ev_next && !same_streams) {
+    for (int i = 0; i < 3 && rc == STP_OK; i++) {
+      if (i > 0 && (streams[i] == streams[i - 1] || streams[i] == streams[0])) continue;   // already joined
+      for (int g = 0; g < 2; g++)
+        for (int j = 0; j < 3 && rc == STP_OK; j++) rc = wait_for(streams[i], g, j);
+    }
+  } else if (ctx->ev_next && !serial) {
+    for (int i = 0; i < 3 && rc == STP_OK; i++)
+      for (int j = 0; j < 3 && rc == STP_OK; j++) rc = wait_for(streams[i], older, j);
+    bool b_after_f = false, b_after_w = false, w_after_b = false, w_after_f = false;
+    for (int m = 0; m < MB; m++) {
+      if (cur_b[m] && m == ctx->last_f_mb) b_after_f = true;
+      if (cur_b[m] && ctx->last_w[m]) b_after_w = true;
+      if (cur_w[m] && ctx->last_b[m]) w_after_b = true;
+      if (cur_w[m] && m == ctx->last_f_mb) w_after_f = true;
+    }
+    if (rc == STP_OK && f_mb >= 0 && ctx->last_b[f_mb]) rc = wait_for(sF, last, 1);
+    if (rc == STP_OK && f_mb >= 0 && ctx->last_w[f_mb]) rc = wait_for(sF, last, 2);
+    if (rc == STP_OK && b_after_f) rc = wait_for(sB, last, 0);
+    if (rc == STP_OK && b_after_w) rc = wait_for(sB, last, 2);
+    if (rc == STP_OK && w_after_b) rc = wait_for(sW, last, 1);
+    if (rc == STP_OK && w_after_f) rc = wait_for(sW, last, 0);
+  }
+  if (rc != STP_OK) { free(cur_b); return rc; }
   int *ev_of = (int *)malloc(sizeof(int) * bsz);
   uint8_t *b_now = (uint8_t *)calloc(bsz, 1);      // B units issued by this step; committed to the context when the step is whole
-  if (!ev_of || !b_now) { free(ev_of); free(b_now); return stp_fail(ctx, STP_ENOSPACE, "out of host memory%s"); }
+  if (!ev_of || !b_now) { free(ev_of); free(b_now); free(cur_b); return stp_fail(ctx, STP_ENOSPACE, "out of host memory%s"); }
   for (size_t i = 0; i < bsz; i++) ev_of[i] = -1;
   int ev_used = 0;
   rc = STP_OK;
@@ -283,13 +327,27 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
   }
   free(ev_of);
   ctx->concurrent = 0;
-  // The end-of-step events are recorded on the error path too: whatever part of the step was enqueued, the next
-  // step still joins all three streams.  The B units count as done only when the whole step was issued.
-  for (int i = 0; i < 3; i++) {
-    const hipError_t e = hipEventRecord(ctx->ev_step[i], streams[i]);
-    if (e != hipSuccess && rc == STP_OK) rc = stp_fail(ctx, STP_EHIP, "hipEventRecord failed: %s", hipGetErrorString(e));
-    ctx->ev_stream[i] = streams[i];
+  // The end-of-step events are recorded on the error path too: whatever part of the step was enqueued, later
+  // steps still order themselves behind it.  The B units count as done only when the whole step was issued.
+  {
+    const int gen = ctx->ev_gen;
+    for (int i = 0; i < 3; i++) {
+      const hipError_t e = hipEventRecord(ctx->ev_step[gen][i], streams[i]);
+      if (e != hipSuccess && rc == STP_OK) rc = stp_fail(ctx, STP_EHIP, "hipEventRecord failed: %s", hipGetErrorString(e));
+      ctx->ev_stream[gen][i] = streams[i];
+    }
+    ctx->ev_valid[gen] = 1;
+    ctx->ev_gen = gen ^ 1;
+    if (ctx->last_mbs != MB || !ctx->last_b) {
+      free(ctx->last_b);
+      ctx->last_b = (uint8_t *)calloc(2 * (size_t)MB, 1);
+      ctx->last_w = ctx->last_b ? ctx->last_b + MB : nullptr;
+      ctx->last_mbs = ctx->last_b ? MB : 0;
+    }
+    if (ctx->last_b) memcpy(ctx->last_b, cur_b, 2 * (size_t)MB);
+    ctx->last_f_mb = f_mb;
   }
+  free(cur_b);
   ctx->ev_next = 1;
   if (rc == STP_OK)
     for (size_t i = 0; i < bsz; i++) ctx->b_done[i] |= b_now[i];

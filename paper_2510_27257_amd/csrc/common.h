@@ -35,8 +35,15 @@ struct stp_ctx {
   char err[512];
   char *ws;          // caller-supplied workspace (device)
   size_t ws_bytes;
-  hipEvent_t ev_step[3];   // end-of-step events of the three braid streams
-  hipStream_t ev_stream[3]; // the stream each of them was last recorded on
+  // End-of-step events of the three braid streams for the last two steps (generation = step parity), the stream
+  // each was recorded on, and what the last step touched: its forward microbatch and, per microbatch, whether it
+  // held B or W work.  A step waits for all of the step before last and, of the last one, only for the streams
+  // whose work it depends on.
+  hipEvent_t ev_step[2][3];
+  hipStream_t ev_stream[2][3];
+  int ev_valid[2], ev_gen;          // ev_gen: generation the NEXT step records into
+  int last_f_mb, last_mbs;
+  uint8_t *last_b, *last_w;         // [last_mbs]
   int have_step_events;
   hipEvent_t *ev_pool;     // events recorded after B ops, waited on by their W ops
   int ev_pool_size;

@@ -41,11 +41,12 @@ extern "C" int stp_create(stp_ctx **out, int device) {
 extern "C" int stp_destroy(stp_ctx *ctx) {
   if (!ctx) return STP_EINVAL;
   if (ctx->have_step_events)
-    for (int i = 0; i < 3; i++) (void)hipEventDestroy(ctx->ev_step[i]);
+    for (int i = 0; i < 6; i++) (void)hipEventDestroy(ctx->ev_step[i / 3][i % 3]);
   for (int i = 0; i < ctx->ev_pool_size; i++) (void)hipEventDestroy(ctx->ev_pool[i]);
   for (int i = 0; i < ctx->ev_copy_made; i++) (void)hipEventDestroy(ctx->ev_copy[i]);
   free(ctx->ev_pool);
   free(ctx->b_done);
+  free(ctx->last_b);   // last_w points into the same block
   delete ctx;
   return STP_OK;
 }

@@ -60,7 +60,7 @@ def test_braided_equals_serialized_bitwise_and_matches_oracle(ctx, name):
     run_sequence(ctx, stg, (s0, s0, s0))
     serial = snapshot(stg)
     sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
-    for rep in range(2):
+    for rep in range(4):
         run_sequence(ctx, stg, (sF, sB, sW))
         for a, b in zip(serial, snapshot(stg)):
             assert torch.equal(a, b), f"{name}: braided run {rep} differs from the serialized order"
@@ -95,6 +95,40 @@ def test_braided_equals_serialized_bitwise_and_matches_oracle(ctx, name):
     for l in range(L):
         for k, r in g_ref[l].items():
             assert rel_err(to_host(stg.g_dev[l][k]), r) < tol, (l, k)
+
+
+@pytest.mark.parametrize("name", ["gpt_bf16_x2", "llama_bf16_x1"])
+def test_repeated_blocks_overlap_only_where_data_allows(ctx, name):
+    """The same block, F of the last microbatch braided with the full backward of microbatch 0, issued eight times
+    in a row without a synchronisation: a block's streams wait for the previous block only where they read or
+    overwrite its data (here the backward stream overwrites what the previous block's weight-gradient stream
+    reads), so blocks overlap at their edges.  Outputs, stashes and the eight-fold accumulated weight gradients
+    must equal the serialized run's bit for bit."""
+    from paper_2510_27257_amd.binding import OP_BW
+    from paper_2510_27257_amd.stage import backward_ops, braid, forward_ops
+    layers, n_mb = STAGES[name]
+    L = len(layers)
+    stg = StageOnDevice(ctx, layers, n_mb, seed=7)
+    stg.load_inputs()
+    s0 = torch.cuda.current_stream()
+    block = braid(forward_ops(L, n_mb - 1), backward_ops(L, 0, OP_BW))
+
+    def run(streams):
+        torch.cuda.synchronize()
+        ctx.braid_reset()
+        stg.zero_grads()
+        ctx.braid_step(stg.stage, forward_ops(L, 0), s0, s0, s0)
+        torch.cuda.synchronize()
+        for _ in range(8):
+            ctx.braid_step(stg.stage, block, *streams)
+        torch.cuda.synchronize()
+        return snapshot(stg) + [m.clone() for m in stg.stash_mem]
+
+    serial = run((s0, s0, s0))
+    streams = tuple(torch.cuda.Stream() for _ in range(3))
+    for rep in range(3):
+        for u, v in zip(serial, run(streams)):
+            assert torch.equal(u, v), f"{name}: run {rep} of overlapping blocks differs from the serialized order"
 
 
 def test_streams_may_change_between_steps_without_a_synchronisation(ctx):
