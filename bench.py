@@ -17,6 +17,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -56,6 +57,21 @@ def time_steps(fn, steps, warmup, torch):
         fn()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def time_each(fn, reps, warmup, torch):
+    """Mean time of `reps` runs of fn, each between two device synchronisations of its own (a whole sequence
+    with its copies to and from the host, as one training iteration would run it)."""
+    for _ in range(warmup):
+        fn()
+    total = 0.0
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        total += time.perf_counter() - t0
+    return total * 1e3 / reps
 
 
 def event_steps(ctx, stage, arr, streams, steps, torch):
@@ -168,6 +184,7 @@ def gemm_context(ctx, wl, reps, torch, stp):
 
 
 HBM_PEAK_GBS = 8000.0
+HOST_LINK_BPS = 50e9          # device <-> page-locked host memory, one direction, large copies (measured 54 - 55 GB/s)
 
 
 def hbm_leg(ctx, wl, torch, stp, reps=200):
@@ -343,19 +360,35 @@ def stage_bench(ctx, args, torch, stp, synth):
     if args.offload_alpha is not None:
         # Section 4.2 / 4.3: a share alpha of the long-lived stashes goes to page-locked host memory on a copy
         # stream and comes back before its consumer; the paper's condition is T_o < T_F per model chunk
-        from paper_2510_27257_amd.binding import OFFLOAD_FWD
+        from paper_2510_27257_amd.binding import OFFLOAD_FWD, OFFLOAD_W_ATTN as B_W_ATTN, OFFLOAD_W_MLP as B_W_MLP
         from paper_2510_27257_amd.stage import run_sequence_with_offload
         alpha = args.offload_alpha
         moved = [0]
+        # a reload has to be under way for as long as its copy takes: per microbatch the stashes of all layers,
+        # at the link's rate, in steps of the sequence's average length
+        if args.offload_lead > 0:
+            lead = args.offload_lead
+        else:
+            per_mb = 0
+            if args.offload_sets in ("fwd", "both"):
+                per_mb = max(per_mb, sum(off.bytes(l, OFFLOAD_FWD, alpha) for l in range(L)))
+            if args.offload_sets in ("w", "both"):
+                per_mb = max(per_mb, sum(off.bytes(l, B_W_MLP, alpha) + off.bytes(l, B_W_ATTN, alpha) for l in range(L)))
+            lead = max(1, math.ceil(per_mb / HOST_LINK_BPS / (ms_braided * 1e-3 / len(steps))))
 
         def run_off():
             ctx.braid_reset()
             moved[0] = run_sequence_with_offload(ctx, stg, steps, (sF, sB, sW), off, alpha,
                                                  forward_stash=args.offload_sets in ("fwd", "both"),
                                                  w_stash=args.offload_sets in ("w", "both"),
-                                                 min_gap=args.offload_min_gap)
+                                                 min_gap=args.offload_min_gap, lead=lead)
 
-        ms_off = time_steps(run_off, reps, 1, torch)
+        # every sequence between synchronisations of its own: issued back to back, the host blocks inside the
+        # asynchronous copy calls of the next sequence while the previous one's copies are in flight (measured:
+        # 35 ms per sequence against 29.7 ms for one alone), which is the runtime's doing and no part of a
+        # training iteration, which ends in a synchronisation anyway
+        ms_off = time_each(run_off, reps, 1, torch)
+        ms_plain_each = time_each(lambda: run((sF, sB, sW)), reps, 1, torch)
         # T_o: the forward stash of the whole chunk (all layers, one microbatch), copied alone
         def copy_alone():
             for l in range(L):
@@ -364,8 +397,9 @@ def stage_bench(ctx, args, torch, stp, synth):
         f_all = (stp.Op * (4 * L))(*forward_ops(L, 0))
         ms_tf = time_steps(lambda: ctx.braid_step(stg.stage, f_all, s0, s0, s0), 5, 1, torch)
         chunk_bytes = sum(off.bytes(l, OFFLOAD_FWD, alpha) for l in range(L))
-        offload = {"alpha": alpha, "sets": args.offload_sets, "min_gap_steps": args.offload_min_gap,
-                   "makespan_ms": ms_off, "makespan_without_ms": ms_braided,
+        offload = {"alpha": alpha, "sets": args.offload_sets, "min_gap_steps": args.offload_min_gap, "reload_lead_steps": lead,
+                   "makespan_ms": ms_off, "makespan_without_ms": ms_plain_each,
+                   "timing": "each sequence between device synchronisations of its own",
                    "bytes_to_host_per_sequence": moved[0], "bytes_back_per_sequence": moved[0],
                    "T_o_ms_forward_stash_of_chunk": ms_to, "T_F_ms_chunk": ms_tf,
                    "d2h_GBps": chunk_bytes / ms_to / 1e6 if ms_to > 0 else None,
@@ -408,6 +442,9 @@ def main():
                          "offloaded to page-locked host memory and reloaded (reported under \"offload\")")
     ap.add_argument("--offload-min-gap", type=int, default=1,
                     help="move only stashes whose consumer is at least this many braid steps after their producer")
+    ap.add_argument("--offload-lead", type=int, default=0,
+                    help="with --offload-alpha: steps a reload is enqueued ahead of its consumer (0 = as many as the copy "
+                         "takes at 50 GB/s)")
     ap.add_argument("--offload-sets", choices=["w", "fwd", "both"], default="w",
                     help="what --offload-alpha moves: the W-stashes of microbatches whose weight gradients are "
                          "deferred (long-lived), the forward stashes (short-lived in a one-stage sequence), or both")

@@ -169,7 +169,7 @@ class Offloader:
                                   self.host[key], self.reload_stream, s_consumer)
 
 
-def plan_offload(steps, n_mb: int, forward_stash: bool = True, w_stash: bool = True, min_gap: int = 1):
+def plan_offload(steps, n_mb: int, forward_stash: bool = True, w_stash: bool = True, min_gap: int = 1, lead: int = 1):
     """Host-side plan of the offload policy of Section 4.2 / 4.3 for a list of braid steps (each a list of ops).
 
     The W-stash of a microbatch whose weight gradients are separated (B in one step, W in a later one) leaves
@@ -177,7 +177,9 @@ def plan_offload(steps, n_mb: int, forward_stash: bool = True, w_stash: bool = T
     that holds its F (unless its B is in the same step) and returns for the step that holds its B.  Only a
     stash whose consumer is at least `min_gap` steps after its producer is moved: the trip to the host and back
     has to fit into that lifespan, or the consumer waits for it (the paper's T_o < T_F condition).  A reload is
-    enqueued one step ahead of its consumer, so that the copy runs under the step before.
+    enqueued `lead` steps ahead of its consumer (never before its offload), so that the copy runs under the steps
+    before: `lead` should cover the copy's duration, bytes / link rate, in steps, or the consumer waits for the
+    rest; a longer lead keeps the stash on the device for longer.
 
     Returns (before, after): per step index the lists of ("reload", kind, mb) to enqueue before the step is
     issued and of ("offload" | "reload", kind, mb) to enqueue after it, kind in {"fwd", "w"}."""
@@ -203,18 +205,18 @@ def plan_offload(steps, n_mb: int, forward_stash: bool = True, w_stash: bool = T
                 if sj is None or sj - si < max(min_gap, 1):
                     continue
                 after[si].append(("offload", kind, mb))
-                # one step ahead of the consumer; right behind the offload if the consumer is the next step
-                after[sj - 1].append(("reload", kind, mb))
+                # `lead` steps ahead of the consumer; right behind the offload if that is earlier than the offload
+                after[max(si, sj - max(lead, 1))].append(("reload", kind, mb))
     return before, after
 
 
 def run_sequence_with_offload(ctx: B.Context, stg: StageOnDevice, steps, streams, off: Offloader, alpha: float,
-                              forward_stash: bool = True, w_stash: bool = True, min_gap: int = 1) -> int:
+                              forward_stash: bool = True, w_stash: bool = True, min_gap: int = 1, lead: int = 1) -> int:
     """Issues the braid steps of a stage sequence with the moves plan_offload lists.  Returns the bytes copied
     device -> host (the same number returns)."""
     L = len(stg.layers)
     sF, sB, sW = streams
-    before, after = plan_offload(steps, stg.n_mb, forward_stash, w_stash, min_gap)
+    before, after = plan_offload(steps, stg.n_mb, forward_stash, w_stash, min_gap, lead)
     moved = 0
 
     def do(action, kind, mb):

@@ -139,10 +139,11 @@ from paper_2510_27257_amd.stage import plan_offload, stage_sequence
 @pytest.mark.parametrize("n_mb", [4, 8, 12])
 @pytest.mark.parametrize("min_gap", [1, 2, 3])
 @pytest.mark.parametrize("sets", [(True, True), (False, True), (True, False)])
-def test_offload_plan_pairs_every_move_and_respects_lifespans(n_mb, min_gap, sets):
+@pytest.mark.parametrize("lead", [1, 3, 100])
+def test_offload_plan_pairs_every_move_and_respects_lifespans(n_mb, min_gap, sets, lead):
     steps = stage_sequence(2, n_mb)
     kinds = [{(o.kind, o.microbatch) for o in st} for st in steps]
-    before, after = plan_offload(steps, n_mb, forward_stash=sets[0], w_stash=sets[1], min_gap=min_gap)
+    before, after = plan_offload(steps, n_mb, forward_stash=sets[0], w_stash=sets[1], min_gap=min_gap, lead=lead)
     assert all(not b for b in before)
     out = {}
     n_moves = 0
@@ -162,10 +163,11 @@ def test_offload_plan_pairs_every_move_and_respects_lifespans(n_mb, min_gap, set
                 cons = (B.OP_B, B.OP_BW) if kind == "fwd" else (B.OP_W,)
                 sj = next(j for j in range(si + 1, len(steps)) if any((k, mb) in kinds[j] for k in cons))
                 assert sj - si >= min_gap
-                out[(kind, mb)] = sj
+                out[(kind, mb)] = (si, sj)
                 n_moves += 1
             else:
-                assert out.pop((kind, mb)) == si + 1        # enqueued one step ahead of the consumer
+                s_off, sj = out.pop((kind, mb))               # its offload came first (earlier step, or earlier in this list)
+                assert si == max(s_off, sj - lead)            # `lead` steps ahead of the consumer, never before the offload
         if not sets[0]:
             assert all(k != "fwd" for _, k, _ in after[si])
         if not sets[1]:
@@ -185,3 +187,5 @@ def test_long_lived_w_stash_of_the_canonical_sequence():
     _, after = plan_offload(steps, 8, forward_stash=False, w_stash=True, min_gap=3)
     moves = [(si, m) for si, a in enumerate(after) for m in a]
     assert moves == [(2, ("offload", "w", 1)), (9, ("reload", "w", 1))]
+    _, after = plan_offload(steps, 8, forward_stash=False, w_stash=True, min_gap=3, lead=4)
+    assert [(si, m) for si, a in enumerate(after) for m in a] == [(2, ("offload", "w", 1)), (6, ("reload", "w", 1))]
