@@ -213,7 +213,7 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
   for (int i = 0; i < 3 && same_streams; i++) same_streams = ctx->ev_stream[last][i] == streams[i];
   auto wait_for = [&](hipStream_t s, int gen, int j) -> int {
     if (!ctx->ev_valid[gen] || ctx->ev_stream[gen][j] == s) return STP_OK;
-    STP_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_step[gen][j], 0));
+    STP_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_step[gen][ctx->ev_alias[gen][j]], 0));
     return STP_OK;
   };
   rc = STP_OK;
@@ -331,10 +331,14 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
   // steps still order themselves behind it.  The B units count as done only when the whole step was issued.
   {
     const int gen = ctx->ev_gen;
-    for (int i = 0; i < 3; i++) {
+    for (int i = 0; i < 3; i++) {      // one event per distinct stream (a serialised step records one)
+      ctx->ev_stream[gen][i] = streams[i];
+      ctx->ev_alias[gen][i] = i;
+      for (int j = 0; j < i; j++)
+        if (streams[j] == streams[i]) { ctx->ev_alias[gen][i] = ctx->ev_alias[gen][j]; break; }
+      if (ctx->ev_alias[gen][i] != i) continue;
       const hipError_t e = hipEventRecord(ctx->ev_step[gen][i], streams[i]);
       if (e != hipSuccess && rc == STP_OK) rc = stp_fail(ctx, STP_EHIP, "hipEventRecord failed: %s", hipGetErrorString(e));
-      ctx->ev_stream[gen][i] = streams[i];
     }
     ctx->ev_valid[gen] = 1;
     ctx->ev_gen = gen ^ 1;

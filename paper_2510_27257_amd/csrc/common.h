@@ -41,6 +41,7 @@ struct stp_ctx {
   // whose work it depends on.
   hipEvent_t ev_step[2][3];
   hipStream_t ev_stream[2][3];
+  int ev_alias[2][3];               // index of the event that stands for stream i (streams passed twice share one)
   int ev_valid[2], ev_gen;          // ev_gen: generation the NEXT step records into
   int last_f_mb, last_mbs;
   uint8_t *last_b, *last_w;         // [last_mbs]
