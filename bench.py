@@ -290,7 +290,7 @@ def stage_bench(ctx, args, torch, stp, synth):
     else:
         layers, cb = [synth.WORKLOADS["vit"]] * 2 + [lm] * 2, [0, 0, 1, 0, 0]
     n_mb = 8
-    stg = StageOnDevice(ctx, layers, n_mb, seed=0, chain_break=cb)
+    stg = StageOnDevice(ctx, layers, n_mb, seed=0, chain_break=cb, tuned_tiles=not args.no_tuned_tiles)
     stg.load_inputs()
     L = len(layers)
     sched = None
@@ -307,7 +307,7 @@ def stage_bench(ctx, args, torch, stp, synth):
         if cb is None:
             cb = [0] * (L + 1)
             cb[first1] = 1
-        stg = StageOnDevice(ctx, layers, n_mb, seed=0, chain_break=cb)
+        stg = StageOnDevice(ctx, layers, n_mb, seed=0, chain_break=cb, tuned_tiles=not args.no_tuned_tiles)
         stg.load_inputs()
         step_lists = S.braid_steps(progs[d_], L, first1)
         seq_name = f"program of device {d_} of {p_} ({m_} microbatches) from the schedule generator"
@@ -422,6 +422,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="gpt7b_tp8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tuned-tiles", action="store_true",
+                    help="leave the measured GEMM tile preferences of the package's tuned_tiles.json aside")
     ap.add_argument("--stage", choices=["pp4", "mllm"], default=None,
                     help="time one pipeline stage's whole braided sequence instead of the single block: "
                          "pp4 = 4 GPT-7B TP=8 layers at seq 4096, 8 microbatches; mllm = 2 ViT layers + 2 such "
@@ -510,7 +512,7 @@ def main():
         stage_bench(ctx, args, torch, stp, synth)
         ctx.close()
         return
-    stg = StageOnDevice(ctx, [wl], n_mb=2, seed=0)
+    stg = StageOnDevice(ctx, [wl], n_mb=2, seed=0, tuned_tiles=not args.no_tuned_tiles)
     stg.load_inputs()
     sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     s0 = torch.cuda.current_stream()
@@ -579,7 +581,9 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: hidden {h}, {wl.heads_local} local heads x {wl.head_dim}, ffn shard {f}, "
                                f"seq {T}, microbatch 1, tp {wl.tp}; step = F(mb1) braided with B+W(mb0), 1 layer",
-                   "flops_per_step": total_flops},
+                   "flops_per_step": total_flops,
+                   "gemm_tile_hints": ("measured tile preferences of paper_2510_27257_amd/tuned_tiles.json for the block's GEMMs"
+                                       if stg.tuned else "none (the library's own tile choice)")},
         "mfma_util_frac_of_bf16_peak": total_flops / (ms_braided * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
         "sustained_shader_clock_mhz": sustained_mhz,
         "sustained_shader_clock_source": "stp_clock_probe: one wave of one compute unit counting shader cycles for a 12 ms window while braided "

@@ -314,6 +314,15 @@ typedef struct {
                             * only): forces that tile, for tuning and tests; anything else is STP_EINVAL */
 } stp_gemm_args;
 int stp_gemm(stp_ctx *ctx, const stp_gemm_args *args, void *hip_stream);
+/* A measured tile preference for the bf16 GEMM of one shape and operand order, used for launches that
+ * stp_braid_step issues on concurrent streams (Section 3: the units of a block share the GPU).  Which tile is
+ * fastest there depends on the kernels of the other streams; the library's own choice models the GEMM alone.
+ * Results do not depend on the tile (every element is summed over K in the same order).  tile_m = tile_n = 0
+ * forgets the preference for that shape.  Host only; at most 96 shapes per context (STP_ENOSPACE);
+ * STP_EINVAL for a tile stp_gemm_args.tile_m / tile_n would not take. */
+int stp_gemm_tile_hint(stp_ctx *ctx, int32_t M, int32_t N, int32_t K, int a_trans, int b_trans,
+                       int32_t tile_m, int32_t tile_n);
+int stp_gemm_tile_hints_clear(stp_ctx *ctx);
 
 /* Normalisation of the Pre-* units.  stats is fp32 [T,2] (mean, rstd); RMSNorm stores (0, rstd). */
 int stp_norm_forward(stp_ctx *ctx, int dtype, int norm, int32_t T, int32_t h, float eps, const void *x,

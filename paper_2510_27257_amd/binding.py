@@ -27,7 +27,7 @@ STASH_FIELDS = ["X_LN", "STATS1", "QKV", "CTX", "LSE", "Z_LN", "STATS2", "H", "H
                 "DQKV", "DCTX", "DELTA", "X_ATTN", "DX_ATTN", "DZ", "DX_LN"]
 
 EXPORTED_SYMBOLS = [
-    "stp_create", "stp_destroy", "stp_last_error", "stp_status_str", "stp_check_desc", "stp_stash_bytes",
+    "stp_gemm_tile_hint", "stp_gemm_tile_hints_clear", "stp_create", "stp_destroy", "stp_last_error", "stp_status_str", "stp_check_desc", "stp_stash_bytes",
     "stp_stash_field", "stp_workspace_bytes", "stp_set_workspace", "stp_forward_unit",
     "stp_backward_input_unit", "stp_backward_weight_unit", "stp_braid_step", "stp_validate_ops",
     "stp_braid_reset", "stp_braid_detach", "stp_attention_plan", "stp_gemm", "stp_norm_forward", "stp_norm_backward", "stp_attention_forward",
@@ -131,6 +131,8 @@ def lib() -> C.CDLL:
     L.stp_braid_detach.argtypes = [vp]
     L.stp_attention_plan.argtypes = [P(LayerDesc), C.c_int, P(i32), P(i32), P(i32), P(C.c_uint16), sz]
     L.stp_gemm.argtypes = [vp, P(GemmArgs), vp]
+    L.stp_gemm_tile_hint.argtypes = [vp, i32, i32, i32, C.c_int, C.c_int, i32, i32]
+    L.stp_gemm_tile_hints_clear.argtypes = [vp]
     L.stp_norm_forward.argtypes = [vp, C.c_int, C.c_int, i32, i32, f32, vp, vp, vp, vp, vp, vp]
     L.stp_norm_backward.argtypes = [vp, C.c_int, C.c_int, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, C.c_int, vp]
     L.stp_attention_forward.argtypes = [vp, P(LayerDesc), vp, vp, vp, C.c_int, vp]
@@ -307,6 +309,13 @@ class Context:
     # ---- kernels -------------------------------------------------------------
     def gemm(self, args: GemmArgs, stream=None):
         self.check(self._lib.stp_gemm(self._h, C.byref(args), _stream(stream)), "stp_gemm")
+
+    def gemm_tile_hint(self, M, N, K, a_trans, b_trans, tile_m, tile_n):
+        self.check(self._lib.stp_gemm_tile_hint(self._h, M, N, K, int(a_trans), int(b_trans), tile_m, tile_n),
+                   "stp_gemm_tile_hint")
+
+    def gemm_tile_hints_clear(self):
+        self.check(self._lib.stp_gemm_tile_hints_clear(self._h), "stp_gemm_tile_hints_clear")
 
     def norm_forward(self, dtype, norm, T, h, eps, x, gamma, beta, y, stats, stream=None):
         self.check(self._lib.stp_norm_forward(self._h, dtype, norm, T, h, eps, _ptr(x), _ptr(gamma), _ptr(beta),

@@ -30,6 +30,7 @@ struct stp_attn_plan {
 };
 #define STP_ATTN_PLAN_CACHE 12
 
+#define STP_TILE_HINTS 96
 struct stp_ctx {
   int device;
   char err[512];
@@ -60,6 +61,11 @@ struct stp_ctx {
   // set by stp_braid_step while it issues a step on distinct streams: kernels launched then share the GPU
   // with the other streams' kernels, which changes the best GEMM tile
   int concurrent;
+  // Tile preferences of the bf16 GEMM for launches issued while stp_braid_step runs on concurrent streams
+  // (stp_gemm_tile_hint): what is fastest there depends on the kernels of the other streams, which no model of
+  // the GEMM alone sees, so a caller may measure and say.
+  struct { int32_t M, N, K, layout, tile_m, tile_n; } tile_hint[STP_TILE_HINTS];
+  int n_tile_hints;
   // plans of the attention kernels for the shapes seen so far (making one simulates the dispatch)
   stp_attn_plan attn_plan[STP_ATTN_PLAN_CACHE];
   int attn_plan_n, attn_plan_next;

@@ -657,6 +657,11 @@ int launch_tile(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t
   const bool dma_ok = a->K % DK == 0 && operand_bytes(A_KC, a->M, a->K, a->lda) > 0 && operand_bytes(B_KC, a->N, a->K, a->ldb) > 0;
   if (!dma_ok) return launch_cfg<128, 128, 2, 2, A_KC, B_KC, EPI>(ctx, a, ep, s);
   TileChoice c = pick_tile(a->M, a->N, a->K, A_KC, B_KC, ctx && ctx->concurrent);
+  if (ctx && ctx->concurrent)       // a measured preference for this shape beside other streams' kernels
+    for (int i = 0; i < ctx->n_tile_hints; i++) {
+      const auto &hnt = ctx->tile_hint[i];
+      if (hnt.M == a->M && hnt.N == a->N && hnt.K == a->K && hnt.layout == 2 * (int)A_KC + (int)B_KC) { c = TileChoice{hnt.tile_m, hnt.tile_n}; break; }
+    }
   if (a->tile_m) c = TileChoice{a->tile_m, a->tile_n};
   if constexpr (A_KC) {
     // 192 rows: 6144 tokens are 32 such tiles, and 32 x (N / 256) fills the 256 compute units in whole rounds

@@ -160,6 +160,37 @@ extern "C" int stp_set_workspace(stp_ctx *ctx, void *p, size_t bytes) {
 }
 
 // ---------------------------------------------------------------------------
+extern "C" int stp_gemm_tile_hint(stp_ctx *ctx, int32_t M, int32_t N, int32_t K, int a_trans, int b_trans, int32_t tile_m,
+                                  int32_t tile_n) {
+  if (!ctx) return STP_EINVAL;
+  const int layout = 2 * (a_trans ? 0 : 1) + (b_trans ? 1 : 0);
+  int at = -1;
+  for (int i = 0; i < ctx->n_tile_hints; i++) {
+    const auto &h = ctx->tile_hint[i];
+    if (h.M == M && h.N == N && h.K == K && h.layout == layout) { at = i; break; }
+  }
+  if (tile_m == 0 && tile_n == 0) {          // forget the preference
+    if (at >= 0) ctx->tile_hint[at] = ctx->tile_hint[--ctx->n_tile_hints];
+    return STP_OK;
+  }
+  const bool square = (tile_m == 128 || tile_m == 256) && (tile_n == 128 || tile_n == 256);
+  const bool wide = tile_m == 192 && tile_n == 256 && !a_trans;
+  if (!square && !wide) return stp_fail(ctx, STP_EINVAL, "stp_gemm_tile_hint: the tile must be 128 or 256 each way, or 192 x 256 with a_trans = 0%s");
+  if (M <= 0 || N <= 0 || K <= 0) return stp_fail(ctx, STP_ESHAPE, "stp_gemm_tile_hint: bad shape%s");
+  if (at < 0) {
+    if (ctx->n_tile_hints >= STP_TILE_HINTS) return stp_fail(ctx, STP_ENOSPACE, "stp_gemm_tile_hint: table full%s");
+    at = ctx->n_tile_hints++;
+  }
+  ctx->tile_hint[at] = {M, N, K, layout, tile_m, tile_n};
+  return STP_OK;
+}
+
+extern "C" int stp_gemm_tile_hints_clear(stp_ctx *ctx) {
+  if (!ctx) return STP_EINVAL;
+  ctx->n_tile_hints = 0;
+  return STP_OK;
+}
+
 extern "C" int stp_gemm(stp_ctx *ctx, const stp_gemm_args *g, void *hip_stream) {
   if (!ctx) return STP_EINVAL;
   if (!g || !g->A || !g->B || !g->C) return stp_fail(ctx, STP_EINVAL, "stp_gemm: null pointer%s");

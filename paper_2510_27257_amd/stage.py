@@ -23,9 +23,13 @@ def _to_dev(x, dtype: str) -> torch.Tensor:
 
 class StageOnDevice:
     def __init__(self, ctx: B.Context, layers: Sequence[synth.Workload], n_mb: int, seed: int = 0,
-                 chain_break: Optional[Sequence[int]] = None):
+                 chain_break: Optional[Sequence[int]] = None, tuned_tiles: bool = True):
         self.ctx, self.layers, self.n_mb, self.seed = ctx, list(layers), n_mb, seed
         L = len(self.layers)
+        # measured GEMM tile preferences for the braided blocks of these layers, where the package has some
+        # (they change the time of a block, never its results)
+        from . import tune
+        self.tuned = tune.apply_tuned(ctx, self.layers) if tuned_tiles else []
         self.descs = (B.LayerDesc * L)(*[B.make_desc(wl) for wl in self.layers])
         self.w_host, self.w_dev, self.g_dev = [], [], []
         w_arr, g_arr = (B.Weights * L)(), (B.WGrads * L)()

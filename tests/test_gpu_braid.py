@@ -131,6 +131,41 @@ def test_repeated_blocks_overlap_only_where_data_allows(ctx, name):
             assert torch.equal(u, v), f"{name}: run {rep} of overlapping blocks differs from the serialized order"
 
 
+def test_tile_hints_change_the_time_of_a_block_never_its_bits(ctx):
+    """stp_gemm_tile_hint: a preference for every GEMM shape of the stage's layers, a different tile each, applies
+    to the launches of concurrent streams only; the braided run still equals the serialized one bit for bit
+    (every element of a product is summed over K in the same order whatever the tile).  Bad tiles are statuses."""
+    from paper_2510_27257_amd import tune
+    layers, n_mb = STAGES["gpt_bf16_x2"]
+    stg = StageOnDevice(ctx, layers, n_mb, seed=2, tuned_tiles=False)
+    stg.load_inputs()
+    s0 = torch.cuda.current_stream()
+    ctx.gemm_tile_hints_clear()
+    run_sequence(ctx, stg, (s0, s0, s0))
+    serial = snapshot(stg)
+    streams = tuple(torch.cuda.Stream() for _ in range(3))
+    try:
+        for i, (M, N, K, at, bt) in enumerate(tune.layer_gemm_shapes(layers[0]).values()):
+            ctx.gemm_tile_hint(M, N, K, at, bt, *tune.TILES[i % len(tune.TILES)])
+        run_sequence(ctx, stg, streams)
+        for u, v in zip(serial, snapshot(stg)):
+            assert torch.equal(u, v)
+        for bad in [(64, 128), (128, 0), (192, 128), (256, 512)]:
+            with pytest.raises(stp.StpError) as e:
+                ctx.gemm_tile_hint(512, 512, 512, 0, 0, *bad)
+            assert e.value.status == 1
+        with pytest.raises(stp.StpError) as e:
+            ctx.gemm_tile_hint(512, 512, 512, 1, 0, 192, 256)      # the 192-row tile needs a k-contiguous A
+        assert e.value.status == 1
+        with pytest.raises(stp.StpError) as e:
+            ctx.gemm_tile_hint(0, 512, 512, 0, 0, 128, 128)
+        assert e.value.status == 2
+        ctx.gemm_tile_hint(512, 512, 512, 0, 0, 192, 256)
+        ctx.gemm_tile_hint(512, 512, 512, 0, 0, 0, 0)              # forgotten again
+    finally:
+        ctx.gemm_tile_hints_clear()
+
+
 def test_streams_may_change_between_steps_without_a_synchronisation(ctx):
     """A step joins the previous one whichever streams that one ran on: alternating between three streams, another
     set of three and a single stream from step to step, with no synchronisation in between, gives the serialized
