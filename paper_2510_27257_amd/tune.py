@@ -24,6 +24,7 @@ from . import binding as B
 from . import synth
 
 TILES: List[Tuple[int, int]] = [(256, 256), (128, 256), (256, 128), (128, 128)]
+WIDE_TILE = (192, 256)          # only with a k-contiguous A operand (a_trans = 0)
 TUNED_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tuned_tiles.json")
 
 Shape = Tuple[int, int, int, int, int]          # M, N, K, a_trans, b_trans
@@ -81,7 +82,7 @@ def descend(ctx: B.Context, shapes: Dict[str, Shape], run: Callable[[], float], 
         for shape, name in unique.items():
             M, N, K, at, bt = shape
             best = min(run(), run())
-            for tile in TILES:
+            for tile in TILES + ([WIDE_TILE] if not at else []):
                 if cur.get(shape) == tile:
                     continue
                 ctx.gemm_tile_hint(M, N, K, at, bt, *tile)
