@@ -247,7 +247,18 @@ extern "C" int stp_braid_step(stp_ctx *ctx, const stp_stage *st, const stp_op *o
   for (size_t i = 0; i < bsz; i++) ev_of[i] = -1;
   int ev_used = 0;
   rc = STP_OK;
-  ctx->concurrent = serial ? 0 : 1;
+  // The GEMMs choose their tile differently when other streams share the GPU: that is so when this step puts
+  // work on at least two different streams (a block of forward passes only, or of stored W units only, runs alone).
+  {
+    bool any_b = false, any_w = false;
+    for (int m = 0; m < MB; m++) { any_b = any_b || cur_b[m]; any_w = any_w || cur_w[m]; }
+    hipStream_t used[3]; int nu = 0;
+    auto use = [&](hipStream_t s) { for (int i = 0; i < nu; i++) if (used[i] == s) return; used[nu++] = s; };
+    if (f_mb >= 0) use(sF);
+    if (any_b) use(sB);
+    if (any_w) use(sW);
+    ctx->concurrent = nu >= 2 ? 1 : 0;
+  }
 
   for (size_t i = 0; i < n_ops && rc == STP_OK; i++) {
     const stp_op &o = ops[i];
