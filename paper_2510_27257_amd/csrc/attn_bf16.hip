@@ -567,16 +567,18 @@ int stp_launch_attn_fwd_bf16(stp_ctx *ctx, const stp_layer_desc *d, const void *
 // 6144, causal, and 16 heads, seq 1024, not causal: the estimate is within 6 - 8 % (rms) and its choice is the
 // fastest chunk length measured, or within 3 % of it.
 static const double kFixedUs[3] = {11.5, 12.0, 12.0}, kStepUs[3] = {1.75, 1.90, 2.65};
+// compute units a chunked attention launch counts on inside a braided block (measured: 96 gives the fastest block on
+// the 4-head and 10-head workloads, 0.3 - 2.5 % ahead of planning for all 256; 32 is 4 - 8 % behind)
+#define STP_ATTN_SHARED_CUS 96
 
 namespace {
 
 // Time of a launch whose workgroups, in the given order, each go to the compute unit that is free first
 // (256 of them, one workgroup each): fixed + per_step * steps per workgroup, every length `zcount` times.
-double plan_makespan(const std::vector<int> &lens, int zcount, double fixed, double per_step) {
+double plan_makespan(const std::vector<int> &lens, int zcount, double fixed, double per_step, int cus) {
   // many (head, sequence) pairs: 16 of them on a proportionally smaller machine give the same picture
   // and keep the planning time bounded
-  int cus = 256;
-  if (zcount > 16) { cus = std::max(1, 256 * 16 / zcount); zcount = 16; }
+  if (zcount > 16) { cus = std::max(1, cus * 16 / zcount); zcount = 16; }
   std::priority_queue<double, std::vector<double>, std::greater<double>> cu;
   for (int i = 0; i < cus; i++) cu.push(0.0);
   double end = 0.0;
@@ -590,7 +592,10 @@ double plan_makespan(const std::vector<int> &lens, int zcount, double fixed, dou
   return end;
 }
 
-void plan_make(int kind, int nblocks, const int *steps, int zcount, stp_attn_plan *plan) {
+// cus: the compute units the launch can count on (all 256 when it has the GPU to itself; fewer inside a braided
+// block, where longer chunks, i.e. fewer workgroups with their fixed cost, win because the other streams' kernels
+// fill what an uneven end of the launch leaves idle); min_chunk: never shorter than this
+void plan_make(int kind, int nblocks, const int *steps, int zcount, stp_attn_plan *plan, int cus = 256, int min_chunk = 0) {
   const double *fixed_us = kFixedUs, *step_us = kStepUs;
   int max_steps = 1;
   for (int x = 0; x < nblocks; x++) max_steps = std::max(max_steps, steps[x]);
@@ -601,13 +606,14 @@ void plan_make(int kind, int nblocks, const int *steps, int zcount, stp_attn_pla
   std::vector<int> lens;
   const int stride = std::max(1, (max_steps - lo) / 48);      // at most about 48 candidates
   for (int c = lo; c <= max_steps; c += stride) {
+    if (c < min_chunk) continue;
     lens.clear();
     for (int x = 0; x < nblocks; x++) {
       for (int k = 0; k < steps[x] / c; k++) lens.push_back(c);
       if (steps[x] % c) lens.push_back(steps[x] % c);
     }
     std::sort(lens.begin(), lens.end(), std::greater<int>());
-    const double t = plan_makespan(lens, zcount, fixed_us[kind], step_us[kind]);
+    const double t = plan_makespan(lens, zcount, fixed_us[kind], step_us[kind], cus);
     if (t < best_t * 0.995) { best_t = t; best_c = c; }      // a longer chunk has to win by half a percent
   }
   plan->chunk_steps = best_c;
@@ -647,9 +653,16 @@ stp_attn_plan *stp_attn_plan_slot(stp_ctx *ctx, const int key[8], bool *hit) {
 }
 
 const stp_attn_plan *stp_attn_plan_get(stp_ctx *ctx, int kind, const stp_layer_desc *d, int nblocks, const int *steps, int zcount) {
-  const int key[8] = {kind + 1, d->seq, d->causal, d->heads_local, stp_kv_heads(d), d->mbsz, d->head_dim, nblocks};
+  const bool shared = ctx && ctx->concurrent;
+  const int key[8] = {kind + 1 + (shared ? 16 : 0), d->seq, d->causal, d->heads_local, stp_kv_heads(d), d->mbsz, d->head_dim, nblocks};
   bool hit;
   stp_attn_plan *p = stp_attn_plan_slot(ctx, key, &hit);
-  if (!hit) plan_make(kind, nblocks, steps, zcount, p);
+  if (hit) return p;
+  if (!shared) { plan_make(kind, nblocks, steps, zcount, p); return p; }
+  // inside a block: plan for a share of the machine, never with shorter chunks than alone (the workspace is sized
+  // by the lone plan's chunk count)
+  stp_attn_plan alone;
+  plan_make(kind, nblocks, steps, zcount, &alone);
+  plan_make(kind, nblocks, steps, zcount, p, STP_ATTN_SHARED_CUS, alone.chunk_steps);
   return p;
 }

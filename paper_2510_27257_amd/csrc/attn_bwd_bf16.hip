@@ -653,7 +653,7 @@ inline const stp_attn_plan *dq_plan(stp_ctx *ctx, const stp_layer_desc *d) {
 // The merged work order of the fused launch: the (block, chunk) pairs of both kernels, sorted by the plan's
 // estimate of their time, longest first (ties keep dkv before dq and each kernel's own order).
 const stp_attn_plan *fused_plan(stp_ctx *ctx, const stp_layer_desc *d, const stp_attn_plan &pkv, const stp_attn_plan &pq) {
-  const int key[8] = {4, d->seq, d->causal, d->heads_local, stp_kv_heads(d), d->mbsz, d->head_dim, 0};
+  const int key[8] = {4 + (ctx && ctx->concurrent ? 16 : 0), d->seq, d->causal, d->heads_local, stp_kv_heads(d), d->mbsz, d->head_dim, 0};
   bool hit;
   stp_attn_plan *p = stp_attn_plan_slot(ctx, key, &hit);
   if (hit) return p;
