@@ -620,8 +620,8 @@ int launch_cfg(stp_ctx *ctx, const stp_gemm_args *a, const Epi &ep, hipStream_t 
 // The 192 x 256 tile exists for 6144-token activations: 32 tile rows x (N / 256) columns fill the 256 CUs in
 // whole rounds where the 256 x 256 tile leaves a quarter to a half of them idle; alone on the GPU it is the
 // fastest tile for seven of the layer's eight token-major shapes (3-12 %).  When other streams run beside
-// the GEMM (the braided block) those idle CUs are not idle, a GEMM spread over all of them only takes longer
-// per tile, and the braided step was measured 1-2 % slower with it: with `shared_gpu` it is not considered.
+// the GEMM (the braided block) those idle CUs are not idle and a GEMM spread over all of them only takes longer
+// per tile: with `shared_gpu` the choice is made differently (first lines of pick_tile).
 struct TileChoice { int bm, bn; };
 inline TileChoice pick_tile(long M, long N, long K, bool a_kc, bool b_kc, bool shared_gpu) {
   struct Cfg { int bm, bn, per_cu; double t_ktile[4]; };   // t_ktile index: 2 * a_kc + b_kc; 0 = layout not built
@@ -630,12 +630,23 @@ inline TileChoice pick_tile(long M, long N, long K, bool a_kc, bool b_kc, bool s
                               {128, 256, 1, {0.432, 0.467, 0.428, 0.492}},
                               {256, 128, 1, {0.449, 0.451, 0.517, 0.496}},
                               {128, 128, 2, {0.240, 0.278, 0.251, 0.285}}};
+  if (shared_gpu) {
+    // Beside other streams' kernels the rounds of the estimate below mean nothing (what a round leaves idle the
+    // other streams use), and what counts is the work a tile costs the compute units: the biggest tile, which
+    // moves the fewest operand bytes per flop, as long as the launch still has enough workgroups to make progress
+    // on its share of the machine.  Measured on nine workloads against the estimate below without the 192-row
+    // tile: never more than 0.3 % behind, 1.5 - 7 % ahead on the shapes of the larger models.  A measured
+    // preference (stp_gemm_tile_hint) overrides it shape by shape.
+    const int opts[4][2] = {{256, 256}, {128, 256}, {256, 128}, {128, 128}};
+    for (auto &o : opts)
+      if (((M + o[0] - 1) / o[0]) * ((N + o[1] - 1) / o[1]) >= 96) return TileChoice{o[0], o[1]};
+    return TileChoice{128, 128};
+  }
   const double kt = (double)(K / DK);
   TileChoice best{256, 256};
   double best_t = 1e30;
   for (const Cfg &c : cfgs) {
     if (c.t_ktile[2 * a_kc + b_kc] == 0.0) continue;
-    if (c.bm == 192 && shared_gpu) continue;
     const long tiles = ((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
     const long slots = 256L * c.per_cu;
     const long full = tiles / slots, rem = tiles % slots;
