@@ -409,7 +409,10 @@ def stage_bench(ctx, args, torch, stp, synth):
         "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": ms_braided, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"stage {args.stage}: {L} layers x {n_mb} microbatches, sequence of {len(steps)} braided blocks",
-                   "sequence": seq_name, "peak_layer_stashes_in_flight": peak, "flops_per_step": flops},
+                   "sequence": seq_name, "peak_layer_stashes_in_flight": peak, "flops_per_step": flops,
+                   "gemm_tile_hints": (f"{stg.n_tile_hints} measured tile preferences of paper_2510_27257_amd/tuned_tiles.json, "
+                                       f"objective '{stg.tuned_objective}' (a stage's sequence of steps)"
+                                       if stg.tuned else "none (the library's own tile choice)")},
         "braid": {"makespan_ms": ms_braided, "serialized_ms": ms_serial, "sum_isolated_ms": sum_iso,
                   "makespan_over_sum_isolated": ms_braided / sum_iso},
         "offload": offload, "schedule": sched}))
@@ -582,7 +585,8 @@ def main():
         "config": {"workload": f"{wl.name}: hidden {h}, {wl.heads_local} local heads x {wl.head_dim}, ffn shard {f}, "
                                f"seq {T}, microbatch 1, tp {wl.tp}; step = F(mb1) braided with B+W(mb0), 1 layer",
                    "flops_per_step": total_flops,
-                   "gemm_tile_hints": ("measured tile preferences of paper_2510_27257_amd/tuned_tiles.json for the block's GEMMs"
+                   "gemm_tile_hints": (f"{stg.n_tile_hints} measured tile preferences of paper_2510_27257_amd/tuned_tiles.json, "
+                                       f"objective '{stg.tuned_objective}' (this block issued back to back)"
                                        if stg.tuned else "none (the library's own tile choice)")},
         "mfma_util_frac_of_bf16_peak": total_flops / (ms_braided * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
         "sustained_shader_clock_mhz": sustained_mhz,

@@ -23,13 +23,22 @@ def _to_dev(x, dtype: str) -> torch.Tensor:
 
 class StageOnDevice:
     def __init__(self, ctx: B.Context, layers: Sequence[synth.Workload], n_mb: int, seed: int = 0,
-                 chain_break: Optional[Sequence[int]] = None, tuned_tiles: bool = True):
+                 chain_break: Optional[Sequence[int]] = None, tuned_tiles=True):
         self.ctx, self.layers, self.n_mb, self.seed = ctx, list(layers), n_mb, seed
         L = len(self.layers)
-        # measured GEMM tile preferences for the braided blocks of these layers, where the package has some
-        # (they change the time of a block, never its results)
+        # measured GEMM tile preferences for these layers' GEMMs beside other streams, where the package has some
+        # (they change the time of a step, never its results).  tuned_tiles: False leaves the context's hints as
+        # they are; "block" / "stage" names the objective they were measured for; True takes "block" for a
+        # single layer (its braided block issued back to back) and "stage" for several (a stage's sequence of
+        # steps).  A context holds the preferences of the stage built last.
         from . import tune
-        self.tuned = tune.apply_tuned(ctx, self.layers) if tuned_tiles else []
+        self.tuned, self.tuned_objective, self.n_tile_hints = [], None, 0
+        if tuned_tiles:
+            self.tuned_objective = tuned_tiles if isinstance(tuned_tiles, str) else ("block" if L == 1 else "stage")
+            ctx.gemm_tile_hints_clear()
+            self.tuned = tune.apply_tuned(ctx, self.layers, objective=self.tuned_objective)
+            table = tune.load_hints(objective=self.tuned_objective)
+            self.n_tile_hints = sum(len(table[n]) for n in self.tuned)
         self.descs = (B.LayerDesc * L)(*[B.make_desc(wl) for wl in self.layers])
         self.w_host, self.w_dev, self.g_dev = [], [], []
         w_arr, g_arr = (B.Weights * L)(), (B.WGrads * L)()

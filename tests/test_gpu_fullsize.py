@@ -41,6 +41,7 @@ def test_full_size_braided_block_matches_oracle(name):
     tol = TOL[wl.dtype]
     ctx = stp.Context(0)
     stg = StageOnDevice(ctx, [wl], n_mb=2, seed=0)
+    assert stg.tuned_objective == "block"         # the launch configuration the benchmark times: its tile preferences
     stg.load_inputs()
     sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     ctx.braid_reset()

@@ -19,6 +19,7 @@ def test_four_layer_stage_sequence_matches_oracle():
     L, n_mb = 4, 8
     ctx = stp.Context(0)
     stg = StageOnDevice(ctx, [wl] * L, n_mb, seed=0)
+    assert stg.tuned_objective == "stage" and stg.tuned == [wl.name]      # the table measured on a stage's sequence
     stg.load_inputs()
     sF, sB, sW = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     ctx.braid_reset()

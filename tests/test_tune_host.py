@@ -51,17 +51,41 @@ def test_descent_finds_the_planted_preferences_and_nothing_else():
     assert ctx.hints == want                      # what stays in the context is what is reported
 
 
-def test_stored_table_is_well_formed_and_applies(tmp_path):
-    table = tune.load_hints()
-    for name, hints in table.items():
-        assert name in synth.WORKLOADS
-        shapes = set(tune.layer_gemm_shapes(synth.WORKLOADS[name]).values())
-        for key, tile in hints.items():
-            assert tuple(int(v) for v in key.split(",")) in shapes, (name, key)     # a GEMM this workload really runs
-            assert tile in ("256x256", "128x256", "256x128", "128x128") or (tile == "192x256" and key.split(",")[3] == "0")
-    p = tmp_path / "t.json"
-    p.write_text(json.dumps({"workloads": {"gpt7b_tp8": {"8,16,24,1,0": "128x256"}}}))
+def test_descent_drops_a_set_that_does_not_beat_the_library_choice_in_the_end():
     ctx = FakeCtx()
-    assert tune.apply_tuned(ctx, ["gpt7b_tp8", "vit"], str(p)) == ["gpt7b_tp8"]
+    shapes = tune.layer_gemm_shapes(synth.WORKLOADS["tiny"])
+    calls = {"n": 0}
+
+    def run():          # drift: every measurement a little faster than the one before, whatever the tiles are
+        calls["n"] += 1
+        return 1.0 * 0.999 ** calls["n"]
+
+    hints, base, final = tune.descend(ctx, shapes, run, passes=1)
+    assert hints == {} and ctx.hints == {} and base == final
+
+
+def test_stored_tables_are_well_formed_and_apply(tmp_path):
+    for objective in ("block", "stage"):
+        table = tune.load_hints(objective=objective)
+        assert table, objective
+        for name, hints in table.items():
+            assert name in synth.WORKLOADS
+            shapes = set(tune.layer_gemm_shapes(synth.WORKLOADS[name]).values())
+            for key, tile in hints.items():
+                assert tuple(int(v) for v in key.split(",")) in shapes, (name, key)     # a GEMM this workload really runs
+                assert tile in ("256x256", "128x256", "256x128", "128x128") or (tile == "192x256" and key.split(",")[3] == "0")
+    p = tmp_path / "t.json"
+    p.write_text(json.dumps({"workloads": {"gpt7b_tp8": {"8,16,24,1,0": "128x256"}},
+                             "stage_workloads": {"gpt7b_tp8": {}, "vit": {"8,16,24,0,0": "256x128"}}}))
+    ctx = FakeCtx()
+    assert tune.apply_tuned(ctx, ["gpt7b_tp8", "vit", "gpt7b_tp8"], str(p)) == ["gpt7b_tp8"]
     assert ctx.hints == {(8, 16, 24, 1, 0): (128, 256)}
+    ctx = FakeCtx()             # the other objective has a table of its own; an empty entry counts as an entry
+    assert tune.apply_tuned(ctx, ["gpt7b_tp8", "vit"], str(p), objective="stage") == ["gpt7b_tp8", "vit"]
+    assert ctx.hints == {(8, 16, 24, 0, 0): (256, 128)}
     assert tune.load_hints(str(tmp_path / "absent.json")) == {}
+    try:
+        tune.load_hints(objective="layer")
+        assert False
+    except ValueError:
+        pass
