@@ -410,9 +410,11 @@ def stage_bench(ctx, args, torch, stp, synth):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"stage {args.stage}: {L} layers x {n_mb} microbatches, sequence of {len(steps)} braided blocks",
                    "sequence": seq_name, "peak_layer_stashes_in_flight": peak, "flops_per_step": flops,
-                   "gemm_tile_hints": (f"{stg.n_tile_hints} measured tile preferences of paper_2510_27257_amd/tuned_tiles.json, "
-                                       f"objective '{stg.tuned_objective}' (a stage's sequence of steps)"
-                                       if stg.tuned else "none (the library's own tile choice)")},
+                   "gemm_tile_hints": ((f"{stg.n_tile_hints} measured tile preferences of paper_2510_27257_amd/tuned_tiles.json, "
+                                        f"objective '{stg.tuned_objective}' (a stage's sequence of steps)") if stg.n_tile_hints
+                                       else ("none: on a stage's sequence of steps the library's own tile choice measured best for these layers "
+                                             "(paper_2510_27257_amd/tuned_tiles.json)") if stg.tuned
+                                       else "none (the library's own tile choice)")},
         "braid": {"makespan_ms": ms_braided, "serialized_ms": ms_serial, "sum_isolated_ms": sum_iso,
                   "makespan_over_sum_isolated": ms_braided / sum_iso},
         "offload": offload, "schedule": sched}))
