@@ -241,6 +241,45 @@ def hbm_leg(ctx, wl, torch, stp, reps=200):
     return out
 
 
+def attention_leg(ctx, wl, torch, stp, reps=200):
+    """The attention core alone at the workload's shape (Attention(.) of Eq. 1 and its backward pass): forward call
+    (main kernel + combine) and backward call (row dot, dK/dV and dQ kernels, combines), HIP events on the launching
+    stream.  Rates count the algorithmic products only: 2 per unmasked (query, key) pair and head dimension forwards
+    (S and PV), 4 backwards (dV, dP, dQ, dK); the backward kernels execute 7 for those 4 plus the forward's S."""
+    T, n, d = wl.seq * 1, wl.heads_local, wl.head_dim
+    desc = stp.make_desc(wl)
+    bf = torch.bfloat16
+    g = torch.Generator(device="cuda").manual_seed(11)
+    qkv = (torch.randn(T, wl.qkv_local, device="cuda", generator=g) * 0.5).to(bf)
+    dout = torch.randn(T, n * d, device="cuda", generator=g).to(bf)
+    out = torch.empty(T, n * d, device="cuda", dtype=bf)
+    lse = torch.empty(n * T, device="cuda", dtype=torch.float32)
+    delta = torch.empty(n * T, device="cuda", dtype=torch.float32)
+    dqkv = torch.empty_like(qkv)
+    nkv = getattr(wl, "kv_heads", 0) or n
+    pairs = T * (T + 1) / 2 if desc.causal else float(T) * T
+    fwd_flops = 4.0 * pairs * d * n
+
+    def timed(fn):
+        for _ in range(max(10, reps // 10)):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms_f = timed(lambda: ctx.attention_forward(desc, qkv, out, lse))
+    ms_b = timed(lambda: ctx.attention_backward(desc, qkv, out, lse, dout, delta, dqkv))
+    return {"forward_ms": ms_f, "forward_tflops": fwd_flops / (ms_f * 1e-3) / 1e12,
+            "backward_ms": ms_b, "backward_tflops_algorithmic": 2.0 * fwd_flops / (ms_b * 1e-3) / 1e12,
+            "shape": f"{n} query heads x {d}, {nkv} key/value heads, seq {T}, causal {int(desc.causal)}, bf16",
+            "how": f"each call alone on the GPU, {reps} in a row between HIP events, random operands"}
+
+
 def cpu_baseline(wl, w_host, fl, synth, reps=1):
     """The fp64 oracle on the host cores: the F, B and W units of one layer-microbatch of `wl`, timed apart."""
     import numpy as np
@@ -614,6 +653,7 @@ def main():
                      "algorithmic_bytes_per_launch": sum(2 * (M * K + K * N + M * N) for (M, N, K) in gemm_shapes(wl)) / 4,
                      "context": gemm_context(ctx, wl, max(10, args.steps), torch, stp)},
         "hbm_kernels": hbm,
+        "attention_kernels": attention_leg(ctx, wl, torch, stp) if wl.dtype == "bf16" else None,
     }
 
     if not args.no_cpu_baseline:
